@@ -1,0 +1,313 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, independent of the oracle's own code.
+
+Each test is chosen so that a plausible slip in oracle/lvx_oracle.py (dropped term, sign, index,
+transposed operand) fails it.  Nothing here touches the HIP path.
+"""
+import math
+
+import numpy as np
+import pytest
+from scipy.special import erf
+
+from oracle import lvx_oracle as O
+
+rng = np.random.default_rng(1234)
+
+
+# ---------------------------------------------------------------- attention
+def brute_attention(q, k, v, scale):
+    """Pure-Python definition: loops over query, head, key, channel."""
+    nq, H, D = q.shape
+    nk = k.shape[0]
+    out = np.zeros((nq, H, D))
+    for r in range(nq):
+        for h in range(H):
+            s = [scale * sum(q[r, h, c] * k[m, h, c] for c in range(D)) for m in range(nk)]
+            mx = max(s)
+            e = [math.exp(t - mx) for t in s]
+            z = sum(e)
+            for c in range(D):
+                out[r, h, c] = sum(e[m] * v[m, h, c] for m in range(nk)) / z
+    return out
+
+
+def test_attention_brute_force_tiny():
+    q = rng.standard_normal((5, 2, 8))
+    k = rng.standard_normal((11, 2, 8))
+    v = rng.standard_normal((11, 2, 8))
+    np.testing.assert_allclose(O.attention(q, k, v, 0.37), brute_attention(q, k, v, 0.37), rtol=1e-12, atol=1e-13)
+
+
+def test_attention_config1_shape_vs_loops():
+    # 2 heads, D=64, 48 queries x 168 keys; loop reference on a row subset keeps it to seconds
+    q = rng.standard_normal((48, 2, 64))
+    k = rng.standard_normal((168, 2, 64))
+    v = rng.standard_normal((168, 2, 64))
+    rows = [0, 17, 47]
+    ref = brute_attention(q[rows], k, v, 0.125)
+    np.testing.assert_allclose(O.attention(q, k, v, 0.125)[rows], ref, rtol=1e-11, atol=1e-12)
+
+
+def test_attention_rows_sum_to_one_and_special_cases():
+    q = rng.standard_normal((7, 3, 16))
+    k = rng.standard_normal((19, 3, 16))
+    v = rng.standard_normal((19, 3, 16))
+    out, p = O.attention(q, k, v, 0.25, return_probs=True)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=0, atol=1e-14)
+    assert (p >= 0).all()
+    # one visible key -> its V exactly
+    one = O.attention(q, k[:1], v[:1], 0.25)
+    np.testing.assert_array_equal(one, np.broadcast_to(v[:1].transpose(1, 0, 2).reshape(1, 3, 16), one.shape))
+    # all V rows equal -> that row
+    vc = np.broadcast_to(v[3], v.shape)
+    np.testing.assert_allclose(O.attention(q, k, vc, 0.25), np.broadcast_to(v[3], (7, 3, 16)), atol=1e-14)
+    # key order does not matter when nothing is masked
+    perm = rng.permutation(19)
+    np.testing.assert_allclose(O.attention(q, k[perm], v[perm], 0.25), out, atol=1e-13)
+    # heads are independent: changing head 1's keys leaves head 0 untouched
+    k2 = k.copy(); k2[:, 1] += 1.0
+    np.testing.assert_array_equal(O.attention(q, k2, v, 0.25)[:, 0], out[:, 0])
+    # scale really multiplies the logits: scale=0 -> uniform average of V
+    np.testing.assert_allclose(O.attention(q, k, v, 0.0), np.broadcast_to(v.mean(0), (7, 3, 16)), atol=1e-14)
+    # shift invariance of softmax survives huge logits (max-subtraction)
+    big = O.attention(q * 1e3, k, v, 1.0)
+    assert np.isfinite(big).all()
+
+
+# ---------------------------------------------------------------- rolling cache protocol
+@pytest.mark.parametrize("window", [1, 2, 4])
+def test_cache_protocol_matches_closed_form_100_steps(window):
+    """Alg. 3: pop the oldest when L entries are held, then append => after step i the cache holds
+    chunks max(0, i-L+1)..i, evicts chunk i-L at step i (i >= L), and a forward at step i sees
+    chunks max(0, i-L)..i-1 plus itself."""
+    c = O.RollingKVCache(window)
+    c.set_sink(np.full((2, 1, 1), -7.0), np.full((2, 1, 1), -9.0))
+    for i in range(100):
+        k = np.full((3, 1, 1), float(i))
+        kk, vv = c.visible(k, k + 0.5)
+        ids = sorted(set(kk[2:, 0, 0].astype(int).tolist()))
+        assert ids == list(range(max(0, i - window), i + 1))
+        assert kk.shape[0] == 2 + 3 * (min(i, window) + 1)
+        # sink is first and never changes
+        assert (kk[:2] == -7.0).all() and (vv[:2] == -9.0).all()
+        n_ev = len(c.evicted)
+        c.append(i, k, k + 0.5)
+        assert c.chunk_ids() == list(range(max(0, i - window + 1), i + 1))
+        if i >= window:
+            assert c.evicted[n_ev:] == [i - window]
+        else:
+            assert len(c.evicted) == n_ev == 0
+
+
+def test_block_causal_mask_rule():
+    m = O.block_causal_mask(n_chunks=7, chunk_tokens=3, sink_tokens=2, window=4)
+    for r in range(21):
+        i = r // 3
+        for col in range(2 + 21):
+            if col < 2:
+                want = True
+            else:
+                j = (col - 2) // 3
+                want = (i - 4 <= j <= i)
+            assert m[r, col] == want
+
+
+def test_streaming_attention_equals_block_causal_full_sequence():
+    """Chunk-vs-cache attention at step i == rows of block i of ONE masked attention over
+    [sink, c0..c_{n-1}] (mask rule Sec. 3.2 + window of Eq. 1), including warm-up steps."""
+    H, D, nc, ns, W, n = 2, 8, 5, 3, 2, 7
+    ks, vs = rng.standard_normal((ns, H, D)), rng.standard_normal((ns, H, D))
+    q = rng.standard_normal((n * nc, H, D))
+    k = rng.standard_normal((n * nc, H, D))
+    v = rng.standard_normal((n * nc, H, D))
+    mask = O.block_causal_mask(n, nc, ns, W)
+    full = O.attention(q, np.concatenate([ks, k]), np.concatenate([vs, v]), 0.3, mask=mask)
+    cache = O.RollingKVCache(W)
+    cache.set_sink(ks, vs)
+    for i in range(n):
+        sl = slice(i * nc, (i + 1) * nc)
+        o = O.chunk_attention_step(cache, q[sl], k[sl], v[sl], 0.3, i)
+        np.testing.assert_allclose(o, full[sl], rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- RoPE
+def complex_rope_1d(x, pos, theta):
+    """Textbook 1-D RoPE written with complex numbers: z_k -> z_k * exp(i pos theta^(-2k/d))."""
+    d = x.shape[-1]
+    z = x[..., 0::2] + 1j * x[..., 1::2]
+    w = np.exp(1j * pos[:, None, None] * theta ** (-2.0 * np.arange(d // 2) / d))
+    z = z * w
+    out = np.empty_like(x)
+    out[..., 0::2], out[..., 1::2] = z.real, z.imag
+    return out
+
+
+def test_rope_reduces_to_textbook_per_axis():
+    fh, fw = 3, 4
+    x = rng.standard_normal((2 * fh * fw, 2, 128))
+    y = O.rope3d(x, 5, fh, fw)
+    t, r, c = O.token_positions(x.shape[0], 5, fh, fw)
+    # positions: frame-major, then row, then column
+    assert t.tolist() == [5] * 12 + [6] * 12 and r[:12].tolist() == [0] * 4 + [1] * 4 + [2] * 4 and c[:5].tolist() == [0, 1, 2, 3, 0]
+    np.testing.assert_allclose(y[..., :44], complex_rope_1d(x[..., :44], t.astype(float), 1e4), atol=1e-12)
+    np.testing.assert_allclose(y[..., 44:86], complex_rope_1d(x[..., 44:86], r.astype(float), 1e4), atol=1e-12)
+    np.testing.assert_allclose(y[..., 86:], complex_rope_1d(x[..., 86:], c.astype(float), 1e4), atol=1e-12)
+
+
+def test_rope_identity_norm_relative_and_composition():
+    fh, fw = 3, 4
+    n = fh * fw
+    x = rng.standard_normal((n, 2, 128))
+    y = O.rope3d(x, 0, fh, fw)
+    np.testing.assert_array_equal(y[0], x[0])                      # position (0,0,0) is the identity
+    pair = lambda a: a[..., 0::2] ** 2 + a[..., 1::2] ** 2
+    np.testing.assert_allclose(pair(y), pair(x), rtol=1e-12)       # each pair keeps its norm
+    # scores depend only on position differences: shift every t by the same amount
+    q, k = rng.standard_normal((n, 2, 128)), rng.standard_normal((n, 2, 128))
+    s0 = np.einsum("qhd,khd->hqk", O.rope3d(q, 3, fh, fw), O.rope3d(k, 1, fh, fw))
+    s1 = np.einsum("qhd,khd->hqk", O.rope3d(q, 40003, fh, fw), O.rope3d(k, 40001, fh, fw))
+    np.testing.assert_allclose(s0, s1, rtol=0, atol=1e-8)          # holds at the 4e4 indices of a 10 000 s rollout
+    # rotations compose additively in t (on the first frame where y = x = 0 for token 0)
+    one = x[:1]
+    a = O.rope3d(O.rope3d(one, 7, fh, fw), 5, fh, fw)
+    np.testing.assert_allclose(a, O.rope3d(one, 12, fh, fw), atol=1e-12)
+    # rotation direction: pair (1,0) at angle pos*1 (k=0) goes to (cos, sin)
+    e = np.zeros((1, 1, 128)); e[0, 0, 0] = 1.0
+    r = O.rope3d(e, 2, fh, fw)
+    np.testing.assert_allclose(r[0, 0, :2], [math.cos(2.0), math.sin(2.0)], atol=1e-15)
+    # second pair of the t axis uses theta^(-2/44)
+    e = np.zeros((1, 1, 128)); e[0, 0, 2] = 1.0
+    r = O.rope3d(e, 2, fh, fw)
+    ang = 2.0 * 1e4 ** (-2.0 / 44)
+    np.testing.assert_allclose(r[0, 0, 2:4], [math.cos(ang), math.sin(ang)], atol=1e-15)
+
+
+# ---------------------------------------------------------------- norms, GELU, linear
+def test_rmsnorm_layernorm_closed_forms():
+    x = rng.standard_normal((6, 64)) * 3 + 1
+    y = O.rmsnorm(x, np.ones(64), eps=0.0)
+    np.testing.assert_allclose(np.sqrt((y ** 2).mean(-1)), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(O.rmsnorm(17.0 * x, np.ones(64), eps=0.0), y, rtol=1e-12)
+    g = rng.standard_normal(64)
+    np.testing.assert_allclose(O.rmsnorm(x, g, 1e-6), x / np.sqrt((x * x).mean(-1, keepdims=True) + 1e-6) * g, rtol=1e-14)
+    # RMSNorm does not subtract the mean
+    assert abs(O.rmsnorm(x, np.ones(64)).mean()) > 0.05
+    z = O.layernorm(x, eps=0.0)
+    np.testing.assert_allclose(z.mean(-1), 0.0, atol=1e-14)
+    np.testing.assert_allclose(z.var(-1), 1.0, rtol=1e-12)
+    np.testing.assert_allclose(O.layernorm(x + 5.0, eps=0.0), z, atol=1e-12)
+    np.testing.assert_allclose(O.modulate(x, 0.5, 2.0, 0.0), z * 3.0 + 0.5, rtol=1e-13)
+    # eps sits inside the square root, added to the mean square / variance
+    c = np.full((1, 4), 2.0)
+    np.testing.assert_allclose(O.rmsnorm(c, np.ones(4), eps=5.0), 2.0 / 3.0, rtol=1e-15)
+    np.testing.assert_allclose(O.layernorm(np.array([[1.0, -1.0]]), eps=3.0), [[0.5, -0.5]], rtol=1e-15)
+
+
+def test_gelu_tanh():
+    x = np.linspace(-6, 6, 2001)
+    g = O.gelu_tanh(x)
+    assert O.gelu_tanh(np.array(0.0)) == 0.0
+    np.testing.assert_allclose(g - O.gelu_tanh(-x), x, atol=1e-14)
+    np.testing.assert_allclose(O.gelu_tanh(np.array([30.0, -30.0])), [30.0, 0.0], atol=1e-12)
+    assert np.abs(g - 0.5 * x * (1 + erf(x / math.sqrt(2)))).max() < 1e-3
+    np.testing.assert_allclose(O.gelu_tanh(np.array(1.0)), 0.5 * (1 + math.tanh(math.sqrt(2 / math.pi) * 1.044715)), rtol=1e-15)
+
+
+def test_linear_is_x_times_w_transposed():
+    x = rng.standard_normal((4, 6))
+    W = rng.standard_normal((5, 6))               # [out, in], non-square so a transposed operand cannot pass
+    ref = np.array([[sum(x[n, i] * W[o, i] for i in range(6)) for o in range(5)] for n in range(4)])
+    np.testing.assert_allclose(O.linear(x, W), ref, rtol=1e-13)
+    np.testing.assert_array_equal(O.linear(x, np.eye(6)), x)
+
+
+# ---------------------------------------------------------------- block / stage
+def tiny_cfg():
+    return O.StageConfig(n_heads=2, head_dim=8, frame_h=2, frame_w=3, chunk_frames=2, window=2, sink_frames=1,
+                         rope_axes=(4, 2, 2))
+
+
+def tiny_weights(cfg, ffn=24, std=0.3):
+    d = cfg.d_model
+    shapes = {"W_qkv": (3 * d, d), "W_o": (d, d), "Wc_q": (d, d), "Wc_k": (d, d), "Wc_v": (d, d), "Wc_o": (d, d),
+              "W_1": (ffn, d), "W_2": (d, ffn)}
+    w = {k: rng.standard_normal(s) * std for k, s in shapes.items()}
+    for g in ("g_q", "g_k", "gc_q", "gc_k"):
+        w[g] = 1.0 + 0.1 * rng.standard_normal(d)
+    return w
+
+
+def fresh_cache(cfg, seed):
+    r = np.random.default_rng(seed)
+    c = O.RollingKVCache(cfg.window)
+    c.set_sink(r.standard_normal((cfg.frame_tokens, cfg.n_heads, cfg.head_dim)),
+               r.standard_normal((cfg.frame_tokens, cfg.n_heads, cfg.head_dim)))
+    return c
+
+
+def test_block_identity_cases_and_mod6_default():
+    cfg = tiny_cfg()
+    d = cfg.d_model
+    x = rng.standard_normal((cfg.chunk_tokens, d))
+    ctx = rng.standard_normal((5, d))
+    w = tiny_weights(cfg)
+    # zero output projections -> the block passes x through
+    w0 = dict(w, W_o=np.zeros((d, d)), Wc_o=np.zeros((d, d)), W_2=np.zeros_like(w["W_2"]))
+    np.testing.assert_array_equal(O.dit_block(x, w0, fresh_cache(cfg, 1), ctx, None, 0, 1, cfg), x)
+    # zero gates remove the self-attention and FFN branches; what is left is x + cross-attention(x)
+    m = np.zeros((6, d))
+    y = O.dit_block(x, w, fresh_cache(cfg, 1), ctx, m, 0, 1, cfg)
+    np.testing.assert_allclose(y, x + O.cross_attention(x, ctx, w, cfg), rtol=1e-13)
+    # mod6=None is shift=scale=0, gate=1
+    m = np.zeros((6, d)); m[2] = 1.0; m[5] = 1.0
+    np.testing.assert_array_equal(O.dit_block(x, w, fresh_cache(cfg, 1), ctx, None, 0, 1, cfg),
+                                  O.dit_block(x, w, fresh_cache(cfg, 1), ctx, m, 0, 1, cfg))
+    # the block appends exactly one entry: the K/V of this forward (post-norm, post-RoPE K; raw V)
+    c = fresh_cache(cfg, 1)
+    O.dit_block(x, w, c, ctx, None, 0, 1, cfg)
+    q, k, v = O.qkv_for_cache(O.modulate(x, 0.0, 0.0), w, cfg, 1)
+    assert c.chunk_ids() == [0]
+    np.testing.assert_array_equal(c.blocks[0][1], k)
+    np.testing.assert_array_equal(c.blocks[0][2], v)
+
+
+def test_euler_step_sign_and_dt_zero():
+    cfg = tiny_cfg()
+    d = cfg.d_model
+    x = rng.standard_normal((cfg.chunk_tokens, d))
+    ctx = rng.standard_normal((5, d))
+    layers = [tiny_weights(cfg), tiny_weights(cfg)]
+    caches = [fresh_cache(cfg, 1), fresh_cache(cfg, 2)]
+    np.testing.assert_array_equal(O.denoise_stage(x, layers, caches, ctx, None, 0.0, 0, 1, cfg), x)
+    caches = [fresh_cache(cfg, 1), fresh_cache(cfg, 2)]
+    h = x
+    for l in range(2):
+        h = O.dit_block(h, layers[l], fresh_cache(cfg, l + 1), ctx, None, 0, 1, cfg)
+    np.testing.assert_allclose(O.denoise_stage(x, layers, caches, ctx, None, -0.25, 0, 1, cfg), x - 0.25 * h, rtol=1e-14)
+    # flow matching (Sec. 2.1): x_t = (1-s) x0 + s xT, v = xT - x0.  T Euler steps with dt = -1/T and the exact
+    # velocity carry xT to x0 -- fixes the sign convention of the update.
+    x0, xT, T = rng.standard_normal(9), rng.standard_normal(9), 4
+    z = xT.copy()
+    for _ in range(T):
+        z = z + (xT - x0) * (-1.0 / T)
+    np.testing.assert_allclose(z, x0, atol=1e-14)
+
+
+def test_streaming_stage_equals_full_sequence_stack():
+    """Two-layer stack streamed chunk by chunk through per-layer rolling caches == the same stack run once over
+    the whole sequence with the block-causal windowed mask (state of block j at layer l depends only on blocks
+    j-w..j of layer l-1).  Covers warm-up (steps < w) and eviction (steps > w)."""
+    cfg = tiny_cfg()
+    d = cfg.d_model
+    n_chunks = 6
+    layers = [tiny_weights(cfg), tiny_weights(cfg)]
+    xs = [rng.standard_normal((cfg.chunk_tokens, d)) for _ in range(n_chunks)]
+    ctxs = [rng.standard_normal((5, d)) for _ in range(n_chunks)]
+    mod6 = [rng.standard_normal((6, d)) * 0.3 + np.array([0, 0, 1, 0, 0, 1])[:, None] for _ in layers]
+    caches = [fresh_cache(cfg, 10 + l) for l in range(2)]
+    sinks = [fresh_cache(cfg, 10 + l).sink for l in range(2)]
+    t0 = lambda i: 1 + cfg.chunk_frames * i
+    full = O.full_sequence_stage(xs, layers, sinks, ctxs, mod6, -0.25, t0, cfg)
+    for i in range(n_chunks):
+        y = O.denoise_stage(xs[i], layers, caches, ctxs[i], mod6, -0.25, i, t0(i), cfg)
+        np.testing.assert_allclose(y, full[i], rtol=1e-10, atol=1e-11)
