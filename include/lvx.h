@@ -1,0 +1,219 @@
+/*
+ * lvx — C ABI of the MI355X (gfx950) hot path of one denoising stage of a streaming causal video DiT
+ * (Live Avatar, arXiv 2512.04677).
+ *
+ * Conventions (all entry points):
+ *   - Plain C, no exceptions.  Every call returns lvx_status_t; on failure lvx_last_error() gives a
+ *     thread-local message.  Argument checks happen on the host before anything is enqueued.
+ *   - "dev" pointers are device (HBM) addresses owned by the caller; "host" pointers are ordinary host
+ *     memory.  The library never allocates or frees device memory and never synchronises: all work is
+ *     enqueued on the given HIP stream (lvx_stream_t is a hipStream_t; NULL = the default stream).
+ *   - Activations are bf16, row-major, token-major: element (token n, channel c) at base[n*ld + c],
+ *     channel c = head*head_dim + dim.  `ld` is a row stride in ELEMENTS.  Device pointers must be
+ *     16-byte aligned and ld a multiple of 8.
+ *   - Linear weights are bf16, row-major [out_features][in_features], no bias.
+ *   - Gains and modulation vectors are fp32.
+ *   - The KV cache's internal layout is private to the library (K head-major, V stored transposed in
+ *     64-key tiles so that both are direct MFMA operands); lvx_kvcache_gather reads it back in the
+ *     token-major layout for checks and for off-loading.
+ */
+#ifndef LVX_H
+#define LVX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LVX_OK = 0,
+    LVX_ERR_INVALID_ARG = 1, /* null / misaligned pointer, negative size, bad enum */
+    LVX_ERR_SHAPE = 2,       /* a size the kernels do not support or that does not match the descriptor */
+    LVX_ERR_STATE = 3,       /* call order violated (chunk index out of sequence, sink not set, ...) */
+    LVX_ERR_UNSUPPORTED = 4, /* valid request outside what is built (e.g. head_dim not 64/128) */
+    LVX_ERR_HIP = 5          /* a HIP runtime call failed; message holds hipGetErrorString */
+} lvx_status_t;
+
+typedef void *lvx_stream_t; /* hipStream_t */
+
+const char *lvx_last_error(void);
+/* Library version string, e.g. "lvx 0.1 gfx950". */
+const char *lvx_version(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Rolling KV cache (paper Eq. 1; Alg. 3 / Alg. 4 cache lines; Sec. 3.3 "History Corrupt" and sink frame).
+ *
+ * One cache = one denoising timestep's state for all layers: per layer a sink segment of
+ * sink_frames*frame_h*frame_w keys that is never evicted, followed by window_chunks+1 chunk slots of
+ * chunk_frames*frame_h*frame_w keys each.  The forward of chunk i must see its own K/V (blocks attend
+ * to themselves in full, Sec. 3.2) and the `window_chunks` chunks before it, so the chunk's K/V are
+ * written first, into slot i mod (window_chunks+1), overwriting chunk i-(window_chunks+1): that is the
+ * "pop oldest, append" of Alg. 3 with the append moved before the attention.  Attention is invariant to
+ * key order (no mask, K carries its rotary phase), so the visible keys are always the contiguous prefix
+ *   [0, sink_keys + min(i+1, window_chunks+1)*chunk_keys).
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+    int32_t n_layers;      /* 40 */
+    int32_t n_heads;       /* 40 */
+    int32_t head_dim;      /* 128 (64 also supported) */
+    int32_t frame_h;       /* 30  tokens per latent-frame column */
+    int32_t frame_w;       /* 52 */
+    int32_t chunk_frames;  /* 3  latent frames per block (Sec. 4.1) */
+    int32_t window_chunks; /* 4  past blocks kept, w in Eq. 1 */
+    int32_t sink_frames;   /* 1 */
+} lvx_cache_desc_t;
+
+typedef struct lvx_kvcache lvx_kvcache_t; /* opaque host-side handle */
+
+/* Result of the ring arithmetic for one append. */
+typedef struct {
+    int32_t slot;           /* chunk slot written: chunk_index mod (window_chunks+1) */
+    int64_t evicted_chunk;  /* chunk index overwritten, -1 while the ring is filling */
+    int32_t n_valid_chunks; /* chunks held after the append, including the new one */
+    int32_t key_offset;     /* first key row of the slot, counted from the sink's first key */
+    int32_t key_count;      /* visible keys after the append (sink + valid chunks) */
+} lvx_slot_info_t;
+
+#define LVX_MAX_SLOTS 16
+typedef struct {
+    int64_t last_chunk;                 /* last chunk index appended to this layer, -1 if none */
+    int32_t sink_set;                   /* 1 once lvx_kvcache_set_sink ran for this layer */
+    int32_t n_valid_chunks;
+    int32_t key_count;
+    int32_t n_slots;                    /* window_chunks+1 */
+    int64_t slot_chunk[LVX_MAX_SLOTS];  /* chunk index living in each slot, -1 if empty */
+} lvx_ring_state_t;
+
+/* Bytes of device storage the caller must provide for K and V of all layers. 0 on a bad descriptor. */
+size_t lvx_kvcache_bytes(const lvx_cache_desc_t *desc /* host */);
+
+/* Pure host arithmetic of the ring (no device, no handle): where chunk `chunk_index` goes and what it
+ * evicts.  Errors: null pointers, bad descriptor, negative chunk_index. */
+lvx_status_t lvx_ring_slot(const lvx_cache_desc_t *desc /* host */, int64_t chunk_index, lvx_slot_info_t *out /* host */);
+
+/* Creates the host handle over caller-owned device storage (>= lvx_kvcache_bytes, 256-byte aligned) and
+ * enqueues a zero fill of it (stale keys past the visible prefix must be finite).  The storage must stay
+ * alive until lvx_kvcache_destroy.  Errors: INVALID_ARG (null/misaligned), SHAPE (bad descriptor, storage too
+ * small), UNSUPPORTED (head_dim not in {64,128}, window_chunks+1 > LVX_MAX_SLOTS). */
+lvx_status_t lvx_kvcache_init(const lvx_cache_desc_t *desc /* host */, void *dev_storage, size_t bytes,
+                              lvx_stream_t stream, lvx_kvcache_t **out /* host */);
+/* Frees host state only. */
+lvx_status_t lvx_kvcache_destroy(lvx_kvcache_t *cache);
+
+/* Writes the sink frame's K (already normalised and rotated) and V, token-major [sink_keys][ld], into the
+ * never-evicted segment of `layer` (Sec. 3.3: the sink stays in KV memory permanently). */
+lvx_status_t lvx_kvcache_set_sink(lvx_kvcache_t *cache, int32_t layer, const void *dev_k, const void *dev_v,
+                                  int64_t ld, lvx_stream_t stream);
+
+/* Alg. 3 "pop(0) if full; append": writes chunk `chunk_index`'s K-hat and V, token-major
+ * [chunk_keys][ld], into its ring slot of `layer`; the oldest chunk is overwritten once the ring is full; the
+ * sink segment is untouched.  chunk_index must be last_chunk+1 for that layer (0 first) else LVX_ERR_STATE.
+ * `out` (host, may be NULL) receives the slot arithmetic.  The copy is bit-exact. */
+lvx_status_t lvx_chunk_append_evict(lvx_kvcache_t *cache, int32_t layer, const void *dev_k, const void *dev_v,
+                                    int64_t ld, int64_t chunk_index, lvx_slot_info_t *out /* host */,
+                                    lvx_stream_t stream);
+
+lvx_status_t lvx_kvcache_get_state(const lvx_kvcache_t *cache, int32_t layer, lvx_ring_state_t *out /* host */);
+/* Restores ring bookkeeping after the caller restored the device storage (resume after off-loading). */
+lvx_status_t lvx_kvcache_set_state(lvx_kvcache_t *cache, int32_t layer, const lvx_ring_state_t *in /* host */);
+
+/* Reads keys [first_key, first_key+n_keys) of `layer` back as token-major [n_keys][ld] K and V (bit-exact). */
+lvx_status_t lvx_kvcache_gather(const lvx_kvcache_t *cache, int32_t layer, int32_t first_key, int32_t n_keys,
+                                void *dev_k_out, void *dev_v_out, int64_t ld, lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Fused Q/K RMSNorm + 3-D rotary embedding (rotary indices per latent frame: Appendix D "Rolling RoPE";
+ * the axis split, theta and the norm are the workload's, not the paper's).
+ *   y = x / sqrt(mean_c(x^2) + eps) * g          over all n_heads*head_dim channels of a token (g NULL: skip)
+ *   pair k of axis a (dims base_a+2k, base_a+2k+1):  (u,v) -> (u cos - v sin, u sin + v cos),
+ *   angle = pos_a * theta^(-2k/axes[a]),  pos = (t0 + n / (frame_h*frame_w), (n / frame_w) % frame_h, n % frame_w).
+ * Angles are formed in fp64 on the device, the rest in fp32.  In-place (out == in) is allowed.
+ * Either of q / k may be NULL (then its output is ignored).
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+    int32_t n_heads, head_dim;
+    int32_t axes[3];     /* dims given to t, y, x; even, sum = head_dim (44, 42, 42) */
+    float theta;         /* 10000 */
+    int32_t frame_h, frame_w;
+    float eps;           /* 1e-6 */
+    int32_t apply_rope;  /* 0 = norm only (cross-attention) */
+} lvx_rope_desc_t;
+
+lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc /* host */, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
+                        const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0,
+                        void *dev_q_out, void *dev_k_out, int64_t ld_out, lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Chunk-to-cache attention (Eq. 1; Appendix C attention paragraph: current tokens against the concatenation
+ * of cached K/V and themselves):  O[n,h,:] = softmax_m(scale * <q[n,h,:], K[m,h,:]>) V[m,h,:] over the visible
+ * prefix of `layer` (every key visible, no mask).  q, out: [n_q][ld] bf16.  bf16 MFMA, fp32 online softmax.
+ * Errors: STATE if the layer has no visible keys yet.
+ * ------------------------------------------------------------------------------------------------ */
+lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *cache, int32_t layer, const void *dev_q, int64_t ld_q,
+                                 int32_t n_q, float scale, void *dev_out, int64_t ld_out, lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Building blocks of the DiT block, exported for unit parity tests.
+ * ------------------------------------------------------------------------------------------------ */
+typedef enum {
+    LVX_EPI_STORE = 0,      /* C = A W^T */
+    LVX_EPI_GELU_TANH = 1,  /* C = gelu_tanh(A W^T) */
+    LVX_EPI_RESID_GATE = 2  /* C = R + gate[n] * (A W^T); gate NULL = 1; C may alias R */
+} lvx_epilogue_t;
+
+/* C[M][N] = epilogue(A[M][K] * W[N][K]^T), bf16 in/out, fp32 accumulate on MFMA.  K % 64 == 0, N % 8 == 0. */
+lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64_t ldw, void *dev_c, int64_t ldc,
+                        int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi, const void *dev_resid, int64_t ldr,
+                        const float *dev_gate, lvx_stream_t stream);
+
+/* u = LayerNorm(x) * (1 + scale) + shift, no affine, biased variance, eps inside the root.  shift/scale fp32 [d]
+ * or NULL (0).  x, u: [n][ld] bf16. */
+lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale,
+                                    float eps, int32_t n_tokens, int32_t d, void *dev_u, int64_t ldu, lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * DiT block and denoise stage (Alg. 4, DiT-device branch: forward with the local rolling cache, cache update,
+ * Euler step x <- x + v dt).  Block wiring (the paper defers to its base architecture; this is the workload's):
+ *   u  = LN(x)(1+scale1)+shift1;  [q|k|v] = u W_qkv^T;  q^,k^ = RoPE(RMSNorm(q,k));  append(k^, v);
+ *   x += gate1 * (Attn(q^, cache) W_o^T);
+ *   x += Attn(RMSNorm(LN(x) Wc_q^T), RMSNorm(ctx Wc_k^T), ctx Wc_v^T) Wc_o^T;
+ *   x += gate2 * (gelu_tanh((LN(x)(1+scale2)+shift2) W_1^T) W_2^T).
+ * mod6: fp32 [6][d] = shift1, scale1, gate1, shift2, scale2, gate2; NULL = 0,0,1,0,0,1.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+    const void *W_qkv;  /* [3d][d] rows: q, k, v */
+    const void *W_o;    /* [d][d] */
+    const void *Wc_q, *Wc_k, *Wc_v, *Wc_o; /* [d][d] */
+    const void *W_1;    /* [ffn][d] */
+    const void *W_2;    /* [d][ffn] */
+    const float *g_q, *g_k;   /* [d] self-attention RMSNorm gains, NULL = no norm */
+    const float *gc_q, *gc_k; /* [d] cross-attention RMSNorm gains, NULL = no norm */
+} lvx_block_weights_t;
+
+typedef struct {
+    int32_t n_layers;
+    int32_t d_ffn;
+    lvx_rope_desc_t rope;              /* n_heads*head_dim = d_model; must agree with the cache descriptor */
+    const lvx_block_weights_t *blocks; /* host array [n_layers] of device pointers */
+} lvx_stage_t;
+
+size_t lvx_workspace_bytes(const lvx_stage_t *stage /* host */, int32_t n_tokens, int32_t n_ctx);
+
+/* One block on the current chunk.  x_inout [n_tokens][d] bf16 (ld = d); ctx [n_ctx][d] bf16; t0 = temporal rotary
+ * index of the chunk's first frame; n_tokens must equal the cache's chunk size.  workspace: device scratch of
+ * lvx_workspace_bytes, 256-byte aligned. */
+lvx_status_t lvx_dit_block(const lvx_stage_t *stage /* host */, int32_t layer, lvx_kvcache_t *cache, void *dev_x_inout,
+                           int32_t n_tokens, const void *dev_ctx, int32_t n_ctx, const float *dev_mod6,
+                           int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
+/* All blocks, then x <- x + dt * stack(x).  mod6_per_layer: fp32 [n_layers][6][d] or NULL. */
+lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage /* host */, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
+                               const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
+                               int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LVX_H */

@@ -1,0 +1,234 @@
+"""Python binding of liblvx.so (the gfx950 HIP path).  Argument marshalling only: every step runs in the library.
+
+PyTorch supplies device memory and the current HIP stream, nothing else.  There is no CPU fallback: `load()` raises
+if the library has not been built (`python -m paper_2512_04677_amd.build`), and every call raises `LvxError` on a
+non-zero status.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblvx.so")
+_lib = None
+
+LVX_MAX_SLOTS = 16
+EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE = 0, 1, 2
+STATUS_NAMES = {0: "LVX_OK", 1: "LVX_ERR_INVALID_ARG", 2: "LVX_ERR_SHAPE", 3: "LVX_ERR_STATE", 4: "LVX_ERR_UNSUPPORTED",
+                5: "LVX_ERR_HIP"}
+
+
+class LvxError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("%s: %s" % (STATUS_NAMES.get(status, status), message))
+        self.status = status
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "n_heads", "head_dim", "frame_h", "frame_w", "chunk_frames",
+                                         "window_chunks", "sink_frames")]
+
+
+class SlotInfo(C.Structure):
+    _fields_ = [("slot", C.c_int32), ("evicted_chunk", C.c_int64), ("n_valid_chunks", C.c_int32),
+                ("key_offset", C.c_int32), ("key_count", C.c_int32)]
+
+
+class RingState(C.Structure):
+    _fields_ = [("last_chunk", C.c_int64), ("sink_set", C.c_int32), ("n_valid_chunks", C.c_int32),
+                ("key_count", C.c_int32), ("n_slots", C.c_int32), ("slot_chunk", C.c_int64 * LVX_MAX_SLOTS)]
+
+
+class RopeDesc(C.Structure):
+    _fields_ = [("n_heads", C.c_int32), ("head_dim", C.c_int32), ("axes", C.c_int32 * 3), ("theta", C.c_float),
+                ("frame_h", C.c_int32), ("frame_w", C.c_int32), ("eps", C.c_float), ("apply_rope", C.c_int32)]
+
+
+class BlockWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("W_qkv", "W_o", "Wc_q", "Wc_k", "Wc_v", "Wc_o", "W_1", "W_2",
+                                          "g_q", "g_k", "gc_q", "gc_k")]
+
+
+class Stage(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_ffn", C.c_int32), ("rope", RopeDesc), ("blocks", C.POINTER(BlockWeights))]
+
+
+# name -> (restype, argtypes); the list the header declares
+_vp, _i32, _i64, _f32, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_float, C.c_size_t
+SIGNATURES = {
+    "lvx_last_error": (C.c_char_p, []),
+    "lvx_version": (C.c_char_p, []),
+    "lvx_kvcache_bytes": (_sz, [C.POINTER(CacheDesc)]),
+    "lvx_ring_slot": (C.c_int, [C.POINTER(CacheDesc), _i64, C.POINTER(SlotInfo)]),
+    "lvx_kvcache_init": (C.c_int, [C.POINTER(CacheDesc), _vp, _sz, _vp, C.POINTER(_vp)]),
+    "lvx_kvcache_destroy": (C.c_int, [_vp]),
+    "lvx_kvcache_set_sink": (C.c_int, [_vp, _i32, _vp, _vp, _i64, _vp]),
+    "lvx_chunk_append_evict": (C.c_int, [_vp, _i32, _vp, _vp, _i64, _i64, C.POINTER(SlotInfo), _vp]),
+    "lvx_kvcache_get_state": (C.c_int, [_vp, _i32, C.POINTER(RingState)]),
+    "lvx_kvcache_set_state": (C.c_int, [_vp, _i32, C.POINTER(RingState)]),
+    "lvx_kvcache_gather": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "lvx_rope3d": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "lvx_chunk_attention": (C.c_int, [_vp, _i32, _vp, _i64, _i32, _f32, _vp, _i64, _vp]),
+    "lvx_linear": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
+    "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
+    "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
+    "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
+    "lvx_denoise_stage": (C.c_int, [C.POINTER(Stage), _vp, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _vp, _sz, _vp]),
+}
+
+
+def load():
+    """Loads liblvx.so; raises if it is missing (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("liblvx.so is not built: run `python -m paper_2512_04677_amd.build` "
+                           "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = C.CDLL(LIB_PATH)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _check(status):
+    if status != 0:
+        raise LvxError(status, load().lvx_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def version():
+    return load().lvx_version().decode()
+
+
+def cache_desc(n_layers, n_heads, head_dim, frame_h, frame_w, chunk_frames, window_chunks, sink_frames):
+    return CacheDesc(n_layers, n_heads, head_dim, frame_h, frame_w, chunk_frames, window_chunks, sink_frames)
+
+
+def rope_desc(n_heads, head_dim, axes, theta, frame_h, frame_w, eps=1e-6, apply_rope=1):
+    return RopeDesc(n_heads, head_dim, (C.c_int32 * 3)(*axes), theta, frame_h, frame_w, eps, apply_rope)
+
+
+def lvx_kvcache_bytes(desc):
+    return load().lvx_kvcache_bytes(C.byref(desc))
+
+
+def lvx_ring_slot(desc, chunk_index):
+    info = SlotInfo()
+    _check(load().lvx_ring_slot(C.byref(desc), chunk_index, C.byref(info)))
+    return info
+
+
+class KVCache:
+    """Owns the torch storage tensor and the library handle of one rolling cache."""
+
+    def __init__(self, desc, device="cuda:0"):
+        import torch
+        self.desc = desc
+        nbytes = lvx_kvcache_bytes(desc)
+        if nbytes == 0:
+            raise LvxError(2, load().lvx_last_error().decode())
+        self.storage = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        h = C.c_void_p()
+        _check(load().lvx_kvcache_init(C.byref(desc), _ptr(self.storage), nbytes, _stream(), C.byref(h)))
+        self.handle = h
+
+    def close(self):
+        if self.handle is not None:
+            load().lvx_kvcache_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def lvx_kvcache_set_sink(cache, layer, k, v, ld=None):
+    _check(load().lvx_kvcache_set_sink(cache.handle, layer, _ptr(k), _ptr(v), ld if ld is not None else k.stride(0), _stream()))
+
+
+def lvx_chunk_append_evict(cache, layer, k, v, chunk_index, ld=None):
+    info = SlotInfo()
+    _check(load().lvx_chunk_append_evict(cache.handle, layer, _ptr(k), _ptr(v), ld if ld is not None else k.stride(0),
+                                         chunk_index, C.byref(info), _stream()))
+    return info
+
+
+def lvx_kvcache_get_state(cache, layer):
+    s = RingState()
+    _check(load().lvx_kvcache_get_state(cache.handle, layer, C.byref(s)))
+    return s
+
+
+def lvx_kvcache_set_state(cache, layer, state):
+    _check(load().lvx_kvcache_set_state(cache.handle, layer, C.byref(state)))
+
+
+def lvx_kvcache_gather(cache, layer, first_key, n_keys, k_out, v_out):
+    _check(load().lvx_kvcache_gather(cache.handle, layer, first_key, n_keys, _ptr(k_out), _ptr(v_out), k_out.stride(0), _stream()))
+
+
+def lvx_rope3d(desc, q_in, k_in, g_q, g_k, n_tokens, t0, q_out, k_out, ld_in=None, ld_out=None):
+    ref_in = q_in if q_in is not None else k_in
+    ref_out = q_out if q_out is not None else k_out
+    _check(load().lvx_rope3d(C.byref(desc), _ptr(q_in), _ptr(k_in), ld_in if ld_in is not None else ref_in.stride(0),
+                             _ptr(g_q), _ptr(g_k), n_tokens, t0, _ptr(q_out), _ptr(k_out),
+                             ld_out if ld_out is not None else ref_out.stride(0), _stream()))
+
+
+def lvx_chunk_attention(cache, layer, q, scale, out, n_q=None):
+    _check(load().lvx_chunk_attention(cache.handle, layer, _ptr(q), q.stride(0), q.shape[0] if n_q is None else n_q,
+                                      scale, _ptr(out), out.stride(0), _stream()))
+
+
+def lvx_linear(a, w, c, epi=EPI_STORE, resid=None, gate=None, M=None):
+    M = a.shape[0] if M is None else M
+    N, K = w.shape
+    _check(load().lvx_linear(_ptr(a), a.stride(0), _ptr(w), w.stride(0), _ptr(c), c.stride(0), M, N, K, epi,
+                             _ptr(resid), resid.stride(0) if resid is not None else 0, _ptr(gate), _stream()))
+
+
+def lvx_layernorm_modulate(x, shift, scale, eps, u):
+    _check(load().lvx_layernorm_modulate(_ptr(x), x.stride(0), _ptr(shift), _ptr(scale), eps, x.shape[0], x.shape[1],
+                                         _ptr(u), u.stride(0), _stream()))
+
+
+class StageHandle:
+    """Host-side stage descriptor: keeps the weight tensors alive and holds the C structs."""
+
+    def __init__(self, layers, rope, d_ffn):
+        self.layers = layers
+        self.n = len(layers)
+        self.blocks = (BlockWeights * self.n)()
+        for i, w in enumerate(layers):
+            for name, _ in BlockWeights._fields_:
+                t = w.get(name)
+                setattr(self.blocks[i], name, None if t is None else t.data_ptr())
+        self.rope = rope
+        self.c = Stage(self.n, d_ffn, rope, C.cast(self.blocks, C.POINTER(BlockWeights)))
+
+
+def lvx_workspace_bytes(stage, n_tokens, n_ctx):
+    return load().lvx_workspace_bytes(C.byref(stage.c), n_tokens, n_ctx)
+
+
+def lvx_dit_block(stage, layer, cache, x, ctx, mod6, chunk_index, t0, workspace):
+    _check(load().lvx_dit_block(C.byref(stage.c), layer, cache.handle, _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0], _ptr(mod6),
+                                chunk_index, t0, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def lvx_denoise_stage(stage, cache, x, ctx, mod6_per_layer, dt, chunk_index, t0, workspace):
+    _check(load().lvx_denoise_stage(C.byref(stage.c), cache.handle, _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0],
+                                    _ptr(mod6_per_layer), dt, chunk_index, t0, _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(), _stream()))

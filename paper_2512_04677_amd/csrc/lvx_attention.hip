@@ -1,0 +1,232 @@
+// Chunk-to-cache attention for gfx950: O = softmax(scale * Q K^T) V over the visible key prefix, no mask
+// (paper Eq. 1 and the mask rule of Sec. 3.2: everything in the cache is visible to the current block).
+//
+// Design (MI355X-first, not the Hopper kernels the paper names):
+//   * one workgroup = one head x (32*NWAVES) queries; each 64-lane wave owns 32 queries and the full head_dim.
+//   * scores are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in that accumulator layout a lane
+//     holds scores of ONE query (column lane%32) for 16 keys per 32-key block, so the online-softmax statistics are
+//     per-lane scalars (one cross-half exchange per tile) and the exponentiated scores are already in the B-operand
+//     layout of the second MFMA, O^T += V^T P^T, with no LDS round trip.
+//   * K tiles ([64 keys][D]) and V^T tiles ([D][64 keys], stored transposed in the cache) are double-buffered in LDS;
+//     rows are padded so that 16 consecutive lanes reading 16 bytes each hit disjoint banks.
+//   * K rows are placed in LDS in the order the accumulator layout wants (lane i of the A operand reads LDS row i),
+//     which makes each half-wave's 16 scores per block belong to 16 CONSECUTIVE keys, so V^T fragments are
+//     contiguous 16-byte reads.
+//   * the running maximum is only raised when a tile exceeds it by more than 2^6 (wave-uniform branch), so the
+//     rescale of the O accumulators almost never runs; the final division by the row sum absorbs the stale maximum.
+//   * workgroup -> (head, query tile) mapping keeps all query tiles of a head on one XCD (hardware deals consecutive
+//     workgroup ids round-robin over the 8 XCDs), so a head's K/V stream is fetched into one L2 only.
+#include "lvx_internal.h"
+
+namespace {
+
+constexpr int KT = LVX_KEY_TILE;
+
+template <int D, int NWAVES>
+__global__ void __launch_bounds__(64 * NWAVES)
+    lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
+                         const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
+                         int64_t ld_out, int n_qtiles, int total_wg, int per_xcd) {
+    constexpr int NT = 64 * NWAVES;
+    constexpr int QT = 32 * NWAVES;
+    constexpr int K_LD = D + 8;   // bf16 per padded K row
+    constexpr int V_LD = KT + 8;  // bf16 per padded V^T row
+    constexpr int K_STAGE = KT * K_LD;
+    constexpr int V_STAGE = D * V_LD;
+    constexpr int CH = KT * D / 8;  // 16-byte chunks per tile (same for K and V^T)
+    static_assert(CH % NT == 0, "tile chunks must divide over the threads");
+    constexpr int CPT = CH / NT;
+    constexpr int MK = D / 16;  // MFMA k-steps over head_dim
+    constexpr int DB = D / 32;  // 32-row blocks of O^T
+
+    __shared__ __attribute__((aligned(16))) bf16_t ks[2 * K_STAGE];
+    __shared__ __attribute__((aligned(16))) bf16_t vs[2 * V_STAGE];
+
+    // XCD-aware decode: consecutive block ids go to consecutive XCDs; give each XCD a contiguous range of work
+    const int xcd = blockIdx.x & 7;
+    const int widx = xcd * per_xcd + (blockIdx.x >> 3);
+    if (widx >= total_wg) return;
+    const int head = widx / n_qtiles;
+    const int qtile = widx % n_qtiles;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+
+    // Q fragments (B operand of S^T = K Q^T): lane holds Q[query l32][d = 16m + 8hh .. +7]
+    bf16x8_t qf[MK];
+    {
+        int row = qtile * QT + wave * 32 + l32;
+        if (row > n_q - 1) row = n_q - 1;
+        const bf16_t *qp = q + (size_t)row * ld_q + (size_t)head * D + hh * 8;
+#pragma unroll
+        for (int m = 0; m < MK; ++m) qf[m] = *reinterpret_cast<const bf16x8_t *>(qp + 16 * m);
+    }
+
+    const int n_tiles = (n_keys + KT - 1) / KT;
+    const u32x4_t *k_src = reinterpret_cast<const u32x4_t *>(kp + (size_t)head * cap * D);
+    const u32x4_t *v_src = reinterpret_cast<const u32x4_t *>(vtp + (size_t)head * cap * D);
+
+    u32x4_t kreg[CPT], vreg[CPT];
+#define LVX_ATTN_GLOAD(t_)                                   \
+    {                                                        \
+        const u32x4_t *kt_ = k_src + (size_t)(t_) * CH;        \
+        const u32x4_t *vt_ = v_src + (size_t)(t_) * CH;        \
+        _Pragma("unroll") for (int i = 0; i < CPT; ++i) {    \
+            kreg[i] = kt_[tid + i * NT];                     \
+            vreg[i] = vt_[tid + i * NT];                     \
+        }                                                    \
+    }
+    // key row r = 32*blk + 16h + 4g4 + r4 goes to LDS row 32*blk + 8*g4 + 4h + r4 (accumulator row order)
+#define LVX_ATTN_LSTORE(buf_)                                                                             \
+    {                                                                                                     \
+        _Pragma("unroll") for (int i = 0; i < CPT; ++i) {                                                 \
+            const int g = tid + i * NT;                                                                   \
+            const int r = g / (D / 8), cc = g % (D / 8);                                                  \
+            const int rr = (r & 32) | (((r >> 2) & 3) << 3) | (((r >> 4) & 1) << 2) | (r & 3);            \
+            *reinterpret_cast<u32x4_t *>(&ks[(buf_) * K_STAGE + rr * K_LD + cc * 8]) = kreg[i];             \
+            const int d = g / (KT / 8), kc = g % (KT / 8);                                                \
+            *reinterpret_cast<u32x4_t *>(&vs[(buf_) * V_STAGE + d * V_LD + kc * 8]) = vreg[i];              \
+        }                                                                                                 \
+    }
+
+    f32x16_t o[DB];
+#pragma unroll
+    for (int i = 0; i < DB; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
+    float mc = -INFINITY;  // running maximum, already multiplied by c_exp2
+    float l_run = 0.f;
+
+    LVX_ATTN_GLOAD(0);
+    LVX_ATTN_LSTORE(0);
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < n_tiles) LVX_ATTN_GLOAD(t + 1);
+
+        f32x16_t s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
+            const bf16_t *kr = &ks[buf * K_STAGE + (kb * 32 + l32) * K_LD + hh * 8];
+#pragma unroll
+            for (int m = 0; m < MK; ++m) {
+                const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(kr + 16 * m);
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[m], s[kb], 0, 0, 0);
+            }
+        }
+        // accumulator register v of block kb holds key  t*64 + kb*32 + 16*hh + v  for query l32
+        if (t == n_tiles - 1 && (n_keys % KT) != 0) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (t * KT + kb * 32 + 16 * hh + v >= n_keys) s[kb][v] = -INFINITY;
+        }
+        float tmax = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[kb][v]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float tmc = tmax * c_exp2;
+        const bool need = tmc > mc + 6.0f;
+        if (__any(need)) {
+            const float alpha = need ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;
+            if (need) mc = tmc;
+            l_run *= alpha;
+#pragma unroll
+            for (int i = 0; i < DB; ++i)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
+        }
+        bf16x8_t pb[2][2];
+        float lsum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));
+                lsum += p;
+                pb[kb][v >> 3][v & 7] = (__bf16)p;
+            }
+        l_run += lsum;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+            const bf16_t *vr = &vs[buf * V_STAGE + (db * 32 + l32) * V_LD + 16 * hh];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int mm = 0; mm < 2; ++mm) {
+                    const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(vr + kb * 32 + 8 * mm);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kb][mm], o[db], 0, 0, 0);
+                }
+        }
+        if (t + 1 < n_tiles) LVX_ATTN_LSTORE(buf ^ 1);
+        __syncthreads();
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.0f / l_tot;
+    const int row = qtile * QT + wave * 32 + l32;
+    if (row < n_q) {
+        bf16_t *op = out + (size_t)row * ld_out + (size_t)head * D;
+        // accumulator register 4g+r of block db holds O^T[d = 32db + 8g + 4hh + r][query l32]
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint2 w;
+                w.x = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
+                w.y = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
+                *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hh) = w;
+            }
+    }
+}
+
+template <int D, int NWAVES>
+lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
+                    float scale, bf16_t *out, int64_t ld_out, hipStream_t stream) {
+    constexpr int QT = 32 * NWAVES;
+    const int n_qtiles = (n_q + QT - 1) / QT;
+    const int total = n_qtiles * H;
+    const int per_xcd = (total + 7) / 8;
+    const float c = scale * 1.4426950408889634f;
+    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
+                       n_keys, c, out, ld_out, n_qtiles, total, per_xcd);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+}  // namespace
+
+lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
+                                  const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
+                                  hipStream_t stream) {
+    LVX_REQUIRE(n_q > 0 && n_keys > 0 && n_keys <= cap && cap % KT == 0, LVX_ERR_SHAPE, "attention: n_q %d, n_keys %d, cap %d", n_q,
+                n_keys, cap);
+    LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
+    if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream);
+    if (D == 64) return launch<64, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream);
+    return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
+}
+
+extern "C" lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *c, int32_t layer, const void *dev_q, int64_t ld_q, int32_t n_q,
+                                            float scale, void *dev_out, int64_t ld_out, lvx_stream_t stream) {
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(dev_q != nullptr && dev_out != nullptr, LVX_ERR_INVALID_ARG, "q or out is NULL");
+    LVX_REQUIRE(lvx_aligned16(dev_q) && lvx_aligned16(dev_out), LVX_ERR_INVALID_ARG, "q and out must be 16-byte aligned");
+    const int64_t d = (int64_t)c->desc.n_heads * c->desc.head_dim;
+    LVX_REQUIRE(ld_q >= d && ld_q % 8 == 0 && ld_out >= d && ld_out % 8 == 0, LVX_ERR_SHAPE,
+                "row strides must be multiples of 8 and >= n_heads*head_dim");
+    LVX_REQUIRE(n_q > 0, LVX_ERR_SHAPE, "n_q %d must be positive", n_q);
+    LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "scale must be positive");
+    const lvx_ring_state_t &s = c->state[layer];
+    LVX_REQUIRE(s.key_count > 0, LVX_ERR_STATE, "layer %d has no visible keys (set the sink / append a chunk first)", layer);
+    return lvx_launch_attention((const bf16_t *)dev_q, ld_q, n_q, c->desc.n_heads, c->desc.head_dim, lvx_cache_k(c, layer),
+                                lvx_cache_vt(c, layer), c->cap_keys, s.key_count, scale, (bf16_t *)dev_out, ld_out, (hipStream_t)stream);
+}

@@ -1,0 +1,154 @@
+// DiT block and denoise stage: host-side sequencing of the kernels on one HIP stream, no synchronisation inside.
+// (Paper Alg. 4, DiT-device branch: forward with the device's local rolling KV cache, cache update, Euler step;
+// Sec. 3.4: throughput of the pipeline is set by this single denoise forward.)
+#include "lvx_internal.h"
+
+#include <math.h>
+
+namespace {
+
+struct ws_layout_t {
+    size_t u, big, ctx_kv, pack_k, pack_v, h, total;  // byte offsets
+    int cap_ctx;
+};
+
+size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+
+ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
+    ws_layout_t w;
+    const size_t d = (size_t)s->rope.n_heads * s->rope.head_dim;
+    const size_t wide = 3 * d > (size_t)s->d_ffn ? 3 * d : (size_t)s->d_ffn;
+    w.cap_ctx = (n_ctx + LVX_KEY_TILE - 1) / LVX_KEY_TILE * LVX_KEY_TILE;
+    size_t off = 0;
+    w.u = off;       off += round256((size_t)n_tokens * d * 2);
+    w.big = off;     off += round256((size_t)n_tokens * wide * 2);
+    w.ctx_kv = off;  off += round256((size_t)n_ctx * 2 * d * 2);
+    w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
+    w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
+    w.h = off;       off += round256((size_t)n_tokens * d * 2);
+    w.total = off;
+    return w;
+}
+
+lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_tokens, int n_ctx) {
+    LVX_REQUIRE(s != nullptr, LVX_ERR_INVALID_ARG, "stage descriptor is NULL");
+    LVX_REQUIRE(s->blocks != nullptr && s->n_layers > 0, LVX_ERR_INVALID_ARG, "stage has no blocks");
+    LVX_REQUIRE(s->rope.n_heads > 0 && (s->rope.head_dim == 64 || s->rope.head_dim == 128), LVX_ERR_UNSUPPORTED,
+                "head_dim %d not supported (64 or 128)", s->rope.head_dim);
+    const int d = s->rope.n_heads * s->rope.head_dim;
+    LVX_REQUIRE(d % 64 == 0 && s->d_ffn > 0 && s->d_ffn % 64 == 0, LVX_ERR_SHAPE, "d_model %d and d_ffn %d must be multiples of 64", d,
+                s->d_ffn);
+    LVX_REQUIRE(n_tokens > 0 && n_ctx > 0, LVX_ERR_SHAPE, "n_tokens %d and n_ctx %d must be positive", n_tokens, n_ctx);
+    if (c != nullptr) {
+        LVX_REQUIRE(c->desc.n_heads == s->rope.n_heads && c->desc.head_dim == s->rope.head_dim && c->desc.frame_h == s->rope.frame_h &&
+                        c->desc.frame_w == s->rope.frame_w,
+                    LVX_ERR_SHAPE, "stage and cache descriptors disagree on heads / head_dim / frame size");
+        LVX_REQUIRE(c->desc.n_layers >= s->n_layers, LVX_ERR_SHAPE, "cache has %d layers, stage has %d", c->desc.n_layers, s->n_layers);
+        LVX_REQUIRE(n_tokens == c->chunk_keys, LVX_ERR_SHAPE, "n_tokens %d must equal the cache's chunk size %d", n_tokens, c->chunk_keys);
+    }
+    return LVX_OK;
+}
+
+#define LVX_TRY(expr)                    \
+    do {                                 \
+        lvx_status_t st_ = (expr);       \
+        if (st_ != LVX_OK) return st_;   \
+    } while (0)
+
+lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, bf16_t *x, int n, const bf16_t *ctx, int n_ctx,
+                       const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st) {
+    const lvx_block_weights_t &w = s->blocks[layer];
+    const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
+    const float eps = s->rope.eps;
+    const float scale = 1.0f / sqrtf((float)D);
+    bf16_t *u = (bf16_t *)(ws + L.u);
+    bf16_t *big = (bf16_t *)(ws + L.big);
+    bf16_t *ctx_kv = (bf16_t *)(ws + L.ctx_kv);
+    bf16_t *pack_k = (bf16_t *)(ws + L.pack_k);
+    bf16_t *pack_v = (bf16_t *)(ws + L.pack_v);
+    const float *shift1 = mod6 ? mod6 : nullptr, *scale1 = mod6 ? mod6 + d : nullptr, *gate1 = mod6 ? mod6 + 2 * d : nullptr;
+    const float *shift2 = mod6 ? mod6 + 3 * d : nullptr, *scale2 = mod6 ? mod6 + 4 * d : nullptr, *gate2 = mod6 ? mod6 + 5 * d : nullptr;
+
+    // self-attention branch
+    LVX_TRY(lvx_layernorm_modulate(x, d, shift1, scale1, eps, n, d, u, d, st));
+    LVX_TRY(lvx_linear(u, d, w.W_qkv, d, big, 3 * d, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    LVX_TRY(lvx_rope3d(&s->rope, big, big + d, 3 * d, w.g_q, w.g_k, n, t0, big, big + d, 3 * d, st));
+    LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, 3 * d, chunk_index, nullptr, st));
+    LVX_TRY(lvx_chunk_attention(c, layer, big, 3 * d, n, scale, u, d, st));
+    LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE, x, d, gate1, st));
+
+    // cross-attention to the audio + text context
+    LVX_TRY(lvx_layernorm_modulate(x, d, nullptr, nullptr, eps, n, d, u, d, st));
+    LVX_TRY(lvx_linear(u, d, w.Wc_q, d, big, d, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    LVX_TRY(lvx_linear(ctx, d, w.Wc_k, d, ctx_kv, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    LVX_TRY(lvx_linear(ctx, d, w.Wc_v, d, ctx_kv + d, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    lvx_rope_desc_t norm_only = s->rope;
+    norm_only.apply_rope = 0;
+    if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, d, w.gc_q, nullptr, n, 0, big, nullptr, d, st));
+    if (w.gc_k) LVX_TRY(lvx_rope3d(&norm_only, nullptr, ctx_kv, 2 * d, nullptr, w.gc_k, n_ctx, 0, nullptr, ctx_kv, 2 * d, st));
+    if (L.cap_ctx != n_ctx) {  // keys past n_ctx in the last tile must be finite
+        LVX_TRY(lvx_launch_fill_zero(pack_k, (size_t)L.cap_ctx * d * 2, st));
+        LVX_TRY(lvx_launch_fill_zero(pack_v, (size_t)L.cap_ctx * d * 2, st));
+    }
+    LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, 2 * d, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
+    LVX_TRY(lvx_launch_attention(big, d, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, d, st));
+    LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE, x, d, nullptr, st));
+
+    // feed-forward
+    LVX_TRY(lvx_layernorm_modulate(x, d, shift2, scale2, eps, n, d, u, d, st));
+    LVX_TRY(lvx_linear(u, d, w.W_1, d, big, f, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st));
+    LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE, x, d, gate2, st));
+    return LVX_OK;
+}
+
+lvx_status_t check_common(const lvx_stage_t *s, lvx_kvcache *c, void *x, int n, const void *ctx, int n_ctx, void *ws, size_t ws_bytes,
+                          int64_t chunk_index, int t0) {
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    LVX_TRY(check_stage(s, c, n, n_ctx));
+    LVX_REQUIRE(x != nullptr && ctx != nullptr && ws != nullptr, LVX_ERR_INVALID_ARG, "x, ctx or workspace is NULL");
+    LVX_REQUIRE(lvx_aligned16(x) && lvx_aligned16(ctx) && (((uintptr_t)ws) & 255u) == 0, LVX_ERR_INVALID_ARG,
+                "x / ctx must be 16-byte and workspace 256-byte aligned");
+    const size_t need = lvx_workspace_bytes(s, n, n_ctx);
+    LVX_REQUIRE(ws_bytes >= need, LVX_ERR_SHAPE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    LVX_REQUIRE(chunk_index >= 0 && t0 >= 0, LVX_ERR_INVALID_ARG, "chunk_index and t0 must be non-negative");
+    return LVX_OK;
+}
+
+}  // namespace
+
+extern "C" size_t lvx_workspace_bytes(const lvx_stage_t *stage, int32_t n_tokens, int32_t n_ctx) {
+    if (check_stage(stage, nullptr, n_tokens, n_ctx) != LVX_OK) return 0;
+    return ws_layout(stage, n_tokens, n_ctx).total;
+}
+
+extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
+                                      const void *dev_ctx, int32_t n_ctx, const float *dev_mod6, int64_t chunk_index, int32_t t0,
+                                      void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
+    LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
+    LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
+    const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
+    return run_block(stage, layer, cache, (bf16_t *)dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
+                     (char *)dev_workspace, L, (hipStream_t)stream);
+}
+
+extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
+                                          const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
+                                          int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
+    LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
+    for (int l = 0; l < stage->n_layers; ++l)
+        LVX_REQUIRE(cache->state[l].last_chunk + 1 == chunk_index, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", l,
+                    (long long)(cache->state[l].last_chunk + 1), (long long)chunk_index);
+    const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
+    const int d = stage->rope.n_heads * stage->rope.head_dim;
+    bf16_t *x = (bf16_t *)dev_x_inout;
+    bf16_t *h = (bf16_t *)((char *)dev_workspace + L.h);
+    const size_t n_elems = (size_t)n_tokens * d;
+    LVX_TRY(lvx_launch_copy(x, h, n_elems, (hipStream_t)stream));
+    for (int l = 0; l < stage->n_layers; ++l) {
+        const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
+        LVX_TRY(run_block(stage, l, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, m6, chunk_index, t0, (char *)dev_workspace, L,
+                          (hipStream_t)stream));
+    }
+    // Euler step of Alg. 3 / Alg. 4:  x <- x + v dt, the stack output standing in for the velocity
+    return lvx_launch_axpy(x, h, dt, x, n_elems, (hipStream_t)stream);
+}

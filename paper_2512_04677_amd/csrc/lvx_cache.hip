@@ -1,0 +1,366 @@
+// Rolling KV cache: host ring bookkeeping + the append / sink / gather kernels.
+//
+// Protocol (paper Alg. 3 / Alg. 4: "if the cache holds L entries pop the oldest, then append"; Sec. 3.3: one sink
+// frame stays for ever; Sec. 3.2: a block attends to itself in full).  The forward of chunk i has to see chunk i's own
+// K/V, so the write happens before the attention and the ring has window+1 slots: chunk i lands in slot
+// i mod (window+1) and physically overwrites chunk i-(window+1), which the list protocol had already dropped after
+// the forward of chunk i-1.
+//
+// HBM layout per layer (private): K  [head][cap_keys][D]            -> a 64-key K tile of one head is 64*D contiguous bf16
+//                                 V^T[head][cap_keys/64][D][64]     -> a 64-key V tile is stored transposed, contiguous,
+// so both tiles stream into LDS with 16-byte loads and are direct MFMA A-operands (contraction index contiguous).
+// Key rows: [0, sink_keys) sink, then slot s at sink_keys + s*chunk_keys.
+#include "lvx_internal.h"
+
+#include <new>
+#include <string.h>
+
+// ------------------------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+
+lvx_status_t lvx_fail(lvx_status_t code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" const char *lvx_last_error(void) { return g_err; }
+extern "C" const char *lvx_version(void) { return "lvx 0.1 gfx950"; }
+
+// ------------------------------------------------------------------------------------------------ kernels
+__global__ void __launch_bounds__(256) lvx_fill_zero_kernel(uint4 *p, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (; i < n16; i += stride) p[i] = z;
+}
+
+// One workgroup = one head x one 64-key tile of the destination.  Copies the rows of K that fall into the tile and
+// writes the matching part of the transposed V tile (through LDS).  Only keys in [key0, key0+n) are touched: a tile
+// shared with a neighbouring slot keeps the neighbour's keys.
+template <int D>
+__global__ void __launch_bounds__(256) lvx_pack_kv_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, int64_t ld,
+                                                          int n, int cap, int key0, int tile0, bf16_t *__restrict__ kp,
+                                                          bf16_t *__restrict__ vtp) {
+    constexpr int KT = LVX_KEY_TILE;
+    constexpr int CPR = D / 8;        // 16-byte chunks per row
+    constexpr int LDS_LD = D + 8;     // padded row, keeps 16-byte alignment
+    __shared__ __attribute__((aligned(16))) bf16_t vs[KT * LDS_LD];
+
+    const int tile = tile0 + blockIdx.x;
+    const int h = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int key_lo = tile * KT;
+    const int n_tiles = cap / KT;
+
+    for (int g = tid; g < KT * CPR; g += 256) {
+        const int r = g / CPR, c = g % CPR;
+        const int key = key_lo + r;
+        const int src = key - key0;
+        uint4 val = make_uint4(0, 0, 0, 0);
+        if (src >= 0 && src < n) {
+            const size_t so = (size_t)src * ld + (size_t)h * D + c * 8;
+            const uint4 kv = *reinterpret_cast<const uint4 *>(k + so);
+            *reinterpret_cast<uint4 *>(kp + ((size_t)h * cap + key) * D + c * 8) = kv;
+            val = *reinterpret_cast<const uint4 *>(v + so);
+        }
+        *reinterpret_cast<uint4 *>(&vs[r * LDS_LD + c * 8]) = val;
+    }
+    __syncthreads();
+    bf16_t *vt_tile = vtp + ((size_t)h * n_tiles + tile) * (size_t)D * KT;
+    for (int g = tid; g < D * (KT / 8); g += 256) {
+        const int d = g / (KT / 8), kc = g % (KT / 8);
+        const int lo = key_lo + kc * 8 - key0;  // source index of the first of 8 keys
+        if (lo + 7 < 0 || lo >= n) continue;
+        bf16_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = vs[(kc * 8 + j) * LDS_LD + d];
+        bf16_t *dst = vt_tile + (size_t)d * KT + kc * 8;
+        if (lo >= 0 && lo + 7 < n) {
+            uint4 o;
+            o.x = e[0] | ((uint32_t)e[1] << 16);
+            o.y = e[2] | ((uint32_t)e[3] << 16);
+            o.z = e[4] | ((uint32_t)e[5] << 16);
+            o.w = e[6] | ((uint32_t)e[7] << 16);
+            *reinterpret_cast<uint4 *>(dst) = o;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (lo + j >= 0 && lo + j < n) dst[j] = e[j];
+        }
+    }
+}
+
+// Inverse of the pack: thread = (key, head, 16-byte chunk).  Check / off-load path, not tuned.
+template <int D>
+__global__ void __launch_bounds__(256) lvx_gather_kv_kernel(const bf16_t *__restrict__ kp, const bf16_t *__restrict__ vtp, int cap,
+                                                            int H, int first_key, int n_keys, bf16_t *__restrict__ k_out,
+                                                            bf16_t *__restrict__ v_out, int64_t ld) {
+    constexpr int KT = LVX_KEY_TILE;
+    constexpr int CPR = D / 8;
+    const size_t total = (size_t)n_keys * H * CPR;
+    const int n_tiles = cap / KT;
+    for (size_t g = (size_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (size_t)gridDim.x * 256) {
+        const int c = (int)(g % CPR);
+        const int h = (int)((g / CPR) % H);
+        const int r = (int)(g / ((size_t)CPR * H));
+        const int key = first_key + r;
+        const size_t oo = (size_t)r * ld + (size_t)h * D + c * 8;
+        *reinterpret_cast<uint4 *>(k_out + oo) = *reinterpret_cast<const uint4 *>(kp + ((size_t)h * cap + key) * D + c * 8);
+        const bf16_t *vt_tile = vtp + ((size_t)h * n_tiles + key / KT) * (size_t)D * KT;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v_out[oo + j] = vt_tile[(size_t)(c * 8 + j) * KT + key % KT];
+    }
+}
+
+__global__ void __launch_bounds__(256) lvx_axpy_kernel(const uint4 *x, const uint4 *h, float dt, uint4 *out, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        const uint4 a = x[i], b = h[i];
+        uint4 o;
+        o.x = pack_bf16x2(bf16_lo(a.x) + dt * bf16_lo(b.x), bf16_hi(a.x) + dt * bf16_hi(b.x));
+        o.y = pack_bf16x2(bf16_lo(a.y) + dt * bf16_lo(b.y), bf16_hi(a.y) + dt * bf16_hi(b.y));
+        o.z = pack_bf16x2(bf16_lo(a.z) + dt * bf16_lo(b.z), bf16_hi(a.z) + dt * bf16_hi(b.z));
+        o.w = pack_bf16x2(bf16_lo(a.w) + dt * bf16_lo(b.w), bf16_hi(a.w) + dt * bf16_hi(b.w));
+        out[i] = o;
+    }
+}
+
+__global__ void __launch_bounds__(256) lvx_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+static int grid_for(size_t n_items) {
+    size_t g = (n_items + 255) / 256;
+    if (g > 256 * 32) g = 256 * 32;
+    if (g == 0) g = 1;
+    return (int)g;
+}
+
+lvx_status_t lvx_launch_axpy(const bf16_t *x, const bf16_t *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream) {
+    const size_t n16 = n_elems / 8;
+    hipLaunchKernelGGL(lvx_axpy_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (const uint4 *)x, (const uint4 *)h, dt,
+                       (uint4 *)out, n16);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return LVX_OK;
+    hipLaunchKernelGGL(lvx_fill_zero_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (uint4 *)dst, n16);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_copy(const bf16_t *src, bf16_t *dst, size_t n_elems, hipStream_t stream) {
+    const size_t n16 = n_elems / 8;
+    hipLaunchKernelGGL(lvx_copy_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (const uint4 *)src, (uint4 *)dst, n16);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, int n, int H, int D, int cap, int key0,
+                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream) {
+    if (n <= 0) return LVX_OK;
+    const int tile0 = key0 / LVX_KEY_TILE;
+    const int tile1 = (key0 + n - 1) / LVX_KEY_TILE;
+    dim3 grid(tile1 - tile0 + 1, H);
+    if (D == 128)
+        hipLaunchKernelGGL(lvx_pack_kv_kernel<128>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed);
+    else if (D == 64)
+        hipLaunchKernelGGL(lvx_pack_kv_kernel<64>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed);
+    else
+        return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+// ------------------------------------------------------------------------------------------------ host logic
+static lvx_status_t check_desc(const lvx_cache_desc_t *d) {
+    LVX_REQUIRE(d != nullptr, LVX_ERR_INVALID_ARG, "cache descriptor is NULL");
+    LVX_REQUIRE(d->n_layers > 0 && d->n_heads > 0 && d->frame_h > 0 && d->frame_w > 0 && d->chunk_frames > 0 &&
+                    d->window_chunks >= 0 && d->sink_frames >= 0,
+                LVX_ERR_SHAPE, "cache descriptor has a non-positive size");
+    LVX_REQUIRE(d->head_dim == 64 || d->head_dim == 128, LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", d->head_dim);
+    LVX_REQUIRE(d->window_chunks + 1 <= LVX_MAX_SLOTS, LVX_ERR_UNSUPPORTED, "window_chunks+1 exceeds %d slots", LVX_MAX_SLOTS);
+    const int64_t cap = (int64_t)d->frame_h * d->frame_w * ((int64_t)d->sink_frames + (int64_t)d->chunk_frames * (d->window_chunks + 1));
+    LVX_REQUIRE(cap < (1ll << 30), LVX_ERR_SHAPE, "cache too large: %lld keys per head", (long long)cap);
+    return LVX_OK;
+}
+
+static int cap_keys_of(const lvx_cache_desc_t *d) {
+    const int fk = d->frame_h * d->frame_w;
+    const int total = fk * (d->sink_frames + d->chunk_frames * (d->window_chunks + 1));
+    return (total + LVX_KEY_TILE - 1) / LVX_KEY_TILE * LVX_KEY_TILE;
+}
+
+extern "C" size_t lvx_kvcache_bytes(const lvx_cache_desc_t *desc) {
+    if (check_desc(desc) != LVX_OK) return 0;
+    return (size_t)2 * sizeof(bf16_t) * desc->n_layers * desc->n_heads * (size_t)cap_keys_of(desc) * desc->head_dim;
+}
+
+extern "C" lvx_status_t lvx_ring_slot(const lvx_cache_desc_t *desc, int64_t chunk_index, lvx_slot_info_t *out) {
+    lvx_status_t st = check_desc(desc);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(out != nullptr, LVX_ERR_INVALID_ARG, "out is NULL");
+    LVX_REQUIRE(chunk_index >= 0, LVX_ERR_INVALID_ARG, "chunk_index %lld is negative", (long long)chunk_index);
+    const int n_slots = desc->window_chunks + 1;
+    const int fk = desc->frame_h * desc->frame_w;
+    const int sink_keys = fk * desc->sink_frames, chunk_keys = fk * desc->chunk_frames;
+    out->slot = (int32_t)(chunk_index % n_slots);
+    out->evicted_chunk = chunk_index >= n_slots ? chunk_index - n_slots : -1;
+    out->n_valid_chunks = (int32_t)(chunk_index + 1 < n_slots ? chunk_index + 1 : n_slots);
+    out->key_offset = sink_keys + out->slot * chunk_keys;
+    out->key_count = sink_keys + out->n_valid_chunks * chunk_keys;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_init(const lvx_cache_desc_t *desc, void *dev_storage, size_t bytes, lvx_stream_t stream,
+                                         lvx_kvcache_t **out) {
+    lvx_status_t st = check_desc(desc);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(out != nullptr, LVX_ERR_INVALID_ARG, "out handle pointer is NULL");
+    LVX_REQUIRE(dev_storage != nullptr, LVX_ERR_INVALID_ARG, "dev_storage is NULL");
+    LVX_REQUIRE((((uintptr_t)dev_storage) & 255u) == 0, LVX_ERR_INVALID_ARG, "dev_storage must be 256-byte aligned");
+    const size_t need = lvx_kvcache_bytes(desc);
+    LVX_REQUIRE(bytes >= need, LVX_ERR_SHAPE, "cache storage too small: %zu bytes given, %zu needed", bytes, need);
+
+    lvx_kvcache *c = new (std::nothrow) lvx_kvcache;
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "out of host memory");
+    c->desc = *desc;
+    const int fk = desc->frame_h * desc->frame_w;
+    c->sink_keys = fk * desc->sink_frames;
+    c->chunk_keys = fk * desc->chunk_frames;
+    c->n_slots = desc->window_chunks + 1;
+    c->cap_keys = cap_keys_of(desc);
+    c->layer_k_elems = (size_t)desc->n_heads * c->cap_keys * desc->head_dim;
+    c->k_base = (bf16_t *)dev_storage;
+    c->vt_base = c->k_base + c->layer_k_elems * desc->n_layers;
+    c->state = new (std::nothrow) lvx_ring_state_t[desc->n_layers];
+    if (!c->state) {
+        delete c;
+        return lvx_fail(LVX_ERR_INVALID_ARG, "out of host memory");
+    }
+    for (int l = 0; l < desc->n_layers; ++l) {
+        lvx_ring_state_t &s = c->state[l];
+        memset(&s, 0, sizeof(s));
+        s.last_chunk = -1;
+        s.n_slots = c->n_slots;
+        s.key_count = 0;
+        for (int i = 0; i < LVX_MAX_SLOTS; ++i) s.slot_chunk[i] = -1;
+    }
+    const size_t n16 = need / 16;
+    hipLaunchKernelGGL(lvx_fill_zero_kernel, dim3(grid_for(n16)), dim3(256), 0, (hipStream_t)stream, (uint4 *)dev_storage, n16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete[] c->state;
+        delete c;
+        return lvx_fail(LVX_ERR_HIP, "zero fill launch: %s", hipGetErrorString(e));
+    }
+    *out = c;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_destroy(lvx_kvcache_t *cache) {
+    LVX_REQUIRE(cache != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    delete[] cache->state;
+    delete cache;
+    return LVX_OK;
+}
+
+static lvx_status_t check_layer_and_rows(const lvx_kvcache *c, int32_t layer, const void *k, const void *v, int64_t ld) {
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(k != nullptr && v != nullptr, LVX_ERR_INVALID_ARG, "K or V pointer is NULL");
+    LVX_REQUIRE(lvx_aligned16(k) && lvx_aligned16(v), LVX_ERR_INVALID_ARG, "K and V must be 16-byte aligned");
+    LVX_REQUIRE(ld >= (int64_t)c->desc.n_heads * c->desc.head_dim && ld % 8 == 0, LVX_ERR_SHAPE,
+                "row stride %lld must be a multiple of 8 and >= n_heads*head_dim", (long long)ld);
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_set_sink(lvx_kvcache_t *c, int32_t layer, const void *dev_k, const void *dev_v, int64_t ld,
+                                             lvx_stream_t stream) {
+    lvx_status_t st = check_layer_and_rows(c, layer, dev_k, dev_v, ld);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(c->sink_keys > 0, LVX_ERR_STATE, "this cache has no sink segment (sink_frames = 0)");
+    st = lvx_launch_pack_kv((const bf16_t *)dev_k, (const bf16_t *)dev_v, ld, c->sink_keys, c->desc.n_heads, c->desc.head_dim,
+                            c->cap_keys, 0, (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer), (hipStream_t)stream);
+    if (st != LVX_OK) return st;
+    lvx_ring_state_t &s = c->state[layer];
+    s.sink_set = 1;
+    s.key_count = c->sink_keys + s.n_valid_chunks * c->chunk_keys;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_chunk_append_evict(lvx_kvcache_t *c, int32_t layer, const void *dev_k, const void *dev_v, int64_t ld,
+                                               int64_t chunk_index, lvx_slot_info_t *out, lvx_stream_t stream) {
+    lvx_status_t st = check_layer_and_rows(c, layer, dev_k, dev_v, ld);
+    if (st != LVX_OK) return st;
+    lvx_ring_state_t &s = c->state[layer];
+    LVX_REQUIRE(chunk_index == s.last_chunk + 1, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", layer,
+                (long long)(s.last_chunk + 1), (long long)chunk_index);
+    LVX_REQUIRE(c->sink_keys == 0 || s.sink_set, LVX_ERR_STATE, "layer %d: sink not set before the first append", layer);
+    lvx_slot_info_t info;
+    st = lvx_ring_slot(&c->desc, chunk_index, &info);
+    if (st != LVX_OK) return st;
+    st = lvx_launch_pack_kv((const bf16_t *)dev_k, (const bf16_t *)dev_v, ld, c->chunk_keys, c->desc.n_heads, c->desc.head_dim,
+                            c->cap_keys, info.key_offset, (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer),
+                            (hipStream_t)stream);
+    if (st != LVX_OK) return st;
+    s.last_chunk = chunk_index;
+    s.slot_chunk[info.slot] = chunk_index;
+    s.n_valid_chunks = info.n_valid_chunks;
+    s.key_count = info.key_count;
+    if (out) *out = info;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_get_state(const lvx_kvcache_t *c, int32_t layer, lvx_ring_state_t *out) {
+    LVX_REQUIRE(c != nullptr && out != nullptr, LVX_ERR_INVALID_ARG, "cache handle or out is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    *out = c->state[layer];
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_set_state(lvx_kvcache_t *c, int32_t layer, const lvx_ring_state_t *in) {
+    LVX_REQUIRE(c != nullptr && in != nullptr, LVX_ERR_INVALID_ARG, "cache handle or state is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(in->n_slots == c->n_slots, LVX_ERR_SHAPE, "state has %d slots, cache has %d", in->n_slots, c->n_slots);
+    LVX_REQUIRE(in->last_chunk >= -1, LVX_ERR_STATE, "state.last_chunk %lld invalid", (long long)in->last_chunk);
+    // the bookkeeping must be what the ring arithmetic yields for last_chunk
+    const int64_t n_valid = in->last_chunk + 1 < c->n_slots ? in->last_chunk + 1 : c->n_slots;
+    LVX_REQUIRE(in->n_valid_chunks == n_valid, LVX_ERR_STATE, "state.n_valid_chunks %d inconsistent with last_chunk", in->n_valid_chunks);
+    LVX_REQUIRE(in->key_count == (in->sink_set ? c->sink_keys : 0) + (int)n_valid * c->chunk_keys, LVX_ERR_STATE,
+                "state.key_count %d inconsistent", in->key_count);
+    for (int sl = 0; sl < c->n_slots; ++sl) {
+        int64_t want = -1;
+        for (int64_t j = in->last_chunk; j >= 0 && j > in->last_chunk - c->n_slots; --j)
+            if (j % c->n_slots == sl) want = j;
+        LVX_REQUIRE(in->slot_chunk[sl] == want, LVX_ERR_STATE, "state.slot_chunk[%d] = %lld, ring arithmetic gives %lld", sl,
+                    (long long)in->slot_chunk[sl], (long long)want);
+    }
+    c->state[layer] = *in;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_gather(const lvx_kvcache_t *c, int32_t layer, int32_t first_key, int32_t n_keys, void *dev_k_out,
+                                           void *dev_v_out, int64_t ld, lvx_stream_t stream) {
+    lvx_status_t st = check_layer_and_rows(c, layer, dev_k_out, dev_v_out, ld);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(first_key >= 0 && n_keys >= 0 && (int64_t)first_key + n_keys <= c->cap_keys, LVX_ERR_SHAPE,
+                "key range [%d,%d) outside the cache (%d keys)", first_key, first_key + n_keys, c->cap_keys);
+    if (n_keys == 0) return LVX_OK;
+    const size_t total = (size_t)n_keys * c->desc.n_heads * (c->desc.head_dim / 8);
+    if (c->desc.head_dim == 128)
+        hipLaunchKernelGGL(lvx_gather_kv_kernel<128>, dim3(grid_for(total)), dim3(256), 0, (hipStream_t)stream, lvx_cache_k(c, layer),
+                           lvx_cache_vt(c, layer), c->cap_keys, c->desc.n_heads, first_key, n_keys, (bf16_t *)dev_k_out,
+                           (bf16_t *)dev_v_out, ld);
+    else
+        hipLaunchKernelGGL(lvx_gather_kv_kernel<64>, dim3(grid_for(total)), dim3(256), 0, (hipStream_t)stream, lvx_cache_k(c, layer),
+                           lvx_cache_vt(c, layer), c->cap_keys, c->desc.n_heads, first_key, n_keys, (bf16_t *)dev_k_out,
+                           (bf16_t *)dev_v_out, ld);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}

@@ -1,0 +1,72 @@
+// Internal declarations shared by the lvx translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+
+#include "lvx.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+
+#define LVX_KEY_TILE 64  // keys per V^T tile in the cache and per LDS stage of the attention kernel
+
+lvx_status_t lvx_fail(lvx_status_t code, const char *fmt, ...);
+
+#define LVX_CHECK_HIP(expr)                                                                      \
+    do {                                                                                         \
+        hipError_t e_ = (expr);                                                                  \
+        if (e_ != hipSuccess) return lvx_fail(LVX_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define LVX_REQUIRE(cond, code, ...)                         \
+    do {                                                     \
+        if (!(cond)) return lvx_fail((code), __VA_ARGS__);   \
+    } while (0)
+
+static inline bool lvx_aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// ---- device helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+// round-to-nearest-even pack of two floats into two bf16 (lo = a, hi = b); maps to v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    bf16x2_t r;
+    r[0] = (__bf16)a;
+    r[1] = (__bf16)b;
+    return *reinterpret_cast<uint32_t *>(&r);
+}
+
+// ---- cache handle (host) ----------------------------------------------------------------------
+struct lvx_kvcache {
+    lvx_cache_desc_t desc;
+    int32_t sink_keys, chunk_keys, n_slots, cap_keys;  // cap_keys: capacity per head, multiple of LVX_KEY_TILE
+    size_t layer_k_elems;                              // elements of K (= of V^T) per layer
+    bf16_t *k_base;                                    // [layer][head][cap_keys][D]
+    bf16_t *vt_base;                                   // [layer][head][cap_keys/64][D][64]
+    lvx_ring_state_t *state;                           // [n_layers]
+};
+
+static inline const bf16_t *lvx_cache_k(const lvx_kvcache *c, int layer) { return c->k_base + (size_t)layer * c->layer_k_elems; }
+static inline const bf16_t *lvx_cache_vt(const lvx_kvcache *c, int layer) { return c->vt_base + (size_t)layer * c->layer_k_elems; }
+
+// ---- internal launchers (all enqueue on `stream`, arguments already validated) ----------------
+// Token-major K/V rows [n][ld] -> packed K [H][cap][D] rows key0.. and V^T tiles [H][cap/64][D][64].
+lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, int n, int H, int D, int cap, int key0,
+                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream);
+// Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
+lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
+                                  const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
+                                  hipStream_t stream);
+lvx_status_t lvx_launch_axpy(const bf16_t *x, const bf16_t *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
+// Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
+lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);
+lvx_status_t lvx_launch_copy(const bf16_t *src, bf16_t *dst, size_t n_elems, hipStream_t stream);

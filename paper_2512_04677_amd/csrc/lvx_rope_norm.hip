@@ -1,0 +1,257 @@
+// HBM-bound row kernels: fused Q/K RMSNorm + 3-D rotary embedding, and LayerNorm + modulation.
+//
+// One 64-lane wave owns one token row (all heads), four rows per workgroup, no LDS and no barriers: the row is
+// read once with 16-byte loads, kept in registers, reduced with wave shuffles, transformed and written once.
+// Rotary indices count latent frames and reach ~4e4 in long rollouts (paper Appendix D, "Rolling RoPE"; Sec. 4.3
+// 10 000 s experiment), where an fp32 product pos*freq already loses ~1e-3 rad, so each token's head_dim/2 angles
+// are formed and reduced in fp64 (one per lane, shared by all heads and by q and k) and only the resulting
+// sin/cos are kept in fp32.
+#include "lvx_internal.h"
+
+#include <math.h>
+
+namespace {
+
+struct rope_table_t {
+    double inv_freq[64];  // theta^(-2k/d_a) of pair p (p = global pair index inside the head)
+    int32_t axis[64];     // 0 = t, 1 = y, 2 = x
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m);
+    return v;
+}
+
+constexpr int ROWS_PER_WG = 4;
+
+// CPL = 16-byte chunks per lane (row length <= 64*8*CPL)
+template <int CPL>
+__global__ void __launch_bounds__(64 * ROWS_PER_WG)
+    lvx_rope_norm_kernel(const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in,
+                         const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
+                         bf16_t *k_out, int64_t ld_out, int d_model, int head_dim, int frame_h, int frame_w, float eps,
+                         int apply_rope, rope_table_t tab) {
+    const int lane = threadIdx.x & 63;
+    const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
+    if (token >= n_tokens) return;
+    const int n_chunks = d_model / 8;
+    const int cph = head_dim / 8;  // chunks per head: 8 or 16, divides 64, so (lane + 64 j) % cph == lane % cph
+
+    float cs = 1.f, sn = 0.f;
+    if (apply_rope && lane < head_dim / 2) {
+        const int ax = tab.axis[lane];
+        const int pos = ax == 0 ? t0 + token / (frame_h * frame_w) : (ax == 1 ? (token / frame_w) % frame_h : token % frame_w);
+        double s, c;
+        sincos((double)pos * tab.inv_freq[lane], &s, &c);
+        cs = (float)c;
+        sn = (float)s;
+    }
+    float c4[4], s4[4];
+    const int p0 = (lane % cph) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        c4[j] = __shfl(cs, p0 + j);
+        s4[j] = __shfl(sn, p0 + j);
+    }
+
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const bf16_t *in = which == 0 ? q_in : k_in;
+        bf16_t *outp = which == 0 ? q_out : k_out;
+        const float *g = which == 0 ? g_q : g_k;
+        if (in == nullptr) continue;
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(in + (size_t)token * ld_in);
+        u32x4_t x[CPL];
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int c = lane + 64 * j;
+            if (c < n_chunks) {
+                x[j] = src[c];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = bf16_lo(x[j][e]), b = bf16_hi(x[j][e]);
+                    ss += a * a + b * b;
+                }
+            }
+        }
+        float rinv = 1.f;
+        if (g != nullptr) {
+            ss = wave_sum(ss);
+            rinv = 1.0f / sqrtf(ss / (float)d_model + eps);
+        }
+        u32x4_t *dst = reinterpret_cast<u32x4_t *>(outp + (size_t)token * ld_out);
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int c = lane + 64 * j;
+            if (c < n_chunks) {
+                float4 g0 = make_float4(1.f, 1.f, 1.f, 1.f), g1 = g0;
+                if (g != nullptr) {
+                    g0 = *reinterpret_cast<const float4 *>(g + c * 8);
+                    g1 = *reinterpret_cast<const float4 *>(g + c * 8 + 4);
+                }
+                const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                u32x4_t y;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = bf16_lo(x[j][e]) * rinv * gg[2 * e];
+                    const float b = bf16_hi(x[j][e]) * rinv * gg[2 * e + 1];
+                    y[e] = pack_bf16x2(a * c4[e] - b * s4[e], a * s4[e] + b * c4[e]);
+                }
+                dst[c] = y;
+            }
+        }
+    }
+}
+
+template <int CPL>
+__global__ void __launch_bounds__(64 * ROWS_PER_WG)
+    lvx_layernorm_modulate_kernel(const bf16_t *__restrict__ x_in, int64_t ldx, const float *__restrict__ shift,
+                                  const float *__restrict__ scale, float eps, int n_tokens, int d, bf16_t *__restrict__ u_out,
+                                  int64_t ldu) {
+    const int lane = threadIdx.x & 63;
+    const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
+    if (token >= n_tokens) return;
+    const int n_chunks = d / 8;
+    const u32x4_t *src = reinterpret_cast<const u32x4_t *>(x_in + (size_t)token * ldx);
+    u32x4_t x[CPL];
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < n_chunks) {
+            x[j] = src[c];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum += bf16_lo(x[j][e]) + bf16_hi(x[j][e]);
+        }
+    }
+    const float mean = wave_sum(sum) / (float)d;
+    float sq = 0.f;
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < n_chunks) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = bf16_lo(x[j][e]) - mean, b = bf16_hi(x[j][e]) - mean;
+                sq += a * a + b * b;
+            }
+        }
+    }
+    const float rinv = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
+    u32x4_t *dst = reinterpret_cast<u32x4_t *>(u_out + (size_t)token * ldu);
+#pragma unroll
+    for (int j = 0; j < CPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < n_chunks) {
+            float sc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sh[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (scale != nullptr) {
+                const float4 a = *reinterpret_cast<const float4 *>(scale + c * 8), b = *reinterpret_cast<const float4 *>(scale + c * 8 + 4);
+                sc[0] = a.x, sc[1] = a.y, sc[2] = a.z, sc[3] = a.w, sc[4] = b.x, sc[5] = b.y, sc[6] = b.z, sc[7] = b.w;
+            }
+            if (shift != nullptr) {
+                const float4 a = *reinterpret_cast<const float4 *>(shift + c * 8), b = *reinterpret_cast<const float4 *>(shift + c * 8 + 4);
+                sh[0] = a.x, sh[1] = a.y, sh[2] = a.z, sh[3] = a.w, sh[4] = b.x, sh[5] = b.y, sh[6] = b.z, sh[7] = b.w;
+            }
+            u32x4_t y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = (bf16_lo(x[j][e]) - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
+                const float b = (bf16_hi(x[j][e]) - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
+                y[e] = pack_bf16x2(a, b);
+            }
+            dst[c] = y;
+        }
+    }
+}
+
+}  // namespace
+
+static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
+    LVX_REQUIRE(r != nullptr, LVX_ERR_INVALID_ARG, "rope descriptor is NULL");
+    LVX_REQUIRE(r->n_heads > 0 && r->frame_h > 0 && r->frame_w > 0, LVX_ERR_SHAPE, "rope descriptor has a non-positive size");
+    LVX_REQUIRE(r->head_dim == 64 || r->head_dim == 128, LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", r->head_dim);
+    if (r->apply_rope) {
+        LVX_REQUIRE(r->axes[0] >= 0 && r->axes[1] >= 0 && r->axes[2] >= 0 && r->axes[0] % 2 == 0 && r->axes[1] % 2 == 0 &&
+                        r->axes[2] % 2 == 0 && r->axes[0] + r->axes[1] + r->axes[2] == r->head_dim,
+                    LVX_ERR_SHAPE, "rope axes (%d,%d,%d) must be even and sum to head_dim %d", r->axes[0], r->axes[1], r->axes[2],
+                    r->head_dim);
+        LVX_REQUIRE(r->theta > 1.f, LVX_ERR_INVALID_ARG, "rope theta must be > 1");
+    }
+    LVX_REQUIRE((int64_t)r->n_heads * r->head_dim <= 64 * 8 * 16, LVX_ERR_UNSUPPORTED, "n_heads*head_dim %lld exceeds 8192",
+                (long long)r->n_heads * r->head_dim);
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
+                                   const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
+                                   void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
+    lvx_status_t st = check_rope_desc(desc);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(dev_q_in != nullptr || dev_k_in != nullptr, LVX_ERR_INVALID_ARG, "both q and k are NULL");
+    LVX_REQUIRE((dev_q_in == nullptr) == (dev_q_out == nullptr) && (dev_k_in == nullptr) == (dev_k_out == nullptr), LVX_ERR_INVALID_ARG,
+                "each input needs its output pointer");
+    LVX_REQUIRE(lvx_aligned16(dev_q_in) && lvx_aligned16(dev_k_in) && lvx_aligned16(dev_q_out) && lvx_aligned16(dev_k_out) &&
+                    lvx_aligned16(dev_g_q) && lvx_aligned16(dev_g_k),
+                LVX_ERR_INVALID_ARG, "pointers must be 16-byte aligned");
+    const int d = desc->n_heads * desc->head_dim;
+    LVX_REQUIRE(ld_in >= d && ld_in % 8 == 0 && ld_out >= d && ld_out % 8 == 0, LVX_ERR_SHAPE,
+                "row strides must be multiples of 8 and >= n_heads*head_dim");
+    LVX_REQUIRE(n_tokens >= 0 && t0 >= 0, LVX_ERR_INVALID_ARG, "n_tokens and t0 must be non-negative");
+    if (n_tokens == 0) return LVX_OK;
+
+    rope_table_t tab;
+    for (int p = 0; p < 64; ++p) {
+        tab.inv_freq[p] = 0.0;
+        tab.axis[p] = 0;
+    }
+    if (desc->apply_rope) {
+        int p = 0;
+        for (int ax = 0; ax < 3; ++ax)
+            for (int k = 0; k < desc->axes[ax] / 2; ++k, ++p) {
+                tab.inv_freq[p] = pow((double)desc->theta, -2.0 * k / (double)desc->axes[ax]);
+                tab.axis[p] = ax;
+            }
+    }
+    const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
+    const int cpl = (d / 8 + 63) / 64;
+#define LVX_ROPE_LAUNCH(CPL)                                                                                                      \
+    hipLaunchKernelGGL(lvx_rope_norm_kernel<CPL>, grid, block, 0, (hipStream_t)stream, (const bf16_t *)dev_q_in,                 \
+                       (const bf16_t *)dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out, (bf16_t *)dev_k_out, \
+                       ld_out, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab)
+    if (cpl <= 2)
+        LVX_ROPE_LAUNCH(2);
+    else if (cpl <= 10)
+        LVX_ROPE_LAUNCH(10);
+    else
+        LVX_ROPE_LAUNCH(16);
+#undef LVX_ROPE_LAUNCH
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale, float eps,
+                                               int32_t n_tokens, int32_t d, void *dev_u, int64_t ldu, lvx_stream_t stream) {
+    LVX_REQUIRE(dev_x != nullptr && dev_u != nullptr, LVX_ERR_INVALID_ARG, "x or u is NULL");
+    LVX_REQUIRE(lvx_aligned16(dev_x) && lvx_aligned16(dev_u) && lvx_aligned16(dev_shift) && lvx_aligned16(dev_scale), LVX_ERR_INVALID_ARG,
+                "pointers must be 16-byte aligned");
+    LVX_REQUIRE(d > 0 && d % 8 == 0 && d <= 64 * 8 * 16, LVX_ERR_SHAPE, "d %d must be a positive multiple of 8, at most 8192", d);
+    LVX_REQUIRE(ldx >= d && ldx % 8 == 0 && ldu >= d && ldu % 8 == 0, LVX_ERR_SHAPE, "row strides must be multiples of 8 and >= d");
+    LVX_REQUIRE(n_tokens >= 0, LVX_ERR_INVALID_ARG, "n_tokens must be non-negative");
+    if (n_tokens == 0) return LVX_OK;
+    const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
+    const int cpl = (d / 8 + 63) / 64;
+#define LVX_LN_LAUNCH(CPL)                                                                                                         \
+    hipLaunchKernelGGL(lvx_layernorm_modulate_kernel<CPL>, grid, block, 0, (hipStream_t)stream, (const bf16_t *)dev_x, ldx, dev_shift, \
+                       dev_scale, eps, n_tokens, d, (bf16_t *)dev_u, ldu)
+    if (cpl <= 2)
+        LVX_LN_LAUNCH(2);
+    else if (cpl <= 10)
+        LVX_LN_LAUNCH(10);
+    else
+        LVX_LN_LAUNCH(16);
+#undef LVX_LN_LAUNCH
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}

@@ -1,0 +1,295 @@
+"""GPU parity: every entry point of liblvx.so against the fp64 CPU oracle on the same seeded inputs, through the C ABI.
+
+Tolerances (activations, bf16 in / fp32 accumulate): max-abs 2e-2 and mean-abs 2e-3, as the build's contract states.
+Outputs whose magnitude exceeds bf16's resolution at that tolerance (the residual stream of a block, |x| >= 8 has a
+half-ulp of 0.031) are gated on the same two numbers divided by the oracle output's RMS; both forms are asserted
+where they apply.  Cache indices and cache contents are compared bit-exactly.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import lvx_synth as S
+from oracle import lvx_oracle as O
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+MAX_ABS, MEAN_ABS = 2e-2, 2e-3
+
+
+def errs(gpu, ref):
+    g = S.to_f64(gpu) if isinstance(gpu, torch.Tensor) else gpu
+    d = np.abs(g.reshape(ref.shape) - ref)
+    return d.max(), d.mean()
+
+
+def assert_close(gpu, ref, what, relative_to_rms=False):
+    mx, mn = errs(gpu, ref)
+    unit = math.sqrt(float((ref ** 2).mean())) if relative_to_rms else 1.0
+    print("%s: max-abs %.3e mean-abs %.3e (unit %.3g)" % (what, mx / unit, mn / unit, unit), flush=True)
+    assert np.isfinite(S.to_f64(gpu)).all(), what
+    assert mx / unit <= MAX_ABS, (what, mx, unit)
+    assert mn / unit <= MEAN_ABS, (what, mn, unit)
+
+
+def make_cache(lvx, p, n_layers=1):
+    desc = lvx.cache_desc(n_layers, p["n_heads"], p["head_dim"], p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"],
+                          p["sink_frames"])
+    return lvx.KVCache(desc, DEV)
+
+
+def dims(p):
+    d = p["n_heads"] * p["head_dim"]
+    fk = p["frame_h"] * p["frame_w"]
+    return d, fk * p["sink_frames"], fk * p["chunk_frames"]
+
+
+# ------------------------------------------------------------------------------------------------ cache
+@pytest.mark.parametrize("preset", ["tiny", "small"])
+def test_ring_append_evict_bit_exact(lvx, preset):
+    """Streaming appends: slot indices equal the list-protocol model at every step and every cache row equals, bit for
+    bit, the row that was appended for the chunk the model says lives there; the sink never changes."""
+    p = S.PRESETS[preset]
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    cache = make_cache(lvx, p)
+    sink_k = S.randn_bf16((sink_n, d), S.seed_of(preset, "sink_k"), device=DEV)
+    sink_v = S.randn_bf16((sink_n, d), S.seed_of(preset, "sink_v"), device=DEV)
+    lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+    model = O.RollingKVCache(W)
+    model.set_sink(S.to_f64(sink_k).reshape(sink_n, H, D), S.to_f64(sink_v).reshape(sink_n, H, D))
+    chunks = {}
+    cap = sink_n + (W + 1) * chunk_n
+    for i in range(3 * (W + 1) + 2):
+        k = S.randn_bf16((chunk_n, d), S.seed_of(preset, "k", i), device=DEV)
+        v = S.randn_bf16((chunk_n, d), S.seed_of(preset, "v", i), device=DEV)
+        chunks[i] = (k, v)
+        visible = model.chunk_ids() + [i]
+        info = lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        st = lvx.lvx_kvcache_get_state(cache, 0)
+        assert info.slot == i % (W + 1) and st.last_chunk == i
+        assert sorted(c for c in st.slot_chunk[:st.n_slots] if c >= 0) == visible
+        assert st.key_count == info.key_count == sink_n + len(visible) * chunk_n
+        model.append(i, S.to_f64(k).reshape(chunk_n, H, D), S.to_f64(v).reshape(chunk_n, H, D))
+        gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+        gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+        lvx.lvx_kvcache_gather(cache, 0, 0, cap, gk, gv)
+        torch.cuda.synchronize()
+        assert torch.equal(gk[:sink_n].view(torch.int16), sink_k.view(torch.int16))
+        assert torch.equal(gv[:sink_n].view(torch.int16), sink_v.view(torch.int16))
+        for s in range(st.n_slots):
+            c = st.slot_chunk[s]
+            if c < 0:
+                continue
+            sl = slice(sink_n + s * chunk_n, sink_n + (s + 1) * chunk_n)
+            assert torch.equal(gk[sl].view(torch.int16), chunks[c][0].view(torch.int16)), (i, s)
+            assert torch.equal(gv[sl].view(torch.int16), chunks[c][1].view(torch.int16)), (i, s)
+    # out-of-sequence append is refused and changes nothing
+    with pytest.raises(lvx.LvxError) as e:
+        lvx.lvx_chunk_append_evict(cache, 0, k, v, i + 2)
+    assert e.value.status == 3
+    assert lvx.lvx_kvcache_get_state(cache, 0).last_chunk == i
+    # state save / restore round trip
+    st = lvx.lvx_kvcache_get_state(cache, 0)
+    lvx.lvx_kvcache_set_state(cache, 0, st)
+    bad = lvx.lvx_kvcache_get_state(cache, 0)
+    bad.slot_chunk[0] = 12345
+    with pytest.raises(lvx.LvxError):
+        lvx.lvx_kvcache_set_state(cache, 0, bad)
+    cache.close()
+
+
+# ------------------------------------------------------------------------------------------------ attention
+def stream_attention(lvx, preset, n_steps, scale_mult=1.0, std=1.0):
+    p = S.PRESETS[preset]
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    scale = scale_mult / math.sqrt(D)
+    cache = make_cache(lvx, p)
+    sink_k = S.randn_bf16((sink_n, d), S.seed_of(preset, "a_sink_k"), std, device=DEV)
+    sink_v = S.randn_bf16((sink_n, d), S.seed_of(preset, "a_sink_v"), device=DEV)
+    lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+    model = O.RollingKVCache(W)
+    model.set_sink(S.to_f64(sink_k).reshape(sink_n, H, D), S.to_f64(sink_v).reshape(sink_n, H, D))
+    for i in range(n_steps):
+        q = S.randn_bf16((chunk_n, d), S.seed_of(preset, "a_q", i), std, device=DEV)
+        k = S.randn_bf16((chunk_n, d), S.seed_of(preset, "a_k", i), std, device=DEV)
+        v = S.randn_bf16((chunk_n, d), S.seed_of(preset, "a_v", i), device=DEV)
+        out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+        lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        torch.cuda.synchronize()
+        ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
+                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "%s attention step %d (scale x%g)" % (preset, i, scale_mult))
+    cache.close()
+
+
+def test_attention_config1_tiny(lvx):
+    """Config 1: 2 heads x 64, 48 queries, keys = 24 sink + 2 past chunks + self = 168 at step 2 (ragged 64-key tiles,
+    partial query tile); steps 0 and 1 are the warm-up key counts 72 and 120."""
+    stream_attention(lvx, "tiny", 5)
+
+
+def test_attention_small_streaming_warmup_and_eviction(lvx):
+    """head_dim 128, chunk 105 tokens (not a multiple of 8): key counts 140..560, eviction from step 5."""
+    stream_attention(lvx, "small", 8)
+
+
+def test_attention_peaked_logits(lvx):
+    """Logit std ~8 (scale x8): the running maximum moves a lot, exercising the rescale branch."""
+    stream_attention(lvx, "small", 3, scale_mult=8.0)
+    stream_attention(lvx, "tiny", 3, scale_mult=0.01)     # near-uniform softmax
+
+
+def test_attention_special_cases(lvx):
+    """All V rows equal -> output is that row; a single dominant key -> its V."""
+    p = S.PRESETS["small"]
+    d, sink_n, chunk_n = dims(p)
+    H, D = p["n_heads"], p["head_dim"]
+    cache = make_cache(lvx, p)
+    vrow = S.randn_bf16((1, d), 7, device=DEV)
+    sink_k = S.randn_bf16((sink_n, d), 8, device=DEV)
+    lvx.lvx_kvcache_set_sink(cache, 0, sink_k, vrow.expand(sink_n, d).contiguous())
+    k = S.randn_bf16((chunk_n, d), 9, device=DEV)
+    q = S.randn_bf16((chunk_n, d), 10, device=DEV)
+    out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+    lvx.lvx_chunk_append_evict(cache, 0, k, vrow.expand(chunk_n, d).contiguous(), 0)
+    lvx.lvx_chunk_attention(cache, 0, q, 1.0 / math.sqrt(D), out)
+    torch.cuda.synchronize()
+    assert_close(out, np.broadcast_to(S.to_f64(vrow), (chunk_n, d)), "equal-V rows")
+    cache.close()
+
+
+# ------------------------------------------------------------------------------------------------ rope / norms / linear
+@pytest.mark.parametrize("preset,t0", [("tiny", 0), ("small", 1), ("small", 40000)])
+def test_rope3d_rmsnorm(lvx, preset, t0):
+    p = S.PRESETS[preset]
+    d, _, n = dims(p)
+    H, D = p["n_heads"], p["head_dim"]
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    qkv = S.randn_bf16((n, 3 * d), S.seed_of(preset, "rope_qkv", t0), device=DEV)
+    gq = S.randn_f32((d,), 11, 0.1, 1.0, device=DEV)
+    gk = S.randn_f32((d,), 12, 0.1, 1.0, device=DEV)
+    ref_in = S.to_f64(qkv)
+    qo = torch.empty((n, d), dtype=torch.bfloat16, device=DEV)
+    ko = torch.empty((n, d), dtype=torch.bfloat16, device=DEV)
+    lvx.lvx_rope3d(rope, qkv[:, :d], qkv[:, d:2 * d], gq, gk, n, t0, qo, ko, ld_in=3 * d)
+    torch.cuda.synchronize()
+    for out, col, g in ((qo, 0, gq), (ko, d, gk)):
+        x = O.rmsnorm(ref_in[:, col:col + d], S.to_f64(g), 1e-6)
+        ref = O.rope3d(x.reshape(n, H, D), t0, p["frame_h"], p["frame_w"], p["rope_axes"], 10000.0)
+        assert_close(out, ref.reshape(n, d), "rope+rmsnorm %s t0=%d" % (preset, t0))
+    # no gains = rotation only; in place inside the fused QKV buffer; V columns untouched
+    v_before = qkv[:, 2 * d:].clone()
+    lvx.lvx_rope3d(rope, qkv[:, :d], qkv[:, d:2 * d], None, None, n, t0, qkv[:, :d], qkv[:, d:2 * d], ld_in=3 * d, ld_out=3 * d)
+    torch.cuda.synchronize()
+    ref = O.rope3d(ref_in[:, :d].reshape(n, H, D), t0, p["frame_h"], p["frame_w"], p["rope_axes"], 10000.0)
+    assert_close(qkv[:, :d].contiguous(), ref.reshape(n, d), "rope only, in place")
+    assert torch.equal(qkv[:, 2 * d:], v_before)
+    # norm only (cross-attention form), q alone
+    norm_only = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"], apply_rope=0)
+    x = S.randn_bf16((n, d), 13, 3.0, device=DEV)
+    y = torch.empty_like(x)
+    lvx.lvx_rope3d(norm_only, x, None, gq, None, n, 0, y, None)
+    torch.cuda.synchronize()
+    assert_close(y, O.rmsnorm(S.to_f64(x), S.to_f64(gq), 1e-6), "rmsnorm only")
+
+
+def test_layernorm_modulate(lvx):
+    for n, d in ((37, 128), (50, 512), (9, 5120)):
+        x = S.randn_bf16((n, d), S.seed_of("ln", n, d), 2.0, 0.5, device=DEV)
+        sh = S.randn_f32((d,), 1, 0.3, device=DEV)
+        sc = S.randn_f32((d,), 2, 0.3, device=DEV)
+        u = torch.empty_like(x)
+        lvx.lvx_layernorm_modulate(x, sh, sc, 1e-6, u)
+        torch.cuda.synchronize()
+        assert_close(u, O.modulate(S.to_f64(x), S.to_f64(sh), S.to_f64(sc), 1e-6), "layernorm+modulate %dx%d" % (n, d))
+        lvx.lvx_layernorm_modulate(x, None, None, 1e-6, u)
+        torch.cuda.synchronize()
+        assert_close(u, O.layernorm(S.to_f64(x), 1e-6), "layernorm %dx%d" % (n, d))
+
+
+@pytest.mark.parametrize("M,N,K", [(200, 320, 192), (48, 8, 64), (1000, 1536, 512), (129, 264, 128)])
+def test_linear_epilogues(lvx, M, N, K):
+    a = S.randn_bf16((M, K), S.seed_of("lin_a", M, N, K), device=DEV)
+    w = S.randn_bf16((N, K), S.seed_of("lin_w", M, N, K), 1.0 / math.sqrt(K), device=DEV)
+    r = S.randn_bf16((M, N), S.seed_of("lin_r", M, N, K), device=DEV)
+    g = S.randn_f32((N,), 5, 0.5, 1.0, device=DEV)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device=DEV)
+    ref = O.linear(S.to_f64(a), S.to_f64(w))
+    lvx.lvx_linear(a, w, c, lvx.EPI_STORE)
+    torch.cuda.synchronize()
+    assert_close(c, ref, "linear %dx%dx%d" % (M, N, K))
+    lvx.lvx_linear(a, w, c, lvx.EPI_GELU_TANH)
+    torch.cuda.synchronize()
+    assert_close(c, O.gelu_tanh(ref), "linear+gelu")
+    lvx.lvx_linear(a, w, c, lvx.EPI_RESID_GATE, resid=r, gate=g)
+    torch.cuda.synchronize()
+    assert_close(c, S.to_f64(r) + S.to_f64(g) * ref, "linear+gated residual")
+    r2 = r.clone()
+    lvx.lvx_linear(a, w, r2, lvx.EPI_RESID_GATE, resid=r2, gate=None)      # in place, gate = 1
+    torch.cuda.synchronize()
+    assert_close(r2, S.to_f64(r) + ref, "linear+residual in place")
+
+
+# ------------------------------------------------------------------------------------------------ block / stage
+def stage_setup(lvx, preset, n_layers, tag):
+    p = S.PRESETS[preset]
+    d, sink_n, chunk_n = dims(p)
+    H, D = p["n_heads"], p["head_dim"]
+    layers = [S.block_weights(d, p["ffn"], l, tag, std=1.0 / math.sqrt(d), device=DEV) for l in range(n_layers)]
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    cache = make_cache(lvx, p, n_layers)
+    cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"], p["rope_axes"])
+    models = []
+    for l in range(n_layers):
+        sk = S.randn_bf16((sink_n, d), S.seed_of(tag, "sink_k", l), device=DEV)
+        sv = S.randn_bf16((sink_n, d), S.seed_of(tag, "sink_v", l), device=DEV)
+        lvx.lvx_kvcache_set_sink(cache, l, sk, sv)
+        m = O.RollingKVCache(p["window"])
+        m.set_sink(S.to_f64(sk).reshape(sink_n, H, D), S.to_f64(sv).reshape(sink_n, H, D))
+        models.append(m)
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, chunk_n, p["n_ctx"]), dtype=torch.uint8, device=DEV)
+    return p, stage, cache, cfg, models, ws, [S.weights_to_f64(w) for w in layers]
+
+
+@pytest.mark.parametrize("preset", ["tiny", "small"])
+def test_dit_block_streaming(lvx, preset):
+    p, stage, cache, cfg, models, ws, w64 = stage_setup(lvx, preset, 1, "blk_" + preset)
+    d, _, n = dims(p)
+    for i in range(p["window"] + 3):
+        x = S.randn_bf16((n, d), S.seed_of(preset, "blk_x", i), device=DEV)
+        ctx = S.randn_bf16((p["n_ctx"], d), S.seed_of(preset, "blk_ctx", i), device=DEV)
+        mod6 = S.randn_f32((6, d), S.seed_of(preset, "blk_mod", i), 0.2, device=DEV)
+        mod6[2] += 1.0
+        mod6[5] += 1.0
+        m6 = None if i == 1 else mod6
+        x_ref = O.dit_block(S.to_f64(x), w64[0], models[0], S.to_f64(ctx), None if m6 is None else S.to_f64(m6), i, 1 + 3 * i, cfg)
+        lvx.lvx_dit_block(stage, 0, cache, x, ctx, m6, i, 1 + 3 * i, ws)
+        torch.cuda.synchronize()
+        assert_close(x, x_ref, "%s block step %d" % (preset, i), relative_to_rms=True)
+    cache.close()
+
+
+def test_denoise_stage_streaming_small(lvx):
+    """3-layer stack, 7 chunks through per-layer rings vs the oracle's list-protocol stage (which the CPU pins tie to the
+    block-causal full-sequence form)."""
+    p, stage, cache, cfg, models, ws, w64 = stage_setup(lvx, "small", 3, "stage_small")
+    d, _, n = dims(p)
+    mod6 = S.randn_f32((3, 6, d), 77, 0.2, device=DEV)
+    mod6[:, 2] += 1.0
+    mod6[:, 5] += 1.0
+    for i in range(7):
+        x = S.randn_bf16((n, d), S.seed_of("stage_x", i), device=DEV)
+        ctx = S.randn_bf16((p["n_ctx"], d), S.seed_of("stage_ctx", i), device=DEV)
+        ref = O.denoise_stage(S.to_f64(x), w64, models, S.to_f64(ctx), S.to_f64(mod6), -0.25, i, 1 + 3 * i, cfg)
+        lvx.lvx_denoise_stage(stage, cache, x, ctx, mod6, -0.25, i, 1 + 3 * i, ws)
+        torch.cuda.synchronize()
+        assert_close(x, ref, "stage chunk %d" % i, relative_to_rms=True)
+        for l in range(3):
+            assert lvx.lvx_kvcache_get_state(cache, l).last_chunk == i
+    cache.close()
