@@ -160,7 +160,8 @@ lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *cache, int32_t layer, cons
 typedef enum {
     LVX_EPI_STORE = 0,      /* C = A W^T */
     LVX_EPI_GELU_TANH = 1,  /* C = gelu_tanh(A W^T) */
-    LVX_EPI_RESID_GATE = 2  /* C = R + gate[n] * (A W^T); gate NULL = 1; C may alias R */
+    LVX_EPI_RESID_GATE = 2, /* C = R + gate[n] * (A W^T); gate NULL = 1; C may alias R */
+    LVX_EPI_RESID_GATE_F32 = 3 /* same, with C and R in fp32 (ldc, ldr in fp32 elements): the in-block residual stream */
 } lvx_epilogue_t;
 
 /* C[M][N] = epilogue(A[M][K] * W[N][K]^T), bf16 in/out, fp32 accumulate on MFMA.  K % 64 == 0, N % 8 == 0. */

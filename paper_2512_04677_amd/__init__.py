@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "liblvx.so")
 _lib = None
 
 LVX_MAX_SLOTS = 16
-EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE = 0, 1, 2
+EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE, EPI_RESID_GATE_F32 = 0, 1, 2, 3
 STATUS_NAMES = {0: "LVX_OK", 1: "LVX_ERR_INVALID_ARG", 2: "LVX_ERR_SHAPE", 3: "LVX_ERR_STATE", 4: "LVX_ERR_UNSUPPORTED",
                 5: "LVX_ERR_HIP"}
 

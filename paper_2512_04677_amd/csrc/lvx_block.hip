@@ -25,7 +25,7 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.ctx_kv = off;  off += round256((size_t)n_ctx * 2 * d * 2);
     w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
-    w.h = off;       off += round256((size_t)n_tokens * d * 2);
+    w.h = off;       off += round256((size_t)n_tokens * d * 4);  // fp32 residual stream
     w.total = off;
     return w;
 }
@@ -55,7 +55,8 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
         if (st_ != LVX_OK) return st_;   \
     } while (0)
 
-lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, bf16_t *x, int n, const bf16_t *ctx, int n_ctx,
+// x: the fp32 residual stream [n][d]
+lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
                        const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st) {
     const lvx_block_weights_t &w = s->blocks[layer];
     const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
@@ -70,15 +71,15 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, bf16_t *
     const float *shift2 = mod6 ? mod6 + 3 * d : nullptr, *scale2 = mod6 ? mod6 + 4 * d : nullptr, *gate2 = mod6 ? mod6 + 5 * d : nullptr;
 
     // self-attention branch
-    LVX_TRY(lvx_layernorm_modulate(x, d, shift1, scale1, eps, n, d, u, d, st));
+    LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, d, st));
     LVX_TRY(lvx_linear(u, d, w.W_qkv, d, big, 3 * d, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
     LVX_TRY(lvx_rope3d(&s->rope, big, big + d, 3 * d, w.g_q, w.g_k, n, t0, big, big + d, 3 * d, st));
     LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, 3 * d, chunk_index, nullptr, st));
     LVX_TRY(lvx_chunk_attention(c, layer, big, 3 * d, n, scale, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE, x, d, gate1, st));
+    LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st));
 
     // cross-attention to the audio + text context
-    LVX_TRY(lvx_layernorm_modulate(x, d, nullptr, nullptr, eps, n, d, u, d, st));
+    LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, d, st));
     LVX_TRY(lvx_linear(u, d, w.Wc_q, d, big, d, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
     LVX_TRY(lvx_linear(ctx, d, w.Wc_k, d, ctx_kv, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
     LVX_TRY(lvx_linear(ctx, d, w.Wc_v, d, ctx_kv + d, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
@@ -92,12 +93,12 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, bf16_t *
     }
     LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, 2 * d, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
     LVX_TRY(lvx_launch_attention(big, d, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE, x, d, nullptr, st));
+    LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st));
 
     // feed-forward
-    LVX_TRY(lvx_layernorm_modulate(x, d, shift2, scale2, eps, n, d, u, d, st));
+    LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, d, st));
     LVX_TRY(lvx_linear(u, d, w.W_1, d, big, f, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st));
-    LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE, x, d, gate2, st));
+    LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st));
     return LVX_OK;
 }
 
@@ -127,8 +128,12 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
     LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
     LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
-    return run_block(stage, layer, cache, (bf16_t *)dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
-                     (char *)dev_workspace, L, (hipStream_t)stream);
+    const size_t n_elems = (size_t)n_tokens * stage->rope.n_heads * stage->rope.head_dim;
+    float *h = (float *)((char *)dev_workspace + L.h);
+    LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_inout, h, n_elems, (hipStream_t)stream));
+    LVX_TRY(run_block(stage, layer, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0, (char *)dev_workspace, L,
+                      (hipStream_t)stream));
+    return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
 }
 
 extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
@@ -141,14 +146,14 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     const int d = stage->rope.n_heads * stage->rope.head_dim;
     bf16_t *x = (bf16_t *)dev_x_inout;
-    bf16_t *h = (bf16_t *)((char *)dev_workspace + L.h);
+    float *h = (float *)((char *)dev_workspace + L.h);
     const size_t n_elems = (size_t)n_tokens * d;
-    LVX_TRY(lvx_launch_copy(x, h, n_elems, (hipStream_t)stream));
+    LVX_TRY(lvx_launch_widen(x, h, n_elems, (hipStream_t)stream));
     for (int l = 0; l < stage->n_layers; ++l) {
         const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
         LVX_TRY(run_block(stage, l, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, m6, chunk_index, t0, (char *)dev_workspace, L,
                           (hipStream_t)stream));
     }
     // Euler step of Alg. 3 / Alg. 4:  x <- x + v dt, the stack output standing in for the velocity
-    return lvx_launch_axpy(x, h, dt, x, n_elems, (hipStream_t)stream);
+    return lvx_launch_euler(x, h, dt, x, n_elems, (hipStream_t)stream);
 }

@@ -115,20 +115,27 @@ __global__ void __launch_bounds__(256) lvx_gather_kv_kernel(const bf16_t *__rest
     }
 }
 
-__global__ void __launch_bounds__(256) lvx_axpy_kernel(const uint4 *x, const uint4 *h, float dt, uint4 *out, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
-        const uint4 a = x[i], b = h[i];
+// 8 elements per thread: out = bf16(x + dt * h), h fp32, x bf16 or absent
+__global__ void __launch_bounds__(256) lvx_euler_kernel(const uint4 *x, const float4 *__restrict__ h, float dt, uint4 *out, size_t n8) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        uint4 a = make_uint4(0, 0, 0, 0);
+        if (x != nullptr) a = x[i];
+        const float4 h0 = h[2 * i], h1 = h[2 * i + 1];
         uint4 o;
-        o.x = pack_bf16x2(bf16_lo(a.x) + dt * bf16_lo(b.x), bf16_hi(a.x) + dt * bf16_hi(b.x));
-        o.y = pack_bf16x2(bf16_lo(a.y) + dt * bf16_lo(b.y), bf16_hi(a.y) + dt * bf16_hi(b.y));
-        o.z = pack_bf16x2(bf16_lo(a.z) + dt * bf16_lo(b.z), bf16_hi(a.z) + dt * bf16_hi(b.z));
-        o.w = pack_bf16x2(bf16_lo(a.w) + dt * bf16_lo(b.w), bf16_hi(a.w) + dt * bf16_hi(b.w));
+        o.x = pack_bf16x2(bf16_lo(a.x) + dt * h0.x, bf16_hi(a.x) + dt * h0.y);
+        o.y = pack_bf16x2(bf16_lo(a.y) + dt * h0.z, bf16_hi(a.y) + dt * h0.w);
+        o.z = pack_bf16x2(bf16_lo(a.z) + dt * h1.x, bf16_hi(a.z) + dt * h1.y);
+        o.w = pack_bf16x2(bf16_lo(a.w) + dt * h1.z, bf16_hi(a.w) + dt * h1.w);
         out[i] = o;
     }
 }
 
-__global__ void __launch_bounds__(256) lvx_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+__global__ void __launch_bounds__(256) lvx_widen_kernel(const uint4 *__restrict__ src, float4 *__restrict__ dst, size_t n8) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const uint4 a = src[i];
+        dst[2 * i] = make_float4(bf16_lo(a.x), bf16_hi(a.x), bf16_lo(a.y), bf16_hi(a.y));
+        dst[2 * i + 1] = make_float4(bf16_lo(a.z), bf16_hi(a.z), bf16_lo(a.w), bf16_hi(a.w));
+    }
 }
 
 static int grid_for(size_t n_items) {
@@ -138,10 +145,16 @@ static int grid_for(size_t n_items) {
     return (int)g;
 }
 
-lvx_status_t lvx_launch_axpy(const bf16_t *x, const bf16_t *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream) {
-    const size_t n16 = n_elems / 8;
-    hipLaunchKernelGGL(lvx_axpy_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (const uint4 *)x, (const uint4 *)h, dt,
-                       (uint4 *)out, n16);
+lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream) {
+    const size_t n8 = n_elems / 8;
+    hipLaunchKernelGGL(lvx_euler_kernel, dim3(grid_for(n8)), dim3(256), 0, stream, (const uint4 *)x, (const float4 *)h, dt, (uint4 *)out, n8);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_widen(const bf16_t *src, float *dst, size_t n_elems, hipStream_t stream) {
+    const size_t n8 = n_elems / 8;
+    hipLaunchKernelGGL(lvx_widen_kernel, dim3(grid_for(n8)), dim3(256), 0, stream, (const uint4 *)src, (float4 *)dst, n8);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
@@ -150,13 +163,6 @@ lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return LVX_OK;
     hipLaunchKernelGGL(lvx_fill_zero_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (uint4 *)dst, n16);
-    LVX_CHECK_HIP(hipGetLastError());
-    return LVX_OK;
-}
-
-lvx_status_t lvx_launch_copy(const bf16_t *src, bf16_t *dst, size_t n_elems, hipStream_t stream) {
-    const size_t n16 = n_elems / 8;
-    hipLaunchKernelGGL(lvx_copy_kernel, dim3(grid_for(n16)), dim3(256), 0, stream, (const uint4 *)src, (uint4 *)dst, n16);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }

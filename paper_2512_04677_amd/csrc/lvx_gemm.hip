@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
         const int n = tn * BN + wn * WTN + j * 32 + l32;
         if (n >= N) continue;
         float gt = 1.f;
-        if (EPI == LVX_EPI_RESID_GATE && gate != nullptr) gt = gate[n];
+        if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -141,7 +141,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
                 float v = acc[i][j][e];
                 if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(R[(size_t)m * ldr + n]) + gt * v;
-                C[(size_t)m * ldc + n] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+                if (EPI == LVX_EPI_RESID_GATE_F32) {
+                    const float *rf = reinterpret_cast<const float *>(R);
+                    reinterpret_cast<float *>(C)[(size_t)m * ldc + n] = rf[(size_t)m * ldr + n] + gt * v;
+                } else {
+                    C[(size_t)m * ldc + n] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+                }
             }
     }
 }
@@ -160,8 +165,10 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
         LVX_GEMM_LAUNCH(LVX_EPI_STORE);
     else if (epi == LVX_EPI_GELU_TANH)
         LVX_GEMM_LAUNCH(LVX_EPI_GELU_TANH);
-    else
+    else if (epi == LVX_EPI_RESID_GATE)
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE);
+    else
+        LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE_F32);
 #undef LVX_GEMM_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -179,9 +186,9 @@ extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *d
     LVX_REQUIRE(K % BK == 0, LVX_ERR_SHAPE, "K %d must be a multiple of %d", K, BK);
     LVX_REQUIRE(N % 8 == 0, LVX_ERR_SHAPE, "N %d must be a multiple of 8", N);
     LVX_REQUIRE(lda >= K && lda % 8 == 0 && ldw >= K && ldw % 8 == 0 && ldc >= N, LVX_ERR_SHAPE, "bad leading dimension");
-    LVX_REQUIRE(epi == LVX_EPI_STORE || epi == LVX_EPI_GELU_TANH || epi == LVX_EPI_RESID_GATE, LVX_ERR_INVALID_ARG, "unknown epilogue %d",
-                (int)epi);
-    if (epi == LVX_EPI_RESID_GATE) {
+    LVX_REQUIRE(epi == LVX_EPI_STORE || epi == LVX_EPI_GELU_TANH || epi == LVX_EPI_RESID_GATE || epi == LVX_EPI_RESID_GATE_F32,
+                LVX_ERR_INVALID_ARG, "unknown epilogue %d", (int)epi);
+    if (epi == LVX_EPI_RESID_GATE || epi == LVX_EPI_RESID_GATE_F32) {
         LVX_REQUIRE(dev_resid != nullptr, LVX_ERR_INVALID_ARG, "residual epilogue needs a residual pointer");
         LVX_REQUIRE(ldr >= N, LVX_ERR_SHAPE, "bad residual leading dimension");
     }

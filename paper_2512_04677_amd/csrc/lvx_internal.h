@@ -66,7 +66,11 @@ lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, in
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
                                   hipStream_t stream);
-lvx_status_t lvx_launch_axpy(const bf16_t *x, const bf16_t *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
+// out = bf16((x ? x : 0) + dt * h) with h in fp32: the Euler step of the stage (x given) or the narrowing of a block's
+// fp32 residual stream (x NULL, dt 1).
+lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
+lvx_status_t lvx_launch_widen(const bf16_t *src, float *dst, size_t n_elems, hipStream_t stream);
+lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,
+                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream);
 // Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
 lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);
-lvx_status_t lvx_launch_copy(const bf16_t *src, bf16_t *dst, size_t n_elems, hipStream_t stream);

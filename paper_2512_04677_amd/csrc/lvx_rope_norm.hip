@@ -105,25 +105,36 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     }
 }
 
-template <int CPL>
+// Input row is bf16 or fp32 (the residual stream is carried in fp32 inside a block / stage); output is bf16.
+template <int CPL, bool F32IN>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
-    lvx_layernorm_modulate_kernel(const bf16_t *__restrict__ x_in, int64_t ldx, const float *__restrict__ shift,
+    lvx_layernorm_modulate_kernel(const void *__restrict__ x_in, int64_t ldx, const float *__restrict__ shift,
                                   const float *__restrict__ scale, float eps, int n_tokens, int d, bf16_t *__restrict__ u_out,
                                   int64_t ldu) {
     const int lane = threadIdx.x & 63;
     const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
     if (token >= n_tokens) return;
     const int n_chunks = d / 8;
-    const u32x4_t *src = reinterpret_cast<const u32x4_t *>(x_in + (size_t)token * ldx);
-    u32x4_t x[CPL];
+    float x[CPL][8];
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < CPL; ++j) {
         const int c = lane + 64 * j;
         if (c < n_chunks) {
-            x[j] = src[c];
+            if (F32IN) {
+                const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(x_in) + (size_t)token * ldx) + 2 * c;
+                const float4 a = src[0], b = src[1];
+                x[j][0] = a.x, x[j][1] = a.y, x[j][2] = a.z, x[j][3] = a.w, x[j][4] = b.x, x[j][5] = b.y, x[j][6] = b.z, x[j][7] = b.w;
+            } else {
+                const u32x4_t v = reinterpret_cast<const u32x4_t *>(reinterpret_cast<const bf16_t *>(x_in) + (size_t)token * ldx)[c];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sum += bf16_lo(x[j][e]) + bf16_hi(x[j][e]);
+                for (int e = 0; e < 4; ++e) {
+                    x[j][2 * e] = bf16_lo(v[e]);
+                    x[j][2 * e + 1] = bf16_hi(v[e]);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += x[j][e];
         }
     }
     const float mean = wave_sum(sum) / (float)d;
@@ -133,9 +144,9 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
         const int c = lane + 64 * j;
         if (c < n_chunks) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float a = bf16_lo(x[j][e]) - mean, b = bf16_hi(x[j][e]) - mean;
-                sq += a * a + b * b;
+            for (int e = 0; e < 8; ++e) {
+                const float a = x[j][e] - mean;
+                sq += a * a;
             }
         }
     }
@@ -157,8 +168,8 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
             u32x4_t y;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float a = (bf16_lo(x[j][e]) - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
-                const float b = (bf16_hi(x[j][e]) - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
+                const float a = (x[j][2 * e] - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
+                const float b = (x[j][2 * e + 1] - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
                 y[e] = pack_bf16x2(a, b);
             }
             dst[c] = y;
@@ -231,10 +242,10 @@ extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_
     return LVX_OK;
 }
 
-extern "C" lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale, float eps,
-                                               int32_t n_tokens, int32_t d, void *dev_u, int64_t ldu, lvx_stream_t stream) {
-    LVX_REQUIRE(dev_x != nullptr && dev_u != nullptr, LVX_ERR_INVALID_ARG, "x or u is NULL");
-    LVX_REQUIRE(lvx_aligned16(dev_x) && lvx_aligned16(dev_u) && lvx_aligned16(dev_shift) && lvx_aligned16(dev_scale), LVX_ERR_INVALID_ARG,
+lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,
+                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream) {
+    LVX_REQUIRE(x != nullptr && u != nullptr, LVX_ERR_INVALID_ARG, "x or u is NULL");
+    LVX_REQUIRE(lvx_aligned16(x) && lvx_aligned16(u) && lvx_aligned16(shift) && lvx_aligned16(scale), LVX_ERR_INVALID_ARG,
                 "pointers must be 16-byte aligned");
     LVX_REQUIRE(d > 0 && d % 8 == 0 && d <= 64 * 8 * 16, LVX_ERR_SHAPE, "d %d must be a positive multiple of 8, at most 8192", d);
     LVX_REQUIRE(ldx >= d && ldx % 8 == 0 && ldu >= d && ldu % 8 == 0, LVX_ERR_SHAPE, "row strides must be multiples of 8 and >= d");
@@ -242,16 +253,29 @@ extern "C" lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, c
     if (n_tokens == 0) return LVX_OK;
     const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
-#define LVX_LN_LAUNCH(CPL)                                                                                                         \
-    hipLaunchKernelGGL(lvx_layernorm_modulate_kernel<CPL>, grid, block, 0, (hipStream_t)stream, (const bf16_t *)dev_x, ldx, dev_shift, \
-                       dev_scale, eps, n_tokens, d, (bf16_t *)dev_u, ldu)
-    if (cpl <= 2)
-        LVX_LN_LAUNCH(2);
-    else if (cpl <= 10)
-        LVX_LN_LAUNCH(10);
-    else
-        LVX_LN_LAUNCH(16);
+#define LVX_LN_LAUNCH(CPL, F32)                                                                                                  \
+    hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, u, ldu)
+    if (x_is_f32) {
+        if (cpl <= 2)
+            LVX_LN_LAUNCH(2, true);
+        else if (cpl <= 10)
+            LVX_LN_LAUNCH(10, true);
+        else
+            LVX_LN_LAUNCH(16, true);
+    } else {
+        if (cpl <= 2)
+            LVX_LN_LAUNCH(2, false);
+        else if (cpl <= 10)
+            LVX_LN_LAUNCH(10, false);
+        else
+            LVX_LN_LAUNCH(16, false);
+    }
 #undef LVX_LN_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale, float eps,
+                                               int32_t n_tokens, int32_t d, void *dev_u, int64_t ldu, lvx_stream_t stream) {
+    return lvx_launch_layernorm(dev_x, 0, ldx, dev_shift, dev_scale, eps, n_tokens, d, (bf16_t *)dev_u, ldu, (hipStream_t)stream);
 }
