@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the denoise-stage hot path on one MI355X.
+
+A step = one pass of the whole hot path over one chunk: lvx_denoise_stage on 40 DiT blocks at the 14B shape
+(3 latent frames x 1560 tokens against the rolling cache: sink 1560 + 4 past chunks + self = 24 960 keys),
+synthetic seeded inputs and random-init weights, everything resident in HBM before the timed region.
+Prints ONE JSON line: latent frames/s (whole job, one GPU), plus
+  roofline      the chunk-to-cache attention kernel's TFLOP/s against the bf16 dense MFMA peak, its launch durations
+                measured live with HIP events on the launch stream inside the timed region;
+  cpu_baseline  the fp64 numpy oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def attention_flops(n_q, n_k, H, D):
+    return 4.0 * n_q * n_k * D * H
+
+
+def block_flops(n, d, f, n_k, n_ctx, H, D):
+    gemm = 2.0 * n * d * (3 * d) + 2.0 * n * d * d + (2.0 * n * d * d + 2 * 2.0 * n_ctx * d * d + 2.0 * n * d * d) + 2 * 2.0 * n * d * f
+    return gemm + attention_flops(n, n_k, H, D) + attention_flops(n, n_ctx, H, D)
+
+
+def cpu_baseline(p, sample_tokens, n_threads_hint):
+    """Oracle (as it stands) on one DiT block with `sample_tokens` of the chunk's tokens against a full-size cache
+    (sink + 4 past chunks); extrapolated linearly in tokens and layers to frames/s."""
+    import numpy as np
+    from oracle import lvx_oracle as O
+    H, D = p["n_heads"], p["head_dim"]
+    d = H * D
+    fk = p["frame_h"] * p["frame_w"]
+    chunk = fk * p["chunk_frames"]
+    rng = np.random.default_rng(0)
+    cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"], p["rope_axes"])
+    w = {}
+    for name, shape in (("W_qkv", (3 * d, d)), ("W_o", (d, d)), ("Wc_q", (d, d)), ("Wc_k", (d, d)), ("Wc_v", (d, d)),
+                        ("Wc_o", (d, d)), ("W_1", (p["ffn"], d)), ("W_2", (d, p["ffn"]))):
+        w[name] = rng.standard_normal(shape, dtype=np.float32).astype(np.float64) * 0.02
+    for g in ("g_q", "g_k", "gc_q", "gc_k"):
+        w[g] = np.ones(d)
+    cache = O.RollingKVCache(p["window"])
+    cache.set_sink(rng.standard_normal((fk, H, D)), rng.standard_normal((fk, H, D)))
+    for j in range(p["window"]):
+        cache.append(j, rng.standard_normal((chunk, H, D), dtype=np.float32).astype(np.float64),
+                     rng.standard_normal((chunk, H, D), dtype=np.float32).astype(np.float64))
+    x = rng.standard_normal((sample_tokens, d))
+    ctx = rng.standard_normal((p["n_ctx"], d))
+    t0 = time.perf_counter()
+    O.dit_block(x, w, cache, ctx, None, p["window"], 1 + 3 * p["window"], cfg)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        cores = n_threads_hint
+    return dt, cores
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--layers", type=int, default=40, help="debug only: fewer layers is NOT the benchmark workload")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-level", type=int, default=2, help="1: time attention launches only, 2: every kernel class")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=390)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (one denoise stage = one timestep of the pipeline on one GPU); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import lvx_synth as S
+    import paper_2512_04677_amd as lvx
+
+    lvx.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    p = S.PRESETS["attn14b"]
+    H, D = p["n_heads"], p["head_dim"]
+    d = H * D
+    fk = p["frame_h"] * p["frame_w"]
+    sink_n, n = fk * p["sink_frames"], fk * p["chunk_frames"]
+    n_slots = p["window"] + 1
+    n_k = sink_n + n_slots * n
+    L = args.layers
+
+    t_setup = time.perf_counter()
+    layers = [S.block_weights(d, p["ffn"], l, "bench", std=0.02, device=dev, on_device_draw=True) for l in range(L)]
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    cache = lvx.KVCache(lvx.cache_desc(L, H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"]), dev)
+    for l in range(L):
+        sk = S.randn_bf16_device((sink_n, d), S.seed_of("bench_sk", l), 1.0, dev)
+        sv = S.randn_bf16_device((sink_n, d), S.seed_of("bench_sv", l), 1.0, dev)
+        lvx.lvx_kvcache_set_sink(cache, l, sk, sv)
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, p["n_ctx"]), dtype=torch.uint8, device=dev)
+    n_inputs = 8
+    xs = [S.randn_bf16_device((n, d), S.seed_of("bench_x", i), 1.0, dev) for i in range(n_inputs)]
+    ctxs = [S.randn_bf16_device((p["n_ctx"], d), S.seed_of("bench_ctx", i), 1.0, dev) for i in range(n_inputs)]
+    x = torch.empty_like(xs[0])
+    torch.cuda.synchronize()
+    print("[bench] setup %.1f s: %d layers, %.1f GB weights, %.1f GB cache, %.2f GB workspace" % (
+        time.perf_counter() - t_setup, L, sum(t.numel() * t.element_size() for w in layers for t in w.values()) / 1e9,
+        cache.storage.numel() / 1e9, ws.numel() / 1e9), file=sys.stderr, flush=True)
+
+    chunk = [0]
+
+    def step():
+        i = chunk[0]
+        x.copy_(xs[i % n_inputs])
+        lvx.lvx_denoise_stage(stage, cache, x, ctxs[i % n_inputs], None, -0.25, i, 1 + 3 * i, ws)
+        chunk[0] += 1
+
+    # fill the ring (setup, untimed): the steady state the paper's stage runs in has all window+1 slots occupied
+    for _ in range(max(0, n_slots - args.warmup)):
+        step()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    print("[bench] ring full after %d chunks; timing %d steps" % (chunk[0], args.steps), file=sys.stderr, flush=True)
+
+    lvx.lvx_profile_read()
+    lvx.lvx_profile_set(args.profile_level)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    seconds = time.perf_counter() - t0
+    lvx.lvx_profile_set(0)
+    prof = lvx.lvx_profile_read()
+    assert bool(torch.isfinite(x.float()).all()), "stage output is not finite"
+
+    ms_per_step = seconds / args.steps * 1e3
+    frames_per_s = p["chunk_frames"] * args.steps / seconds
+    attn_ms, attn_n = prof["attn_self"]
+    attn_avg_ms = attn_ms / max(attn_n, 1)
+    attn_fl = attention_flops(n, n_k, H, D)
+    attn_tflops = attn_fl / (attn_avg_ms * 1e-3) / 1e12 if attn_n else 0.0
+    stage_fl = L * block_flops(n, d, p["ffn"], n_k, p["n_ctx"], H, D)
+
+    out = {
+        "metric": "latent frames/s per denoise stage (chunk-attention TFLOP/s and % of bf16 MFMA peak in `roofline`)",
+        "value": round(frames_per_s, 4), "unit": "latent frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[4]: one denoise stage on one GPU, %d DiT blocks (hidden 5120, 40 heads x 128, FFN 13824, "
+                               "544 context tokens), chunk 3x1560=4680 tokens, rolling cache full: sink 1560 + 4 past chunks + self "
+                               "= 24960 keys per layer (the attention inside is configs[1])" % L,
+                   "n_layers": L, "chunk_tokens": n, "keys": n_k, "ms_per_chunk": round(ms_per_step, 3),
+                   "stage_tflops": round(stage_fl / (seconds / args.steps) / 1e12, 2),
+                   "stage_frac_of_bf16_peak": round(stage_fl / (seconds / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)},
+        "roofline": {"kernel": "lvx_attention_kernel<128,8> (chunk-to-cache self-attention, configs[1] shape)", "bound": "mfma",
+                     "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": attn_fl, "avg_launch_ms": round(attn_avg_ms, 4), "launches": attn_n},
+        "kernel_ms_per_step": {k: round(v[0] / args.steps, 3) for k, v in prof.items() if v[1]},
+    }
+    if not args.no_cpu_baseline:
+        t_cpu, cores = cpu_baseline(p, args.cpu_sample_tokens, os.cpu_count())
+        est_chunk_s = t_cpu * (n / args.cpu_sample_tokens) * L
+        out["cpu_baseline"] = {"value": round(p["chunk_frames"] / est_chunk_s, 6), "unit": "latent frames/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": "fp64 numpy oracle, ONE DiT block on %d of the chunk's 4680 tokens against a full cache "
+                                         "(sink + 4 chunks + self): %.2f s measured; extrapolated x%.0f tokens x%d layers"
+                                         % (args.cpu_sample_tokens, t_cpu, n / args.cpu_sample_tokens, L)}
+    print(json.dumps(out), flush=True)
+    cache.close()
+
+
+if __name__ == "__main__":
+    main()

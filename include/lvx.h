@@ -214,6 +214,20 @@ lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage /* host */, lvx_kvcache_
                                const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Optional timing of the kernel classes inside lvx_dit_block / lvx_denoise_stage with HIP events recorded on the
+ * caller's stream (the benchmark's roofline figures come from here).  Not thread-safe; level 0 = off (default),
+ * 1 = the chunk-to-cache attention launches only, 2 = every class below.  lvx_profile_read waits for the recorded
+ * events (it synchronises on them), writes per-class totals into host arrays of LVX_PROF_KINDS entries and resets.
+ * ------------------------------------------------------------------------------------------------ */
+enum {
+    LVX_PROF_ATTN_SELF = 0, LVX_PROF_GEMM_QKV = 1, LVX_PROF_GEMM_O = 2, LVX_PROF_GEMM_CROSS = 3, LVX_PROF_GEMM_FFN1 = 4,
+    LVX_PROF_GEMM_FFN2 = 5, LVX_PROF_ATTN_CROSS = 6, LVX_PROF_ROPE_NORM = 7, LVX_PROF_APPEND = 8, LVX_PROF_LAYERNORM = 9,
+    LVX_PROF_KINDS = 10
+};
+lvx_status_t lvx_profile_set(int32_t level);
+lvx_status_t lvx_profile_read(double *ms_total /* host [LVX_PROF_KINDS] */, int64_t *launches /* host [LVX_PROF_KINDS] */);
+
 #ifdef __cplusplus
 }
 #endif

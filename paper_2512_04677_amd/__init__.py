@@ -73,7 +73,11 @@ SIGNATURES = {
     "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
     "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_denoise_stage": (C.c_int, [C.POINTER(Stage), _vp, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _vp, _sz, _vp]),
+    "lvx_profile_set": (C.c_int, [_i32]),
+    "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
+PROF_KINDS = ["attn_self", "gemm_qkv", "gemm_o", "gemm_cross", "gemm_ffn1", "gemm_ffn2", "attn_cross", "rope_norm", "append",
+              "layernorm"]
 
 
 def load():
@@ -232,3 +236,15 @@ def lvx_denoise_stage(stage, cache, x, ctx, mod6_per_layer, dt, chunk_index, t0,
     _check(load().lvx_denoise_stage(C.byref(stage.c), cache.handle, _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0],
                                     _ptr(mod6_per_layer), dt, chunk_index, t0, _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def lvx_profile_set(level):
+    _check(load().lvx_profile_set(level))
+
+
+def lvx_profile_read():
+    """{class: (total_ms, launches)} since the last read; waits for the recorded events."""
+    ms = (C.c_double * len(PROF_KINDS))()
+    n = (C.c_int64 * len(PROF_KINDS))()
+    _check(load().lvx_profile_read(ms, n))
+    return {k: (ms[i], n[i]) for i, k in enumerate(PROF_KINDS)}

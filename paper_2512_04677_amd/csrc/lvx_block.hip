@@ -5,7 +5,41 @@
 
 #include <math.h>
 
+#include <vector>
+
 namespace {
+
+// ---- optional per-kernel-class timing with HIP events on the caller's stream (for the benchmark's roofline figures)
+struct prof_pair_t {
+    hipEvent_t a, b;
+    int kind;
+};
+int g_prof_level = 0;
+std::vector<prof_pair_t> g_prof_pool;
+size_t g_prof_used = 0;
+
+struct prof_scope_t {
+    hipStream_t st;
+    prof_pair_t *p = nullptr;
+    prof_scope_t(int kind, hipStream_t stream) : st(stream) {
+        if (g_prof_level == 0 || (g_prof_level == 1 && kind != LVX_PROF_ATTN_SELF)) return;
+        if (g_prof_used == g_prof_pool.size()) {
+            prof_pair_t n;
+            if (hipEventCreate(&n.a) != hipSuccess) return;
+            if (hipEventCreate(&n.b) != hipSuccess) {
+                (void)hipEventDestroy(n.a);
+                return;
+            }
+            g_prof_pool.push_back(n);
+        }
+        p = &g_prof_pool[g_prof_used++];
+        p->kind = kind;
+        (void)hipEventRecord(p->a, st);
+    }
+    ~prof_scope_t() {
+        if (p) (void)hipEventRecord(p->b, st);
+    }
+};
 
 struct ws_layout_t {
     size_t u, big, ctx_kv, pack_k, pack_v, h, total;  // byte offsets
@@ -71,18 +105,21 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     const float *shift2 = mod6 ? mod6 + 3 * d : nullptr, *scale2 = mod6 ? mod6 + 4 * d : nullptr, *gate2 = mod6 ? mod6 + 5 * d : nullptr;
 
     // self-attention branch
-    LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.W_qkv, d, big, 3 * d, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-    LVX_TRY(lvx_rope3d(&s->rope, big, big + d, 3 * d, w.g_q, w.g_k, n, t0, big, big + d, 3 * d, st));
-    LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, 3 * d, chunk_index, nullptr, st));
-    LVX_TRY(lvx_chunk_attention(c, layer, big, 3 * d, n, scale, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st));
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, d, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(lvx_linear(u, d, w.W_qkv, d, big, 3 * d, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, 3 * d, w.g_q, w.g_k, n, t0, big, big + d, 3 * d, st)); }
+    { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, 3 * d, chunk_index, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, 3 * d, n, scale, u, d, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st)); }
 
     // cross-attention to the audio + text context
-    LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.Wc_q, d, big, d, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-    LVX_TRY(lvx_linear(ctx, d, w.Wc_k, d, ctx_kv, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-    LVX_TRY(lvx_linear(ctx, d, w.Wc_v, d, ctx_kv + d, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, d, st)); }
+    {
+        prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
+        LVX_TRY(lvx_linear(u, d, w.Wc_q, d, big, d, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(lvx_linear(ctx, d, w.Wc_k, d, ctx_kv, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(lvx_linear(ctx, d, w.Wc_v, d, ctx_kv + d, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+    }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
     if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, d, w.gc_q, nullptr, n, 0, big, nullptr, d, st));
@@ -92,13 +129,13 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         LVX_TRY(lvx_launch_fill_zero(pack_v, (size_t)L.cap_ctx * d * 2, st));
     }
     LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, 2 * d, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
-    LVX_TRY(lvx_launch_attention(big, d, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st));
+    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, d, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, d, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st)); }
 
     // feed-forward
-    LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, d, st));
-    LVX_TRY(lvx_linear(u, d, w.W_1, d, big, f, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st));
-    LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st));
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, d, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(lvx_linear(u, d, w.W_1, d, big, f, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st)); }
     return LVX_OK;
 }
 
@@ -116,6 +153,30 @@ lvx_status_t check_common(const lvx_stage_t *s, lvx_kvcache *c, void *x, int n, 
 }
 
 }  // namespace
+
+extern "C" lvx_status_t lvx_profile_set(int32_t level) {
+    LVX_REQUIRE(level >= 0 && level <= 2, LVX_ERR_INVALID_ARG, "profile level %d not in 0..2", level);
+    g_prof_level = level;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_profile_read(double *ms_total, int64_t *launches) {
+    LVX_REQUIRE(ms_total != nullptr && launches != nullptr, LVX_ERR_INVALID_ARG, "output arrays are NULL");
+    for (int k = 0; k < LVX_PROF_KINDS; ++k) {
+        ms_total[k] = 0.0;
+        launches[k] = 0;
+    }
+    for (size_t i = 0; i < g_prof_used; ++i) {
+        prof_pair_t &p = g_prof_pool[i];
+        LVX_CHECK_HIP(hipEventSynchronize(p.b));
+        float ms = 0.f;
+        LVX_CHECK_HIP(hipEventElapsedTime(&ms, p.a, p.b));
+        ms_total[p.kind] += ms;
+        launches[p.kind] += 1;
+    }
+    g_prof_used = 0;
+    return LVX_OK;
+}
 
 extern "C" size_t lvx_workspace_bytes(const lvx_stage_t *stage, int32_t n_tokens, int32_t n_ctx) {
     if (check_stage(stage, nullptr, n_tokens, n_ctx) != LVX_OK) return 0;
