@@ -284,6 +284,27 @@ def dit_block(x, w, cache, ctx, mod6, chunk_index, t0, cfg):
     return x
 
 
+def dit_block_rows(x_rows, positions, w, k_visible, v_visible, ctx, mod6, cfg):
+    """The block's output for a SUBSET of the chunk's tokens, given all keys/values those tokens see.
+
+    Same formulas as dit_block, row by row: every step of the block acts on each token independently except the
+    self-attention, whose keys/values (sink, cached chunks and the current chunk, any order) are passed in.
+    Used for sampled checks at sizes where the whole chunk is too much for the CPU.  Returns (x_out_rows,
+    k_rows, v_rows): k_rows / v_rows are what the block stores in the cache for these tokens."""
+    x = np.asarray(x_rows, F64)
+    H, D = cfg.n_heads, cfg.head_dim
+    d = H * D
+    sh1, sc1, g1, sh2, sc2, g2 = _mod6(mod6, d)
+    u = modulate(x, sh1, sc1, cfg.eps)
+    q, k, v = qkv_for_cache(u, w, cfg, 0, positions)
+    o = attention(q, k_visible, v_visible, 1.0 / np.sqrt(D))
+    x = x + g1 * linear(o.reshape(-1, d), w["W_o"])
+    x = x + cross_attention(x, np.asarray(ctx, F64), w, cfg)
+    u2 = modulate(x, sh2, sc2, cfg.eps)
+    x = x + g2 * ffn(u2, w)
+    return x, k, v
+
+
 def denoise_stage(x, layers, caches, ctx, mod6_per_layer, dt, chunk_index, t0, cfg):
     """One timestep of the pipeline for one chunk: all blocks, then the Euler step x <- x + v*dt.
 

@@ -1,0 +1,162 @@
+"""GPU parity at the benchmark's full sizes (14B-DiT shape), in the launch configuration bench.py times.
+
+The CPU oracle cannot evaluate these sizes whole, so outputs are checked on SAMPLED rows the oracle computes one by one
+(all heads / all channels of each sampled token), teacher-forced where a step depends on the whole chunk: the oracle is
+handed the cache contents the GPU path holds (read back through lvx_kvcache_gather, itself gated bit-exactly by the
+small-size tests) and the rows of that cache are in turn checked against the oracle's own K/V for the sampled tokens.
+Inputs are drawn on the GPU (seeded) and read back, so both sides see the same bits.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import lvx_synth as S
+from oracle import lvx_oracle as O
+from test_gpu_parity import CHAIN, DEV, assert_close, dims, make_cache
+
+pytestmark = pytest.mark.gpu
+P = S.PRESETS["attn14b"]
+
+
+def sample_rows(n, k, seed):
+    """Tile-boundary rows of the 256-query workgroup tile / 32-query wave tile, first / last rows, plus random ones."""
+    fixed = [0, 31, 32, 255, 256, n - 257, n - 73, n - 72, n - 1]
+    rnd = np.random.default_rng(seed).choice(n, size=k, replace=False).tolist()
+    return np.array(sorted(set(fixed + rnd)))
+
+
+def test_config2_attention_sampled_rows_all_warmup_key_counts(lvx):
+    """40 heads x 128, 4680 queries; keys 6240 .. 24960 as the ring fills (6240 = 97.5 tiles: ragged last tile)."""
+    d, sink_n, n = dims(P)
+    H, D = P["n_heads"], P["head_dim"]
+    cache = make_cache(lvx, P)
+    sk = S.randn_bf16_device((sink_n, d), 2, 1.0, DEV)
+    sv = S.randn_bf16_device((sink_n, d), 3, 1.0, DEV)
+    lvx.lvx_kvcache_set_sink(cache, 0, sk, sv)
+    ks, vs = [S.to_f64(sk).reshape(-1, H, D)], [S.to_f64(sv).reshape(-1, H, D)]
+    q = S.randn_bf16_device((n, d), 1, 1.0, DEV)
+    out = torch.empty_like(q)
+    rows = sample_rows(n, 24, 5)
+    q_rows = S.to_f64(q[torch.as_tensor(rows, device=DEV)]).reshape(-1, H, D)
+    scale = 1.0 / math.sqrt(D)
+    for i in range(P["window"] + 1):
+        k = S.randn_bf16_device((n, d), 10 + i, 1.0, DEV)
+        v = S.randn_bf16_device((n, d), 20 + i, 1.0, DEV)
+        info = lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        torch.cuda.synchronize()
+        ks.append(S.to_f64(k).reshape(-1, H, D))
+        vs.append(S.to_f64(v).reshape(-1, H, D))
+        assert info.key_count == sink_n + (i + 1) * n
+        ref = O.attention(q_rows, np.concatenate(ks), np.concatenate(vs), scale)
+        got = out[torch.as_tensor(rows, device=DEV)]
+        assert_close(got, ref.reshape(len(rows), d), "config 2 attention, %d keys" % info.key_count)
+    # whole-output property that holds at any size: each output row is a convex combination of V rows
+    vmax = torch.stack([torch.as_tensor(np.concatenate(vs).reshape(-1, d).max(0)), torch.as_tensor(-np.concatenate(vs).reshape(-1, d).min(0))])
+    o = out.float().cpu()
+    assert bool((o <= vmax[0] + 1e-2).all()) and bool((-o <= vmax[1] + 1e-2).all())
+    cache.close()
+
+
+def test_config3_streaming_loop_100_steps(lvx):
+    """100 chunk steps of rope/norm -> append/evict -> attention at the 14B shape.  Indices are checked against the
+    list protocol at EVERY step; cache bits, rope parity and sampled-row attention parity at steps 0,1,3,4,5,50,99;
+    the sink segment is bit-identical at the end."""
+    d, sink_n, n = dims(P)
+    H, D, W = P["n_heads"], P["head_dim"], P["window"]
+    cache = make_cache(lvx, P)
+    rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
+    gains = torch.ones(d, dtype=torch.float32, device=DEV)
+    # sink: normalised, rotated at t = 0
+    sraw = S.randn_bf16_device((sink_n, 3 * d), 99, 1.0, DEV)
+    lvx.lvx_rope3d(rope, sraw[:, :d], sraw[:, d:2 * d], gains, gains, sink_n, 0, sraw[:, :d], sraw[:, d:2 * d], ld_in=3 * d, ld_out=3 * d)
+    sink_k, sink_v = sraw[:, d:2 * d].contiguous(), sraw[:, 2 * d:].contiguous()
+    lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+    model = O.RollingKVCache(W)
+    model.set_sink(np.zeros((1, 1, 1)), np.zeros((1, 1, 1)))
+    scale = 1.0 / math.sqrt(D)
+    rows = sample_rows(n, 8, 7)
+    rows_t = torch.as_tensor(rows, device=DEV)
+    cap = sink_n + (W + 1) * n
+    out = torch.empty((n, d), dtype=torch.bfloat16, device=DEV)
+    gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    for i in range(100):
+        qkv = S.randn_bf16_device((n, 3 * d), S.seed_of("cfg3", i), 1.0, DEV)
+        check = i in (0, 1, 3, 4, 5, 50, 99)
+        raw_rows = S.to_f64(qkv[rows_t]) if check else None
+        t0 = 1 + 3 * i
+        lvx.lvx_rope3d(rope, qkv[:, :d], qkv[:, d:2 * d], gains, gains, n, t0, qkv[:, :d], qkv[:, d:2 * d], ld_in=3 * d, ld_out=3 * d)
+        visible = model.chunk_ids() + [i]
+        info = lvx.lvx_chunk_append_evict(cache, 0, qkv[:, d:2 * d], qkv[:, 2 * d:], i, ld=3 * d)
+        lvx.lvx_chunk_attention(cache, 0, qkv[:, :d], scale, out)
+        st = lvx.lvx_kvcache_get_state(cache, 0)
+        assert info.slot == i % (W + 1) and info.evicted_chunk == (i - (W + 1) if i > W else -1)
+        assert sorted(c for c in st.slot_chunk[:st.n_slots] if c >= 0) == visible
+        assert info.key_count == st.key_count == sink_n + len(visible) * n
+        model.append(i, np.zeros((1, 1, 1)), np.zeros((1, 1, 1)))
+        if not check:
+            continue
+        torch.cuda.synchronize()
+        lvx.lvx_kvcache_gather(cache, 0, 0, cap, gk, gv)
+        torch.cuda.synchronize()
+        sl = slice(info.key_offset, info.key_offset + n)
+        assert torch.equal(gk[sl].view(torch.int16), qkv[:, d:2 * d].view(torch.int16)), "K bits of step %d" % i
+        assert torch.equal(gv[sl].view(torch.int16), qkv[:, 2 * d:].view(torch.int16)), "V bits of step %d" % i
+        assert torch.equal(gk[:sink_n].view(torch.int16), sink_k.view(torch.int16)) and torch.equal(gv[:sink_n].view(torch.int16), sink_v.view(torch.int16))
+        # rope + rmsnorm parity on the sampled tokens (positions of those tokens)
+        pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
+        for col, name in ((0, "q"), (d, "k")):
+            ref = O.rope3d(O.rmsnorm(raw_rows[:, col:col + d], np.ones(d), 1e-6).reshape(-1, H, D), 0, P["frame_h"], P["frame_w"],
+                           P["rope_axes"], 10000.0, positions=pos)
+            assert_close(qkv[rows_t][:, col:col + d].contiguous(), ref.reshape(len(rows), d), "config 3 step %d rope+norm %s" % (i, name))
+        # attention of the sampled queries against the cache the GPU holds
+        nk = info.key_count
+        ref = O.attention(S.to_f64(qkv[rows_t][:, :d].contiguous()).reshape(-1, H, D), S.to_f64(gk[:nk]).reshape(nk, H, D),
+                          S.to_f64(gv[:nk]).reshape(nk, H, D), scale)
+        assert_close(out[rows_t], ref.reshape(len(rows), d), "config 3 step %d attention (%d keys)" % (i, nk))
+    cache.close()
+
+
+def test_config4_dit_block_sampled_rows(lvx):
+    """One full-size DiT block (weights N(0, 0.02)), cache pre-filled with 4 chunks: the block's output rows for sampled
+    tokens against the oracle's row form, which is handed the keys the GPU cache holds; the cache rows the block wrote
+    for those tokens are checked against the oracle's own K-hat / V."""
+    d, sink_n, n = dims(P)
+    H, D, W = P["n_heads"], P["head_dim"], P["window"]
+    w = S.block_weights(d, P["ffn"], 0, "cfg4", std=0.02, device=DEV, on_device_draw=True)
+    rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
+    stage = lvx.StageHandle([w], rope, P["ffn"])
+    cache = make_cache(lvx, P)
+    lvx.lvx_kvcache_set_sink(cache, 0, S.randn_bf16_device((sink_n, d), 2, 1.0, DEV), S.randn_bf16_device((sink_n, d), 3, 1.0, DEV))
+    for i in range(W):
+        lvx.lvx_chunk_append_evict(cache, 0, S.randn_bf16_device((n, d), 10 + i, 1.0, DEV), S.randn_bf16_device((n, d), 20 + i, 1.0, DEV), i)
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, P["n_ctx"]), dtype=torch.uint8, device=DEV)
+    x = S.randn_bf16_device((n, d), 31, 1.0, DEV)
+    ctx = S.randn_bf16_device((P["n_ctx"], d), 32, 1.0, DEV)
+    mod6 = S.randn_f32((6, d), 33, 0.1, device=DEV)
+    mod6[2] += 1.0
+    mod6[5] += 1.0
+    rows = sample_rows(n, 6, 9)
+    rows_t = torch.as_tensor(rows, device=DEV)
+    x_rows = S.to_f64(x[rows_t])
+    t0 = 1 + 3 * W
+    lvx.lvx_dit_block(stage, 0, cache, x, ctx, mod6, W, t0, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(x.float()).all())
+    cap = sink_n + (W + 1) * n
+    gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    lvx.lvx_kvcache_gather(cache, 0, 0, cap, gk, gv)
+    torch.cuda.synchronize()
+    cfg = O.StageConfig(H, D, P["frame_h"], P["frame_w"], P["chunk_frames"], W, P["sink_frames"], P["rope_axes"])
+    pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
+    ref, k_rows, v_rows = O.dit_block_rows(x_rows, pos, S.weights_to_f64(w), S.to_f64(gk).reshape(cap, H, D), S.to_f64(gv).reshape(cap, H, D),
+                                           S.to_f64(ctx), S.to_f64(mod6), cfg)
+    off = sink_n + (W % (W + 1)) * n
+    assert_close(gk[off + rows_t], k_rows.reshape(len(rows), d), "config 4 cached K-hat rows")
+    assert_close(gv[off + rows_t], v_rows.reshape(len(rows), d), "config 4 cached V rows")
+    assert_close(x[rows_t], ref, "config 4 block output rows", relative_to_rms=True, chain=CHAIN)
+    cache.close()

@@ -311,3 +311,28 @@ def test_streaming_stage_equals_full_sequence_stack():
     for i in range(n_chunks):
         y = O.denoise_stage(xs[i], layers, caches, ctxs[i], mod6, -0.25, i, t0(i), cfg)
         np.testing.assert_allclose(y, full[i], rtol=1e-10, atol=1e-11)
+
+
+def test_block_rows_form_equals_whole_chunk_block():
+    """dit_block_rows (sampled tokens + explicit visible keys) is the same function as dit_block restricted to rows."""
+    cfg = tiny_cfg()
+    d = cfg.d_model
+    w = tiny_weights(cfg)
+    ctx = rng.standard_normal((5, d))
+    mod6 = rng.standard_normal((6, d)) * 0.3
+    cache = fresh_cache(cfg, 3)
+    for i in range(4):
+        x = rng.standard_normal((cfg.chunk_tokens, d))
+        t0 = 1 + cfg.chunk_frames * i
+        before = O.RollingKVCache(cfg.window)
+        before.sink, before.blocks = cache.sink, type(cache.blocks)(cache.blocks)
+        y = O.dit_block(x, w, cache, ctx, mod6, i, t0, cfg)
+        k_new, v_new = cache.blocks[-1][1], cache.blocks[-1][2]
+        k_vis, v_vis = before.visible(k_new, v_new)
+        rows = np.array([0, 5, cfg.chunk_tokens - 1])
+        pos = tuple(p[rows] for p in O.token_positions(cfg.chunk_tokens, t0, cfg.frame_h, cfg.frame_w))
+        perm = rng.permutation(k_vis.shape[0])          # key order must not matter
+        yr, kr, vr = O.dit_block_rows(x[rows], pos, w, k_vis[perm], v_vis[perm], ctx, mod6, cfg)
+        np.testing.assert_allclose(yr, y[rows], rtol=1e-11, atol=1e-12)
+        np.testing.assert_array_equal(kr, k_new[rows])
+        np.testing.assert_array_equal(vr, v_new[rows])
