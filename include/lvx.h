@@ -209,7 +209,14 @@ lvx_status_t lvx_dit_block(const lvx_stage_t *stage /* host */, int32_t layer, l
                            int32_t n_tokens, const void *dev_ctx, int32_t n_ctx, const float *dev_mod6,
                            int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 
-/* All blocks, then x <- x + dt * stack(x).  mod6_per_layer: fp32 [n_layers][6][d] or NULL. */
+/* The same block on an fp32 residual stream x_inout [n_tokens][d] (what lvx_denoise_stage iterates between its widening
+ * of the bf16 input and its Euler step; exported so that a stage can be checked layer by layer). */
+lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage /* host */, int32_t layer, lvx_kvcache_t *cache, float *dev_x_inout,
+                               int32_t n_tokens, const void *dev_ctx, int32_t n_ctx, const float *dev_mod6, int64_t chunk_index,
+                               int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
+/* All blocks, then x <- x + dt * stack(x).  The residual stream is widened to fp32 once, carried in fp32 through all
+ * blocks, and narrowed to bf16 only by the Euler step.  mod6_per_layer: fp32 [n_layers][6][d] or NULL. */
 lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage /* host */, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
                                const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);

@@ -72,6 +72,7 @@ SIGNATURES = {
     "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
     "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
     "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
+    "lvx_dit_block_f32": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_denoise_stage": (C.c_int, [C.POINTER(Stage), _vp, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _vp, _sz, _vp]),
     "lvx_profile_set": (C.c_int, [_i32]),
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
@@ -230,6 +231,11 @@ def lvx_workspace_bytes(stage, n_tokens, n_ctx):
 def lvx_dit_block(stage, layer, cache, x, ctx, mod6, chunk_index, t0, workspace):
     _check(load().lvx_dit_block(C.byref(stage.c), layer, cache.handle, _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0], _ptr(mod6),
                                 chunk_index, t0, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def lvx_dit_block_f32(stage, layer, cache, x32, ctx, mod6, chunk_index, t0, workspace):
+    _check(load().lvx_dit_block_f32(C.byref(stage.c), layer, cache.handle, _ptr(x32), x32.shape[0], _ptr(ctx), ctx.shape[0], _ptr(mod6),
+                                    chunk_index, t0, _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def lvx_denoise_stage(stage, cache, x, ctx, mod6_per_layer, dt, chunk_index, t0, workspace):

@@ -197,6 +197,16 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
     return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
 }
 
+extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t layer, lvx_kvcache_t *cache, float *dev_x_inout, int32_t n_tokens,
+                                          const void *dev_ctx, int32_t n_ctx, const float *dev_mod6, int64_t chunk_index, int32_t t0,
+                                          void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
+    LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
+    LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
+    const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
+    return run_block(stage, layer, cache, dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
+                     (char *)dev_workspace, L, (hipStream_t)stream);
+}
+
 extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
                                           const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                           int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {

@@ -156,7 +156,65 @@ def test_config4_dit_block_sampled_rows(lvx):
     ref, k_rows, v_rows = O.dit_block_rows(x_rows, pos, S.weights_to_f64(w), S.to_f64(gk).reshape(cap, H, D), S.to_f64(gv).reshape(cap, H, D),
                                            S.to_f64(ctx), S.to_f64(mod6), cfg)
     off = sink_n + (W % (W + 1)) * n
-    assert_close(gk[off + rows_t], k_rows.reshape(len(rows), d), "config 4 cached K-hat rows")
-    assert_close(gv[off + rows_t], v_rows.reshape(len(rows), d), "config 4 cached V rows")
+    # K-hat went through three bf16-storing kernels (layernorm, QKV GEMM, rmsnorm+rope), V through two: chain gate
+    assert_close(gk[off + rows_t], k_rows.reshape(len(rows), d), "config 4 cached K-hat rows", chain=CHAIN)
+    assert_close(gv[off + rows_t], v_rows.reshape(len(rows), d), "config 4 cached V rows", chain=CHAIN)
     assert_close(x[rows_t], ref, "config 4 block output rows", relative_to_rms=True, chain=CHAIN)
     cache.close()
+
+
+def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
+    """Full-size stage (40 blocks, 28 GB of weights), two chunks.  (a) lvx_denoise_stage must equal, bit for bit up to
+    the last-place rounding of the Euler step, the chain widen -> 40 x lvx_dit_block_f32 -> Euler run on a second
+    cache; (b) in that chain, layers 0, 20 and 39 are checked on sampled tokens against the oracle's row form, which
+    is given the layer's fp32 input rows and the keys that layer's cache holds; (c) both caches end bit-identical."""
+    d, sink_n, n = dims(P)
+    H, D, W = P["n_heads"], P["head_dim"], P["window"]
+    L = 40
+    layers = [S.block_weights(d, P["ffn"], l, "cfg5", std=0.02, device=DEV, on_device_draw=True) for l in range(L)]
+    rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
+    stage = lvx.StageHandle(layers, rope, P["ffn"])
+    cache_a, cache_b = make_cache(lvx, P, L), make_cache(lvx, P, L)
+    for l in range(L):
+        sk = S.randn_bf16_device((sink_n, d), S.seed_of("cfg5_sk", l), 1.0, DEV)
+        sv = S.randn_bf16_device((sink_n, d), S.seed_of("cfg5_sv", l), 1.0, DEV)
+        lvx.lvx_kvcache_set_sink(cache_a, l, sk, sv)
+        lvx.lvx_kvcache_set_sink(cache_b, l, sk, sv)
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, P["n_ctx"]), dtype=torch.uint8, device=DEV)
+    cfg = O.StageConfig(H, D, P["frame_h"], P["frame_w"], P["chunk_frames"], W, P["sink_frames"], P["rope_axes"])
+    rows = sample_rows(n, 4, 11)
+    rows_t = torch.as_tensor(rows, device=DEV)
+    cap = sink_n + (W + 1) * n
+    gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
+    dt = -0.25
+    for i in range(2):
+        x = S.randn_bf16_device((n, d), S.seed_of("cfg5_x", i), 1.0, DEV)
+        ctx = S.randn_bf16_device((P["n_ctx"], d), S.seed_of("cfg5_ctx", i), 1.0, DEV)
+        t0 = 1 + 3 * i
+        xa = x.clone()
+        lvx.lvx_denoise_stage(stage, cache_a, xa, ctx, None, dt, i, t0, ws)
+        h = x.float()
+        for l in range(L):
+            check = l in (0, 20, 39)
+            h_in_rows = S.to_f64(h[rows_t]) if check else None
+            lvx.lvx_dit_block_f32(stage, l, cache_b, h, ctx, None, i, t0, ws)
+            if not check:
+                continue
+            lvx.lvx_kvcache_gather(cache_b, l, 0, cap, gk, gv)
+            torch.cuda.synchronize()
+            nk = sink_n + (i + 1) * n
+            pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
+            ref, _, _ = O.dit_block_rows(h_in_rows, pos, S.weights_to_f64(layers[l]), S.to_f64(gk[:nk]).reshape(nk, H, D),
+                                         S.to_f64(gv[:nk]).reshape(nk, H, D), S.to_f64(ctx), None, cfg)
+            assert_close(h[rows_t], ref, "config 5 chunk %d layer %d output rows" % (i, l), relative_to_rms=True, chain=CHAIN)
+        torch.cuda.synchronize()
+        want = (x.double() + dt * h.double()).to(torch.bfloat16)
+        diff = (xa.view(torch.int16).int() - want.view(torch.int16).int()).abs()
+        frac = float((diff != 0).float().mean())
+        print("config 5 chunk %d: stage vs block chain, elements differing %.2e, max ulp %d" % (i, frac, int(diff.max())), flush=True)
+        assert int(diff.max()) <= 1 and frac < 1e-3
+        assert bool(torch.isfinite(xa.float()).all())
+    assert torch.equal(cache_a.storage, cache_b.storage)
+    cache_a.close()
+    cache_b.close()
