@@ -9,6 +9,8 @@
 //     layout of the second MFMA, O^T += V^T P^T, with no LDS round trip.
 //   * K tiles ([64 keys][D]) and V^T tiles ([D][64 keys], stored transposed in the cache) are double-buffered in LDS;
 //     rows are padded so that 16 consecutive lanes reading 16 bytes each hit disjoint banks.
+//   * the two waves of each SIMD are run half a period apart (matrix phase against vector phase, see "pipeline" below),
+//     so the softmax VALU work of one wave hides under the MFMA work of the other.
 //   * K rows are placed in LDS in the order the accumulator layout wants (lane i of the A operand reads LDS row i),
 //     which makes each half-wave's 16 scores per block belong to 16 CONSECUTIVE keys, so V^T fragments are
 //     contiguous 16-byte reads.
@@ -38,6 +40,9 @@ __global__ void __launch_bounds__(64 * NWAVES)
     constexpr int CPT = CH / NT;
     constexpr int MK = D / 16;  // MFMA k-steps over head_dim
     constexpr int DB = D / 32;  // 32-row blocks of O^T
+    constexpr int NV = DB * 4;  // V^T fragments (= PV MFMAs) per 64-key tile
+    constexpr int NK = 2 * MK;  // K fragments (= QK MFMAs) per 64-key tile
+    constexpr int PD = 6;       // LDS fragment prefetch distance, in MFMAs
 
     __shared__ __attribute__((aligned(16))) bf16_t ks[2 * K_STAGE];
     __shared__ __attribute__((aligned(16))) bf16_t vs[2 * V_STAGE];
@@ -67,26 +72,44 @@ __global__ void __launch_bounds__(64 * NWAVES)
     const u32x4_t *k_src = reinterpret_cast<const u32x4_t *>(kp + (size_t)head * cap * D);
     const u32x4_t *v_src = reinterpret_cast<const u32x4_t *>(vtp + (size_t)head * cap * D);
 
+    // ---- pipeline -------------------------------------------------------------------------------------------------
+    // A wave alternates between a matrix phase X(t) = { S(t+1) = K(t+1) Q^T ; O += V(t)^T P(t) } (32 MFMAs, LDS reads)
+    // and a vector phase Y(t) = { online softmax of S(t) -> P(t) ; stage the next tiles global -> LDS }.  The two waves
+    // that share a SIMD (wave w and w + NWAVES/2) run half a period apart, with a workgroup barrier after every phase:
+    // while group 0 is in X the other is in Y, so the matrix core and the vector ALU of each SIMD are busy at the same
+    // time instead of both waves queueing for the same unit.
+    //   iteration i, first half :  group 0: X(i-1) (S(0) only before the loop)  group 1: Y(i-1), stage(i)
+    //   iteration i, second half:  group 0: Y(i), stage(i)                      group 1: X(i-1)
+    // stage(i) writes V(i) into V buffer i&1 and K(i+1) into K buffer (i+1)&1; both were last read by group 1 in
+    // X(i-2), one barrier before the first half of iteration i, and are first needed by group 0 in X(i).
+    const int grp = wave / (NWAVES / 2);
     u32x4_t kreg[CPT], vreg[CPT];
-#define LVX_ATTN_GLOAD(t_)                                   \
-    {                                                        \
-        const u32x4_t *kt_ = k_src + (size_t)(t_) * CH;        \
-        const u32x4_t *vt_ = v_src + (size_t)(t_) * CH;        \
-        _Pragma("unroll") for (int i = 0; i < CPT; ++i) {    \
-            kreg[i] = kt_[tid + i * NT];                     \
-            vreg[i] = vt_[tid + i * NT];                     \
-        }                                                    \
+#define LVX_ATTN_GLOAD_K(t_)                                                                   \
+    {                                                                                          \
+        const u32x4_t *kt_ = k_src + (size_t)(t_) * CH;                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) kreg[i_] = kt_[tid + i_ * NT];      \
+    }
+#define LVX_ATTN_GLOAD_V(t_)                                                                   \
+    {                                                                                          \
+        const u32x4_t *vt_ = v_src + (size_t)(t_) * CH;                                        \
+        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) vreg[i_] = vt_[tid + i_ * NT];      \
     }
     // key row r = 32*blk + 16h + 4g4 + r4 goes to LDS row 32*blk + 8*g4 + 4h + r4 (accumulator row order)
-#define LVX_ATTN_LSTORE(buf_)                                                                             \
+#define LVX_ATTN_LSTORE_K(buf_)                                                                           \
     {                                                                                                     \
-        _Pragma("unroll") for (int i = 0; i < CPT; ++i) {                                                 \
-            const int g = tid + i * NT;                                                                   \
+        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                              \
+            const int g = tid + i_ * NT;                                                                  \
             const int r = g / (D / 8), cc = g % (D / 8);                                                  \
             const int rr = (r & 32) | (((r >> 2) & 3) << 3) | (((r >> 4) & 1) << 2) | (r & 3);            \
-            *reinterpret_cast<u32x4_t *>(&ks[(buf_) * K_STAGE + rr * K_LD + cc * 8]) = kreg[i];             \
+            *reinterpret_cast<u32x4_t *>(&ks[(buf_) * K_STAGE + rr * K_LD + cc * 8]) = kreg[i_];          \
+        }                                                                                                 \
+    }
+#define LVX_ATTN_LSTORE_V(buf_)                                                                           \
+    {                                                                                                     \
+        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                              \
+            const int g = tid + i_ * NT;                                                                  \
             const int d = g / (KT / 8), kc = g % (KT / 8);                                                \
-            *reinterpret_cast<u32x4_t *>(&vs[(buf_) * V_STAGE + d * V_LD + kc * 8]) = vreg[i];              \
+            *reinterpret_cast<u32x4_t *>(&vs[(buf_) * V_STAGE + d * V_LD + kc * 8]) = vreg[i_];           \
         }                                                                                                 \
     }
 
@@ -97,76 +120,138 @@ __global__ void __launch_bounds__(64 * NWAVES)
         for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
     float mc = -INFINITY;  // running maximum, already multiplied by c_exp2
     float l_run = 0.f;
+    f32x16_t s[2];
+    bf16x8_t pb[2][2];
 
-    LVX_ATTN_GLOAD(0);
-    LVX_ATTN_LSTORE(0);
+    // S(0) = K(0) Q^T from K buffer 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
+#define LVX_ATTN_S0()                                                                                          \
+    {                                                                                                          \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                     \
+            _Pragma("unroll") for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;                                     \
+            const bf16_t *kr = &ks[(kb * 32 + l32) * K_LD + hh * 8];                                           \
+            bf16x8_t a[MK];                                                                                    \
+            _Pragma("unroll") for (int m = 0; m < MK; ++m) a[m] = *reinterpret_cast<const bf16x8_t *>(kr + 16 * m); \
+            _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
+                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], qf[m], s[kb], 0, 0, 0);                  \
+        }                                                                                                      \
+    }
+    // Matrix phase X(j): O^T += V(j)^T P(j)^T from V buffer j&1, then S(j+1) = K(j+1) Q^T from K buffer (j+1)&1 (on the
+    // last tile the S part recomputes the last tile; its result is never used).  One basic block of NV + NK MFMAs, each
+    // fed by one 16-byte LDS fragment.  The fragment reads run PD MFMAs ahead of their use through a ring of PD
+    // registers, and the scheduler is told to keep that order (PD reads, then MFMA / read pairs, then PD MFMAs), so an
+    // MFMA never waits for a read issued just before it.
+    // Consecutive MFMAs target different accumulators (round robin over the DB blocks of O^T, then over the two
+    // 32-key blocks of S), so none has to wait for the previous one's result.
+    //   fragment f < NV :  r = f / DB: V^T rows 32*(f%DB).., keys 32*(r/2) + 8*(r%2) ..   -> o[f%DB] += frag * pb[r/2][r%2]
+    //   fragment f >= NV:  g = f - NV: K rows 32*(g%2).., dims 16*(g/2) ..                -> s[g%2] += frag * qf[g/2]
+#define LVX_ATTN_FRAG(f_)                                                                                              \
+    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 32 * V_LD + ((((f_) / DB) >> 1) & 1) * 32 + (((f_) / DB) & 1) * 8) \
+               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 1) * 32 * K_LD + (((f_) - NV) >> 1) * 16))
+#define LVX_ATTN_X(j_)                                                                                         \
+    {                                                                                                          \
+        __builtin_amdgcn_s_setprio(2); /* the matrix phase wins instruction arbitration over the other wave's VALU */ \
+        const int tn_ = (j_) + 1 < n_tiles ? (j_) + 1 : (j_);                                                  \
+        const bf16_t *vr = &vs[((j_) & 1) * V_STAGE + l32 * V_LD + 16 * hh];                                   \
+        const bf16_t *kr = &ks[(tn_ & 1) * K_STAGE + l32 * K_LD + hh * 8];                                     \
+        bf16x8_t fr[PD];                                                                                       \
+        _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) s[0][j] = 0.f;                                          \
+        _Pragma("unroll") for (int j = 0; j < 16; ++j) s[1][j] = 0.f;                                          \
+        _Pragma("unroll") for (int f = 0; f < NV + NK; ++f) {                                                  \
+            const bf16x8_t a = fr[f % PD];                                                                     \
+            if (f + PD < NV + NK) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                          \
+            if (f < NV)                                                                                        \
+                o[f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[((f / DB) >> 1) & 1][(f / DB) & 1], o[f % DB], 0, 0, 0); \
+            else                                                                                               \
+                s[(f - NV) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[(f - NV) >> 1], s[(f - NV) & 1], 0, 0, 0); \
+        }                                                                                                      \
+        __builtin_amdgcn_sched_group_barrier(0x100, PD, 0);                                                    \
+        _Pragma("unroll") for (int f = 0; f < NV + NK - PD; ++f) {                                             \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
+        }                                                                                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, PD, 0);                                                    \
+        __builtin_amdgcn_s_setprio(0);                                                                         \
+    }
+    // vector phase: accumulator register v of block kb holds key  t*64 + kb*32 + 16*hh + v  for query l32
+#define LVX_ATTN_Y(t_)                                                                                         \
+    {                                                                                                          \
+        if ((t_) == n_tiles - 1 && (n_keys % KT) != 0) {                                                       \
+            int lim_ = n_keys - (t_) * KT - 16 * hh; /* keys of this lane's first block that are valid */      \
+            asm volatile("" : "+v"(lim_));           /* keep the 32 compares out of the loop preheader */      \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v)    \
+                if (kb * 32 + v >= lim_) s[kb][v] = -INFINITY;                                                 \
+        }                                                                                                      \
+        float tmax = s[0][0];                                                                                  \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v)        \
+            tmax = fmaxf(tmax, s[kb][v]);                                                                      \
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));                                                              \
+        const float tmc = tmax * c_exp2;                                                                       \
+        const bool need = tmc > mc + 6.0f;                                                                     \
+        if (__any(need)) {                                                                                     \
+            const float alpha = need ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;                                \
+            if (need) mc = tmc;                                                                                \
+            l_run *= alpha;                                                                                    \
+            _Pragma("unroll") for (int i = 0; i < DB; ++i) _Pragma("unroll") for (int j = 0; j < 16; ++j)      \
+                o[i][j] *= alpha;                                                                              \
+        }                                                                                                      \
+        float lsum = 0.f;                                                                                      \
+        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) {      \
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));                     \
+            lsum += p;                                                                                         \
+            pb[kb][v >> 3][v & 7] = (__bf16)p;                                                                 \
+        }                                                                                                      \
+        l_run += lsum;                                                                                         \
+    }
+    // stage(i): registers (loaded one period ago) -> LDS, then start the loads of stage i+1
+#define LVX_ATTN_STAGE(i_)                                        \
+    {                                                             \
+        if ((i_) < n_tiles) {                                     \
+            LVX_ATTN_LSTORE_V((i_) & 1);                          \
+            if ((i_) + 1 < n_tiles) {                             \
+                LVX_ATTN_LSTORE_K(((i_) + 1) & 1);                \
+                LVX_ATTN_GLOAD_V((i_) + 1);                       \
+                if ((i_) + 2 < n_tiles) LVX_ATTN_GLOAD_K((i_) + 2); \
+            }                                                     \
+        }                                                         \
+    }
+
+    LVX_ATTN_GLOAD_K(0);
+    LVX_ATTN_LSTORE_K(0);
+    LVX_ATTN_GLOAD_V(0);
+    if (n_tiles > 1) LVX_ATTN_GLOAD_K(1);
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < n_tiles) LVX_ATTN_GLOAD(t + 1);
-
-        f32x16_t s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;
-            const bf16_t *kr = &ks[buf * K_STAGE + (kb * 32 + l32) * K_LD + hh * 8];
-#pragma unroll
-            for (int m = 0; m < MK; ++m) {
-                const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(kr + 16 * m);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[m], s[kb], 0, 0, 0);
-            }
-        }
-        // accumulator register v of block kb holds key  t*64 + kb*32 + 16*hh + v  for query l32
-        if (t == n_tiles - 1 && (n_keys % KT) != 0) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (t * KT + kb * 32 + 16 * hh + v >= n_keys) s[kb][v] = -INFINITY;
-        }
-        float tmax = s[0][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[kb][v]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float tmc = tmax * c_exp2;
-        const bool need = tmc > mc + 6.0f;
-        if (__any(need)) {
-            const float alpha = need ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;
-            if (need) mc = tmc;
-            l_run *= alpha;
-#pragma unroll
-            for (int i = 0; i < DB; ++i)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) o[i][j] *= alpha;
-        }
-        bf16x8_t pb[2][2];
-        float lsum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));
-                lsum += p;
-                pb[kb][v >> 3][v & 7] = (__bf16)p;
-            }
-        l_run += lsum;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-            const bf16_t *vr = &vs[buf * V_STAGE + (db * 32 + l32) * V_LD + 16 * hh];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int mm = 0; mm < 2; ++mm) {
-                    const bf16x8_t a = *reinterpret_cast<const bf16x8_t *>(vr + kb * 32 + 8 * mm);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[kb][mm], o[db], 0, 0, 0);
-                }
-        }
-        if (t + 1 < n_tiles) LVX_ATTN_LSTORE(buf ^ 1);
+    // Each group runs its own straight-line loop (no per-phase branching inside the loop body); both execute the same
+    // number of barriers: 2 before the loop and 2 per iteration.
+    if (grp == 0) {
+        LVX_ATTN_S0();
         __syncthreads();
+        LVX_ATTN_Y(0);
+        LVX_ATTN_STAGE(0);
+        __syncthreads();
+        for (int i = 1; i < n_tiles; ++i) {
+            LVX_ATTN_X(i - 1);
+            __syncthreads();
+            LVX_ATTN_Y(i);
+            LVX_ATTN_STAGE(i);
+            __syncthreads();
+        }
+        LVX_ATTN_X(n_tiles - 1);
+        __syncthreads();
+        __syncthreads();
+    } else {
+        LVX_ATTN_STAGE(0);
+        __syncthreads();
+        LVX_ATTN_S0();
+        __syncthreads();
+        for (int i = 1; i <= n_tiles; ++i) {
+            LVX_ATTN_Y(i - 1);
+            LVX_ATTN_STAGE(i);
+            __syncthreads();
+            LVX_ATTN_X(i - 1);
+            __syncthreads();
+        }
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
