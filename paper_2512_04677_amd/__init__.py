@@ -199,7 +199,7 @@ def lvx_chunk_attention(cache, layer, q, scale, out, n_q=None):
 
 def lvx_linear(a, w, c, epi=EPI_STORE, resid=None, gate=None, M=None):
     M = a.shape[0] if M is None else M
-    N, K = w.shape
+    N, K = w.shape[0], w.shape[1]
     _check(load().lvx_linear(_ptr(a), a.stride(0), _ptr(w), w.stride(0), _ptr(c), c.stride(0), M, N, K, epi,
                              _ptr(resid), resid.stride(0) if resid is not None else 0, _ptr(gate), _stream()))
 
