@@ -100,9 +100,10 @@ def main():
     L = args.layers
 
     t_setup = time.perf_counter()
-    layers = [S.block_weights(d, p["ffn"], l, "bench", std=0.02, device=dev, on_device_draw=True) for l in range(L)]
+    ROW_PAD = 64  # weight rows padded by 128 bytes (row stride in_features + 64), see include/lvx.h
+    layers = [S.block_weights(d, p["ffn"], l, "bench", std=0.02, device=dev, on_device_draw=True, row_pad=ROW_PAD) for l in range(L)]
     rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
-    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"], ldw_d=d + ROW_PAD, ldw_ffn=p["ffn"] + ROW_PAD)
     cache = lvx.KVCache(lvx.cache_desc(L, H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"]), dev)
     for l in range(L):
         sk = S.randn_bf16_device((sink_n, d), S.seed_of("bench_sk", l), 1.0, dev)

@@ -182,6 +182,9 @@ lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float 
  *   x += Attn(RMSNorm(LN(x) Wc_q^T), RMSNorm(ctx Wc_k^T), ctx Wc_v^T) Wc_o^T;
  *   x += gate2 * (gelu_tanh((LN(x)(1+scale2)+shift2) W_1^T) W_2^T).
  * mod6: fp32 [6][d] = shift1, scale1, gate1, shift2, scale2, gate2; NULL = 0,0,1,0,0,1.
+ * Weight rows may be padded (ldw_d / ldw_ffn): a row stride of in_features + 64 elements keeps consecutive rows off the
+ * same memory channel when in_features * 2 bytes is a multiple of 2 KiB (5120 and 13824 both are) and is measurably
+ * faster; the library pads its own workspace rows the same way.
  * ------------------------------------------------------------------------------------------------ */
 typedef struct {
     const void *W_qkv;  /* [3d][d] rows: q, k, v */
@@ -196,6 +199,8 @@ typedef struct {
 typedef struct {
     int32_t n_layers;
     int32_t d_ffn;
+    int32_t ldw_d;                     /* row stride (elements) of the weights with in_features = d_model; 0 = dense */
+    int32_t ldw_ffn;                   /* row stride (elements) of W_2 (in_features = d_ffn); 0 = dense */
     lvx_rope_desc_t rope;              /* n_heads*head_dim = d_model; must agree with the cache descriptor */
     const lvx_block_weights_t *blocks; /* host array [n_layers] of device pointers */
 } lvx_stage_t;

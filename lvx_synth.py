@@ -69,12 +69,15 @@ def block_weight_shapes(d, ffn):
     }
 
 
-def block_weights(d, ffn, layer, tag, std=0.02, device="cpu", on_device_draw=False):
-    """One block's weights ~ N(0, std) in bf16, RMSNorm gains = 1 (fp32)."""
+def block_weights(d, ffn, layer, tag, std=0.02, device="cpu", on_device_draw=False, row_pad=0):
+    """One block's weights ~ N(0, std) in bf16, RMSNorm gains = 1 (fp32).  With row_pad > 0 each matrix is the
+    [:, :in_features] view of an [out, in_features + row_pad] allocation (row stride in + row_pad)."""
     w = {}
     for name, shape in block_weight_shapes(d, ffn).items():
         s = seed_of(tag, "layer", layer, name)
-        w[name] = randn_bf16_device(shape, s, std, device) if on_device_draw else randn_bf16(shape, s, std, device=device)
+        shape = (shape[0], shape[1] + row_pad)
+        t = randn_bf16_device(shape, s, std, device) if on_device_draw else randn_bf16(shape, s, std, device=device)
+        w[name] = t[:, :shape[1] - row_pad] if row_pad else t
     for g in ("g_q", "g_k", "gc_q", "gc_k"):
         w[g] = torch.ones(d, dtype=torch.float32, device=device)
     return w

@@ -49,7 +49,8 @@ class BlockWeights(C.Structure):
 
 
 class Stage(C.Structure):
-    _fields_ = [("n_layers", C.c_int32), ("d_ffn", C.c_int32), ("rope", RopeDesc), ("blocks", C.POINTER(BlockWeights))]
+    _fields_ = [("n_layers", C.c_int32), ("d_ffn", C.c_int32), ("ldw_d", C.c_int32), ("ldw_ffn", C.c_int32), ("rope", RopeDesc),
+                ("blocks", C.POINTER(BlockWeights))]
 
 
 # name -> (restype, argtypes); the list the header declares
@@ -212,7 +213,7 @@ def lvx_layernorm_modulate(x, shift, scale, eps, u):
 class StageHandle:
     """Host-side stage descriptor: keeps the weight tensors alive and holds the C structs."""
 
-    def __init__(self, layers, rope, d_ffn):
+    def __init__(self, layers, rope, d_ffn, ldw_d=0, ldw_ffn=0):
         self.layers = layers
         self.n = len(layers)
         self.blocks = (BlockWeights * self.n)()
@@ -221,7 +222,7 @@ class StageHandle:
                 t = w.get(name)
                 setattr(self.blocks[i], name, None if t is None else t.data_ptr())
         self.rope = rope
-        self.c = Stage(self.n, d_ffn, rope, C.cast(self.blocks, C.POINTER(BlockWeights)))
+        self.c = Stage(self.n, d_ffn, ldw_d, ldw_ffn, rope, C.cast(self.blocks, C.POINTER(BlockWeights)))
 
 
 def lvx_workspace_bytes(stage, n_tokens, n_ctx):

@@ -44,7 +44,12 @@ struct prof_scope_t {
 struct ws_layout_t {
     size_t u, big, ctx_kv, pack_k, pack_v, h, total;  // byte offsets
     int cap_ctx;
+    int64_t ld_u, ld_qkv, ld_cq, ld_ffn, ld_ckv;      // padded row strides (elements) of the bf16 workspace matrices
 };
+
+// Rows of the workspace matrices are padded by 64 elements (128 bytes): with d_model = 5120 or d_ffn = 13824 a dense row is
+// a multiple of 2 KiB, which makes the GEMM's 8-rows-per-instruction loads pile up on few memory channels.
+constexpr int WS_PAD = 64;
 
 size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 
@@ -53,10 +58,15 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     const size_t d = (size_t)s->rope.n_heads * s->rope.head_dim;
     const size_t wide = 3 * d > (size_t)s->d_ffn ? 3 * d : (size_t)s->d_ffn;
     w.cap_ctx = (n_ctx + LVX_KEY_TILE - 1) / LVX_KEY_TILE * LVX_KEY_TILE;
+    w.ld_u = (int64_t)d + WS_PAD;
+    w.ld_qkv = (int64_t)3 * d + WS_PAD;
+    w.ld_cq = (int64_t)d + WS_PAD;
+    w.ld_ffn = (int64_t)s->d_ffn + WS_PAD;
+    w.ld_ckv = (int64_t)2 * d + WS_PAD;
     size_t off = 0;
-    w.u = off;       off += round256((size_t)n_tokens * d * 2);
-    w.big = off;     off += round256((size_t)n_tokens * wide * 2);
-    w.ctx_kv = off;  off += round256((size_t)n_ctx * 2 * d * 2);
+    w.u = off;       off += round256((size_t)n_tokens * w.ld_u * 2);
+    w.big = off;     off += round256((size_t)n_tokens * (wide + WS_PAD) * 2);
+    w.ctx_kv = off;  off += round256((size_t)n_ctx * w.ld_ckv * 2);
     w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.h = off;       off += round256((size_t)n_tokens * d * 4);  // fp32 residual stream
@@ -73,6 +83,8 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
     LVX_REQUIRE(d % 64 == 0 && s->d_ffn > 0 && s->d_ffn % 64 == 0, LVX_ERR_SHAPE, "d_model %d and d_ffn %d must be multiples of 64", d,
                 s->d_ffn);
     LVX_REQUIRE(n_tokens > 0 && n_ctx > 0, LVX_ERR_SHAPE, "n_tokens %d and n_ctx %d must be positive", n_tokens, n_ctx);
+    LVX_REQUIRE((s->ldw_d == 0 || (s->ldw_d >= d && s->ldw_d % 8 == 0)) && (s->ldw_ffn == 0 || (s->ldw_ffn >= s->d_ffn && s->ldw_ffn % 8 == 0)),
+                LVX_ERR_SHAPE, "weight row strides must be 0 (dense) or multiples of 8 not below in_features");
     if (c != nullptr) {
         LVX_REQUIRE(c->desc.n_heads == s->rope.n_heads && c->desc.head_dim == s->rope.head_dim && c->desc.frame_h == s->rope.frame_h &&
                         c->desc.frame_w == s->rope.frame_w,
@@ -104,38 +116,41 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     const float *shift1 = mod6 ? mod6 : nullptr, *scale1 = mod6 ? mod6 + d : nullptr, *gate1 = mod6 ? mod6 + 2 * d : nullptr;
     const float *shift2 = mod6 ? mod6 + 3 * d : nullptr, *scale2 = mod6 ? mod6 + 4 * d : nullptr, *gate2 = mod6 ? mod6 + 5 * d : nullptr;
 
+    const int64_t ldw = s->ldw_d > 0 ? s->ldw_d : d, ldw2 = s->ldw_ffn > 0 ? s->ldw_ffn : f;
+    const int64_t ldu = L.ld_u, ldq = L.ld_qkv, ldc = L.ld_cq, ldf = L.ld_ffn, ldk = L.ld_ckv;
+
     // self-attention branch
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, d, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(lvx_linear(u, d, w.W_qkv, d, big, 3 * d, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, 3 * d, w.g_q, w.g_k, n, t0, big, big + d, 3 * d, st)); }
-    { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, 3 * d, chunk_index, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, 3 * d, n, scale, u, d, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(lvx_linear(u, d, w.W_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(lvx_linear(u, ldu, w.W_qkv, ldw, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
+    { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, ldq, n, scale, u, ldu, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(lvx_linear(u, ldu, w.W_o, ldw, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st)); }
 
     // cross-attention to the audio + text context
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, d, st)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st)); }
     {
         prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
-        LVX_TRY(lvx_linear(u, d, w.Wc_q, d, big, d, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-        LVX_TRY(lvx_linear(ctx, d, w.Wc_k, d, ctx_kv, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-        LVX_TRY(lvx_linear(ctx, d, w.Wc_v, d, ctx_kv + d, 2 * d, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(lvx_linear(u, ldu, w.Wc_q, ldw, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(lvx_linear(ctx, d, w.Wc_k, ldw, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(lvx_linear(ctx, d, w.Wc_v, ldw, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
     }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
-    if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, d, w.gc_q, nullptr, n, 0, big, nullptr, d, st));
-    if (w.gc_k) LVX_TRY(lvx_rope3d(&norm_only, nullptr, ctx_kv, 2 * d, nullptr, w.gc_k, n_ctx, 0, nullptr, ctx_kv, 2 * d, st));
+    if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st));
+    if (w.gc_k) LVX_TRY(lvx_rope3d(&norm_only, nullptr, ctx_kv, ldk, nullptr, w.gc_k, n_ctx, 0, nullptr, ctx_kv, ldk, st));
     if (L.cap_ctx != n_ctx) {  // keys past n_ctx in the last tile must be finite
         LVX_TRY(lvx_launch_fill_zero(pack_k, (size_t)L.cap_ctx * d * 2, st));
         LVX_TRY(lvx_launch_fill_zero(pack_v, (size_t)L.cap_ctx * d * 2, st));
     }
-    LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, 2 * d, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
-    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, d, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, d, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(lvx_linear(u, d, w.Wc_o, d, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st)); }
+    LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
+    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(lvx_linear(u, ldu, w.Wc_o, ldw, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st)); }
 
     // feed-forward
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, d, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(lvx_linear(u, d, w.W_1, d, big, f, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(lvx_linear(big, f, w.W_2, f, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, ldu, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(lvx_linear(u, ldu, w.W_1, ldw, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(lvx_linear(big, ldf, w.W_2, ldw2, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st)); }
     return LVX_OK;
 }
 

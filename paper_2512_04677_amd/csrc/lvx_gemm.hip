@@ -12,6 +12,8 @@
 // that XCD's L2.
 #include "lvx_internal.h"
 
+#include <stdlib.h>
+
 namespace {
 
 constexpr int BK = 64;
@@ -23,6 +25,42 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
     const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
     const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
     return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// Epilogue shared by both kernels.  Accumulator register 4g+r of fragment (i,j) holds row m0 + 32i + 8g + r and column
+// n0 + 32j of C (m0, n0 already include the lane's 4*hh / l32 offsets): for a fixed register, 32 lanes write 32 consecutive
+// columns.  Interior tiles take the branch-free path; only tiles on the M or N edge check every element.
+template <int FM, int FN, int EPI>
+__device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R, int64_t ldr,
+                                                  const float *__restrict__ gate, int M, int N, int m0, int n0) {
+    const bool interior = (m0 - (m0 & 4) + FM * 32 <= M) && (n0 - (n0 & 31) + FN * 32 <= N);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = n0 + j * 32;
+        if (!interior && n >= N) continue;
+        float gt = 1.f;
+        if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const size_t row0 = (size_t)(m0 + i * 32);
+            bf16_t *cp = C + row0 * ldc + n;
+            float *cpf = reinterpret_cast<float *>(C) + row0 * ldc + n;
+            const bf16_t *rp = R + row0 * ldr + n;
+            const float *rpf = reinterpret_cast<const float *>(R) + row0 * ldr + n;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int dm = 8 * (e >> 2) + (e & 3);
+                if (!interior && m0 + i * 32 + dm >= M) continue;
+                float v = acc[i][j][e];
+                if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
+                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
+                if (EPI == LVX_EPI_RESID_GATE_F32)
+                    cpf[(size_t)dm * ldc] = rpf[(size_t)dm * ldr] + gt * v;
+                else
+                    cp[(size_t)dm * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+            }
+        }
+    }
 }
 
 // Scheduling hint for one half of a slab step: MFMA number I is followed by one LDS fragment read (while I < NDSR), by
@@ -206,33 +244,159 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     }
     if (kt < n_k) LVX_GEMM_STEP(0, ra1, rw1, last);
 
-    // accumulator register 4g+r of fragment (i,j): row m = 32i + 8g + 4hh + r, column n = 32j + l32
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = tn * BN + wn * WTN + j * 32 + l32;
-        if (n >= N) continue;
-        float gt = 1.f;
-        if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = tm * BM + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                if (m >= M) continue;
-                float v = acc[i][j][e];
-                if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
-                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(R[(size_t)m * ldr + n]) + gt * v;
-                if (EPI == LVX_EPI_RESID_GATE_F32) {
-                    const float *rf = reinterpret_cast<const float *>(R);
-                    reinterpret_cast<float *>(C)[(size_t)m * ldc + n] = rf[(size_t)m * ldr + n] + gt * v;
-                } else {
-                    C[(size_t)m * ldc + n] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
-                }
-            }
-    }
+    lvx_gemm_epilogue<FM, FN, EPI>(acc, C, ldc, R, ldr, gate, M, N, tm * BM + wm * WTM + 4 * hh, tn * BN + wn * WTN + l32);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+// ------------------------------------------------------------------------------------------------------------------
+// Direct-to-LDS variant (the one lvx_linear launches).  gfx950's global_load_lds_dwordx4 moves 16 bytes per lane from
+// global memory straight into LDS (LDS byte address = M0 + 16*lane), so a slab needs no staging registers, no ds_write
+// and no trip through the register file; the pipeline depth is set by LDS stages (three 48 KB stages for a 128x256 tile)
+// instead of by registers.  A DMA wave-instruction fills 1024 contiguous LDS bytes = 8 rows of 64 bf16, so rows cannot be
+// padded; bank conflicts are avoided by an XOR swizzle instead: the 16-byte chunk c of LDS row r holds global chunk
+// c ^ ((r >> 1) & 7) (the lane simply fetches that chunk), and a fragment read of k-chunk c goes to position
+// c ^ ((r >> 1) & 7): 16 consecutive rows then cover 16 distinct 16-byte units of the 256-byte bank row.
+// The loads are issued through inline asm with explicit s_waitcnt vmcnt(n): the compiler would otherwise wait for ALL
+// outstanding DMA before any LDS read that might alias, which would undo the multi-stage pipeline.
+__device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
+    lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,
+                        int M, int N, int K, const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n,
+                        int per_xcd) {
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+    constexpr int FM = WTM / 32, FN = WTN / 32;
+    constexpr int NKK = BK / 16;
+    constexpr int ROW_B = BK * 2;  // bytes per LDS row (unpadded)
+    constexpr int A_B = BM * ROW_B, STAGE_B = (BM + BN) * ROW_B;
+    constexpr int NSTAGE = 3;
+    constexpr int N_INSTR = (BM + BN) / 8;  // DMA wave-instructions per slab (8 rows each)
+    static_assert(N_INSTR % NW == 0 && (BM / 8) % NW == 0, "DMA instructions must divide over the waves, A and W separately");
+    constexpr int QPW = N_INSTR / NW;   // per wave
+    constexpr int A_Q = (BM / 8) / NW;  // of which the first A_Q fetch A rows
+    static_assert(NKK == 4, "the k-step grouping below assumes 4 k-steps per slab");
+
+    __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * STAGE_B];
+
+    const int total = tiles_m * tiles_n;
+    const int widx = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (widx >= total) return;
+    const int band = widx / (GROUP_M * tiles_n);
+    const int first_m = band * GROUP_M;
+    const int band_m = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    const int in_band = widx - band * GROUP_M * tiles_n;
+    const int tm = first_m + in_band % band_m;
+    const int tn = in_band / band_m;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    // DMA instruction q of this wave covers stage rows 8*(wave + NW*q) .. +7 (A rows first, then W rows); lane -> (row, position)
+    uint32_t doff[QPW];
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) {
+        const int row_s = 8 * (wave + NW * q) + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row_s >> 1) & 7);
+        if (q < A_Q) {
+            int r = tm * BM + row_s;
+            if (r > M - 1) r = M - 1;
+            doff[q] = (uint32_t)(((size_t)r * lda + chunk * 8) * sizeof(bf16_t));
+        } else {
+            int r = tn * BN + (row_s - BM);
+            if (r > N - 1) r = N - 1;
+            doff[q] = (uint32_t)(((size_t)r * ldw + chunk * 8) * sizeof(bf16_t));
+        }
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 1024);
+#define LVX_DMA_ISSUE(stage_, kt_, q_)                                                                                      \
+    lvx_dma16(reinterpret_cast<const char *>((q_) < A_Q ? A : W) + (size_t)(kt_) * ROW_B, doff[q_],                         \
+              lds_wave + (uint32_t)((stage_) * STAGE_B + (q_) * NW * 1024))
+
+    // fragment reads: lane (l32, hh) reads row l32 of a 32-row block, k-chunk 2*kk + hh at its swizzled position
+    const int swz = (l32 >> 1) & 7;
+    const char *a_rd = lds + (wm * WTM + l32) * ROW_B;
+    const char *w_rd = lds + A_B + (wn * WTN + l32) * ROW_B;
+    bf16x8_t af[2][FM], wf[2][FN];
+#define LVX_DMA_READ_FRAGS(stage_, kk_)                                                                                     \
+    {                                                                                                                       \
+        const int co_ = (((kk_) * 2 + hh) ^ swz) * 16 + (stage_) * STAGE_B;                                                 \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) af[(kk_) & 1][i] = *reinterpret_cast<const bf16x8_t *>(a_rd + i * 32 * ROW_B + co_); \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j) wf[(kk_) & 1][j] = *reinterpret_cast<const bf16x8_t *>(w_rd + j * 32 * ROW_B + co_); \
+    }
+#define LVX_DMA_MFMAS(kk_)                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j)            \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(kk_) & 1][i], wf[(kk_) & 1][j], acc[i][j], 0, 0, 0);
+
+    f32x16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int n_k = K / BK;
+    const int last = n_k - 1;
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(0, 0, q);
+#pragma unroll
+    for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(1, (last < 1 ? last : 1), q);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QPW) : "memory");
+    __syncthreads();
+    LVX_DMA_READ_FRAGS(0, 0);
+
+    // Slab t is in stage t % 3.  Per slab: three MFMA groups that each read the next k-step's fragments and issue a third
+    // of the DMA for slab t+2 (into the stage that was read during slab t-1); then wait until this wave's DMA for slab t+1
+    // has landed, one workgroup barrier, and the fourth group, which already reads k-step 0 of slab t+1.
+    int cur = 0, nxt = 1, nx2 = 2;
+    for (int t = 0; t < n_k; ++t) {
+        const int kt_load = t + 2 < last ? t + 2 : last;
+        LVX_DMA_READ_FRAGS(cur, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_MFMAS(0);
+#pragma unroll
+        for (int q = 0; q < QPW; ++q)
+            if ((q * 3) / QPW == 0) LVX_DMA_ISSUE(nx2, kt_load, q);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_READ_FRAGS(cur, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_MFMAS(1);
+#pragma unroll
+        for (int q = 0; q < QPW; ++q)
+            if ((q * 3) / QPW == 1) LVX_DMA_ISSUE(nx2, kt_load, q);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_READ_FRAGS(cur, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_MFMAS(2);
+#pragma unroll
+        for (int q = 0; q < QPW; ++q)
+            if ((q * 3) / QPW == 2) LVX_DMA_ISSUE(nx2, kt_load, q);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QPW) : "memory");
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_READ_FRAGS(nxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        LVX_DMA_MFMAS(3);
+        __builtin_amdgcn_sched_barrier(0);
+        const int tmp = cur;
+        cur = nxt;
+        nxt = nx2;
+        nx2 = tmp;
+    }
+    // no DMA may still be in flight when the workgroup releases its LDS
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    lvx_gemm_epilogue<FM, FN, EPI>(acc, C, ldc, R, ldr, gate, M, N, tm * BM + wm * WTM + 4 * hh, tn * BN + wn * WTN + l32);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DMA>
 lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, bf16_t *C, int64_t ldc, int M, int N, int K, int epi,
                     const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -240,16 +404,21 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
     const int per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
-    hipLaunchKernelGGL((lvx_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, R, ldr, \
-                       gate, tiles_m, tiles_n, per_xcd)
-    if (epi == LVX_EPI_STORE)
+    if (DMA)                                                                                                                       \
+        hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
+                           R, ldr, gate, tiles_m, tiles_n, per_xcd);                                                               \
+    else                                                                                                                           \
+        hipLaunchKernelGGL((lvx_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, R,  \
+                           ldr, gate, tiles_m, tiles_n, per_xcd)
+    if (epi == LVX_EPI_STORE) {
         LVX_GEMM_LAUNCH(LVX_EPI_STORE);
-    else if (epi == LVX_EPI_GELU_TANH)
+    } else if (epi == LVX_EPI_GELU_TANH) {
         LVX_GEMM_LAUNCH(LVX_EPI_GELU_TANH);
-    else if (epi == LVX_EPI_RESID_GATE)
+    } else if (epi == LVX_EPI_RESID_GATE) {
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE);
-    else
+    } else {
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE_F32);
+    }
 #undef LVX_GEMM_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -276,6 +445,10 @@ extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *d
         LVX_REQUIRE(ldr >= N, LVX_ERR_SHAPE, "bad residual leading dimension");
     }
     if (M == 0) return LVX_OK;
-    return launch<128, 256, 2, 4>((const bf16_t *)dev_a, lda, (const bf16_t *)dev_w, ldw, (bf16_t *)dev_c, ldc, M, N, K, (int)epi,
+    static const bool staged = getenv("LVX_GEMM_STAGED") != nullptr;  // register-staged kernel, kept for comparison runs
+    if (staged)
+        return launch<128, 256, 2, 4, false>((const bf16_t *)dev_a, lda, (const bf16_t *)dev_w, ldw, (bf16_t *)dev_c, ldc, M, N, K, (int)epi,
+                                             (const bf16_t *)dev_resid, ldr, dev_gate, (hipStream_t)stream);
+    return launch<128, 256, 2, 4, true>((const bf16_t *)dev_a, lda, (const bf16_t *)dev_w, ldw, (bf16_t *)dev_c, ldc, M, N, K, (int)epi,
                                   (const bf16_t *)dev_resid, ldr, dev_gate, (hipStream_t)stream);
 }

@@ -118,10 +118,12 @@ def test_error_paths_without_a_device():
     assert lib.lvx_layernorm_modulate(p, 5120, None, None, 1e-6, 4, 5124, p, 5120, None) == 2
     # stage / workspace
     blocks = (lvx.BlockWeights * 1)()
-    st = lvx.Stage(1, 13824, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
+    st = lvx.Stage(1, 13824, 0, 0, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
     ws = lib.lvx_workspace_bytes(C.byref(st), 4680, 544)
     assert ws >= 4680 * 5120 * 2 * 2 + 4680 * 15360 * 2
-    st_bad = lvx.Stage(1, 13824 + 8, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
+    st_bad = lvx.Stage(1, 13824 + 8, 0, 0, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
+    st_bad2 = lvx.Stage(1, 13824, 5120 + 4, 0, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
+    assert lib.lvx_workspace_bytes(C.byref(st_bad2), 4680, 544) == 0
     assert lib.lvx_workspace_bytes(C.byref(st_bad), 4680, 544) == 0
     assert lib.lvx_dit_block(C.byref(st), 0, None, p, 4680, p, 544, None, 0, 1, p, ws, None) == 1
     assert lib.lvx_denoise_stage(None, None, p, 4680, p, 544, None, -0.25, 0, 1, p, ws, None) == 1

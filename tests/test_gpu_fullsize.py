@@ -126,9 +126,9 @@ def test_config4_dit_block_sampled_rows(lvx):
     for those tokens are checked against the oracle's own K-hat / V."""
     d, sink_n, n = dims(P)
     H, D, W = P["n_heads"], P["head_dim"], P["window"]
-    w = S.block_weights(d, P["ffn"], 0, "cfg4", std=0.02, device=DEV, on_device_draw=True)
+    w = S.block_weights(d, P["ffn"], 0, "cfg4", std=0.02, device=DEV, on_device_draw=True, row_pad=64)   # padded rows, as bench.py
     rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
-    stage = lvx.StageHandle([w], rope, P["ffn"])
+    stage = lvx.StageHandle([w], rope, P["ffn"], ldw_d=d + 64, ldw_ffn=P["ffn"] + 64)
     cache = make_cache(lvx, P)
     lvx.lvx_kvcache_set_sink(cache, 0, S.randn_bf16_device((sink_n, d), 2, 1.0, DEV), S.randn_bf16_device((sink_n, d), 3, 1.0, DEV))
     for i in range(W):
