@@ -76,7 +76,7 @@ def main():
     ap.add_argument("--layers", type=int, default=40, help="debug only: fewer layers is NOT the benchmark workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-level", type=int, default=2, help="1: time attention launches only, 2: every kernel class")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=390)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=2340)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one denoise stage = one timestep of the pipeline on one GPU); "
