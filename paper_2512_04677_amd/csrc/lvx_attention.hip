@@ -7,8 +7,9 @@
 //     holds scores of ONE query (column lane%32) for 16 keys per 32-key block, so the online-softmax statistics are
 //     per-lane scalars (one cross-half exchange per tile) and the exponentiated scores are already in the B-operand
 //     layout of the second MFMA, O^T += V^T P^T, with no LDS round trip.
-//   * K tiles ([64 keys][D]) and V^T tiles ([D][64 keys], stored transposed in the cache) are double-buffered in LDS;
-//     rows are padded so that 16 consecutive lanes reading 16 bytes each hit disjoint banks.
+//   * K tiles ([64 keys][D]) and V^T tiles ([D][64 keys], stored transposed in the cache) go global -> LDS directly
+//     (global_load_lds_dwordx4, no staging registers) into rings of four tiles each; rows are XOR-swizzled so that 16
+//     consecutive lanes reading 16 bytes each hit disjoint banks.
 //   * the two waves of each SIMD are run half a period apart (matrix phase against vector phase, see "pipeline" below),
 //     so the softmax VALU work of one wave hides under the MFMA work of the other.
 //   * K rows are placed in LDS in the order the accumulator layout wants (lane i of the A operand reads LDS row i),
@@ -24,28 +25,39 @@ namespace {
 
 constexpr int KT = LVX_KEY_TILE;
 
+// direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane
+__device__ __forceinline__ void lvx_attn_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+}
+
 template <int D, int NWAVES>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
                          int64_t ld_out, int n_qtiles, int total_wg, int per_xcd) {
-    constexpr int NT = 64 * NWAVES;
     constexpr int QT = 32 * NWAVES;
-    constexpr int K_LD = D + 8;   // bf16 per padded K row
-    constexpr int V_LD = KT + 8;  // bf16 per padded V^T row
-    constexpr int K_STAGE = KT * K_LD;
-    constexpr int V_STAGE = D * V_LD;
-    constexpr int CH = KT * D / 8;  // 16-byte chunks per tile (same for K and V^T)
-    static_assert(CH % NT == 0, "tile chunks must divide over the threads");
-    constexpr int CPT = CH / NT;
     constexpr int MK = D / 16;  // MFMA k-steps over head_dim
     constexpr int DB = D / 32;  // 32-row blocks of O^T
     constexpr int NV = DB * 4;  // V^T fragments (= PV MFMAs) per 64-key tile
     constexpr int NK = 2 * MK;  // K fragments (= QK MFMAs) per 64-key tile
     constexpr int PD = 6;       // LDS fragment prefetch distance, in MFMAs
+    // LDS: a ring of NS K tiles ([64 keys][D], rows of D*2 bytes) and a ring of NS V^T tiles ([D][64 keys], rows of 128 bytes),
+    // filled by direct-to-LDS loads.  A DMA wave-instruction writes 1024 contiguous bytes, so rows cannot be padded; a 16-byte
+    // chunk c of row r is stored at position c ^ swz(r) instead (the lane fetches the matching global chunk), with
+    // swz(r) = r & 15 for 256-byte rows and (r >> 1) & 7 for 128-byte rows: 16 consecutive rows then hit 16 distinct
+    // 16-byte units of a 256-byte bank row.
+    constexpr int NS = 4;
+    constexpr int TILE_B = KT * D * 2;        // bytes per K tile = per V^T tile
+    constexpr int K_ROW_B = D * 2;
+    constexpr int K_RPI = 1024 / K_ROW_B;     // K rows per DMA instruction (4 or 8)
+    constexpr int K_CPR = D / 8;              // 16-byte chunks per K row (16 or 8)
+    constexpr int N_DMA = TILE_B / 1024;      // DMA instructions per tile (K and V^T alike)
+    static_assert(N_DMA % NWAVES == 0, "DMA instructions must divide over the waves");
+    constexpr int DPW = N_DMA / NWAVES;       // per wave, per tile
+    constexpr int V_ROW_B = KT * 2;           // 128
 
-    __shared__ __attribute__((aligned(16))) bf16_t ks[2 * K_STAGE];
-    __shared__ __attribute__((aligned(16))) bf16_t vs[2 * V_STAGE];
+    __shared__ __attribute__((aligned(1024))) char ks[NS * TILE_B];
+    __shared__ __attribute__((aligned(1024))) char vs[NS * TILE_B];
 
     // XCD-aware decode: consecutive block ids go to consecutive XCDs; give each XCD a contiguous range of work
     const int xcd = blockIdx.x & 7;
@@ -69,49 +81,77 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 
     const int n_tiles = (n_keys + KT - 1) / KT;
-    const u32x4_t *k_src = reinterpret_cast<const u32x4_t *>(kp + (size_t)head * cap * D);
-    const u32x4_t *v_src = reinterpret_cast<const u32x4_t *>(vtp + (size_t)head * cap * D);
+    const char *k_src = reinterpret_cast<const char *>(kp + (size_t)head * cap * D);   // K tile t at k_src + t * TILE_B
+    const char *v_src = reinterpret_cast<const char *>(vtp + (size_t)head * cap * D);  // V^T tile t at v_src + t * TILE_B
+
+    // ---- staging (direct to LDS) -----------------------------------------------------------------------------------------
+    // DMA instruction e of this wave covers LDS rows [rows_per_instr * (wave + NWAVES*e), +rows_per_instr) of a tile.
+    // K: LDS row rr holds key r(rr) (accumulator-row order: key r = 32*blk + 16h + 4g + r4 sits at LDS row 32*blk + 8g + 4h + r4,
+    // which makes each half-wave's 16 scores per block belong to 16 consecutive keys).
+    uint32_t kdoff[DPW], vdoff[DPW];
+#pragma unroll
+    for (int e = 0; e < DPW; ++e) {
+        const int j = wave + NWAVES * e;
+        {
+            const int rr = K_RPI * j + lane / K_CPR;  // LDS row
+            const int pos = lane % K_CPR;
+            const int key = (rr & 32) | (((rr >> 2) & 1) << 4) | (((rr >> 3) & 3) << 2) | (rr & 3);
+            const int swz = K_CPR == 16 ? (rr & 15) : ((rr >> 1) & 7);
+            kdoff[e] = (uint32_t)(key * K_ROW_B + (pos ^ swz) * 16);
+        }
+        {
+            const int rr = 8 * j + (lane >> 3);  // LDS row = head-dim index d
+            const int pos = lane & 7;
+            vdoff[e] = (uint32_t)(rr * V_ROW_B + (pos ^ ((rr >> 1) & 7)) * 16);
+        }
+    }
+    const uint32_t ks_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)ks;
+    const uint32_t vs_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)vs;
+    const uint32_t ks_wave = __builtin_amdgcn_readfirstlane(ks_base + wave * 1024);
+    const uint32_t vs_wave = __builtin_amdgcn_readfirstlane(vs_base + wave * 1024);
+    const int last_tile = n_tiles - 1;
+#define LVX_ATTN_DMA_K(t_)                                                                                                  \
+    {                                                                                                                       \
+        const int tt_ = (t_) < last_tile ? (t_) : last_tile;                                                                \
+        _Pragma("unroll") for (int e = 0; e < DPW; ++e)                                                                     \
+            lvx_attn_dma16(k_src + (size_t)tt_ * TILE_B, kdoff[e], ks_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
+    }
+#define LVX_ATTN_DMA_V(t_)                                                                                                  \
+    {                                                                                                                       \
+        const int tt_ = (t_) < last_tile ? (t_) : last_tile;                                                                \
+        _Pragma("unroll") for (int e = 0; e < DPW; ++e)                                                                     \
+            lvx_attn_dma16(v_src + (size_t)tt_ * TILE_B, vdoff[e], vs_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
+    }
+    // stage u = { V^T(u), K(u+1) }: what the matrix phase X(u) reads
+#define LVX_ATTN_STAGE_DMA(u_) \
+    {                          \
+        LVX_ATTN_DMA_V(u_);    \
+        LVX_ATTN_DMA_K((u_) + 1); \
+    }
+#define LVX_ATTN_WAIT_DMA(n_) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n_) : "memory")
+
+    // fragment read offsets inside a tile (bytes): K fragment m of 32-key block kb: row kb*32 + l32, chunk (2m + hh) ^ swz;
+    // V^T fragment (db, kb, mm): row db*32 + l32, chunk (4kb + 2hh + mm) ^ swz
+    const int k_swz = K_CPR == 16 ? (l32 & 15) : ((l32 >> 1) & 7);
+    const int v_swz = (l32 >> 1) & 7;
+    int kfo[MK], vfo[4];
+#pragma unroll
+    for (int m = 0; m < MK; ++m) kfo[m] = l32 * K_ROW_B + (((2 * m + hh) ^ k_swz) * 16);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vfo[c] = l32 * V_ROW_B + ((((c >> 1) * 4 + 2 * hh + (c & 1)) ^ v_swz) * 16);
 
     // ---- pipeline -------------------------------------------------------------------------------------------------
-    // A wave alternates between a matrix phase X(t) = { S(t+1) = K(t+1) Q^T ; O += V(t)^T P(t) } (32 MFMAs, LDS reads)
-    // and a vector phase Y(t) = { online softmax of S(t) -> P(t) ; stage the next tiles global -> LDS }.  The two waves
-    // that share a SIMD (wave w and w + NWAVES/2) run half a period apart, with a workgroup barrier after every phase:
-    // while group 0 is in X the other is in Y, so the matrix core and the vector ALU of each SIMD are busy at the same
-    // time instead of both waves queueing for the same unit.
-    //   iteration i, first half :  group 0: X(i-1) (S(0) only before the loop)  group 1: Y(i-1), stage(i)
-    //   iteration i, second half:  group 0: Y(i), stage(i)                      group 1: X(i-1)
-    // stage(i) writes V(i) into V buffer i&1 and K(i+1) into K buffer (i+1)&1; both were last read by group 1 in
-    // X(i-2), one barrier before the first half of iteration i, and are first needed by group 0 in X(i).
+    // A wave alternates between a matrix phase X(t) = { O += V(t)^T P(t) ; S(t+1) = K(t+1) Q^T } (MFMAs fed from LDS)
+    // and a vector phase Y(t) = online softmax of S(t) -> P(t).  The two waves that share a SIMD (wave w and
+    // w + NWAVES/2) run half a period apart, with a workgroup barrier after every phase: while group 0 is in X the
+    // other is in Y, so the matrix core and the vector ALU of each SIMD are busy at the same time.
+    //   iteration i, first half :  group 0: X(i-1) (S(0) only before the loop)  group 1: Y(i-1)
+    //   iteration i, second half:  group 0: Y(i)                                group 1: X(i-1)
+    // Staging: every wave issues the DMA of stage i+2 at the end of the first half of iteration i and, before the second
+    // half's barrier, waits until its own DMA of stage i has landed (two younger stages may still be in flight); stage i
+    // is first read by group 0 in X(i), right after that barrier.  Stage i-2, whose ring slots stage i+2 overwrites, was
+    // last read in the second half of iteration i-1 (group 1's X(i-2)), which ended at a barrier before the issue.
     const int grp = wave / (NWAVES / 2);
-    u32x4_t kreg[CPT], vreg[CPT];
-#define LVX_ATTN_GLOAD_K(t_)                                                                   \
-    {                                                                                          \
-        const u32x4_t *kt_ = k_src + (size_t)(t_) * CH;                                        \
-        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) kreg[i_] = kt_[tid + i_ * NT];      \
-    }
-#define LVX_ATTN_GLOAD_V(t_)                                                                   \
-    {                                                                                          \
-        const u32x4_t *vt_ = v_src + (size_t)(t_) * CH;                                        \
-        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) vreg[i_] = vt_[tid + i_ * NT];      \
-    }
-    // key row r = 32*blk + 16h + 4g4 + r4 goes to LDS row 32*blk + 8*g4 + 4h + r4 (accumulator row order)
-#define LVX_ATTN_LSTORE_K(buf_)                                                                           \
-    {                                                                                                     \
-        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                              \
-            const int g = tid + i_ * NT;                                                                  \
-            const int r = g / (D / 8), cc = g % (D / 8);                                                  \
-            const int rr = (r & 32) | (((r >> 2) & 3) << 3) | (((r >> 4) & 1) << 2) | (r & 3);            \
-            *reinterpret_cast<u32x4_t *>(&ks[(buf_) * K_STAGE + rr * K_LD + cc * 8]) = kreg[i_];          \
-        }                                                                                                 \
-    }
-#define LVX_ATTN_LSTORE_V(buf_)                                                                           \
-    {                                                                                                     \
-        _Pragma("unroll") for (int i_ = 0; i_ < CPT; ++i_) {                                              \
-            const int g = tid + i_ * NT;                                                                  \
-            const int d = g / (KT / 8), kc = g % (KT / 8);                                                \
-            *reinterpret_cast<u32x4_t *>(&vs[(buf_) * V_STAGE + d * V_LD + kc * 8]) = vreg[i_];           \
-        }                                                                                                 \
-    }
 
     f32x16_t o[DB];
 #pragma unroll
@@ -123,36 +163,34 @@ __global__ void __launch_bounds__(64 * NWAVES)
     f32x16_t s[2];
     bf16x8_t pb[2][2];
 
-    // S(0) = K(0) Q^T from K buffer 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
+    // S(0) = K(0) Q^T from K slot 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
 #define LVX_ATTN_S0()                                                                                          \
     {                                                                                                          \
         _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                     \
             _Pragma("unroll") for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;                                     \
-            const bf16_t *kr = &ks[(kb * 32 + l32) * K_LD + hh * 8];                                           \
             bf16x8_t a[MK];                                                                                    \
-            _Pragma("unroll") for (int m = 0; m < MK; ++m) a[m] = *reinterpret_cast<const bf16x8_t *>(kr + 16 * m); \
+            _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
+                a[m] = *reinterpret_cast<const bf16x8_t *>(ks + kb * 32 * K_ROW_B + kfo[m]);                   \
             _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], qf[m], s[kb], 0, 0, 0);                  \
         }                                                                                                      \
     }
-    // Matrix phase X(j): O^T += V(j)^T P(j)^T from V buffer j&1, then S(j+1) = K(j+1) Q^T from K buffer (j+1)&1 (on the
-    // last tile the S part recomputes the last tile; its result is never used).  One basic block of NV + NK MFMAs, each
-    // fed by one 16-byte LDS fragment.  The fragment reads run PD MFMAs ahead of their use through a ring of PD
-    // registers, and the scheduler is told to keep that order (PD reads, then MFMA / read pairs, then PD MFMAs), so an
-    // MFMA never waits for a read issued just before it.
-    // Consecutive MFMAs target different accumulators (round robin over the DB blocks of O^T, then over the two
-    // 32-key blocks of S), so none has to wait for the previous one's result.
-    //   fragment f < NV :  r = f / DB: V^T rows 32*(f%DB).., keys 32*(r/2) + 8*(r%2) ..   -> o[f%DB] += frag * pb[r/2][r%2]
-    //   fragment f >= NV:  g = f - NV: K rows 32*(g%2).., dims 16*(g/2) ..                -> s[g%2] += frag * qf[g/2]
+    // Matrix phase X(j): O^T += V(j)^T P(j)^T from V slot j%NS, then S(j+1) = K(j+1) Q^T from K slot (j+1)%NS (past the last
+    // tile the slot holds a copy of the last tile; that S is never used).  One basic block of NV + NK MFMAs, each fed by one
+    // 16-byte LDS fragment.  The fragment reads run PD MFMAs ahead of their use through a ring of PD registers, and the
+    // scheduler is told to keep that order (PD reads, then MFMA / read pairs, then PD MFMAs), so an MFMA never waits for a
+    // read issued just before it.  Consecutive MFMAs target different accumulators (round robin over the DB blocks of O^T,
+    // then over the two 32-key blocks of S), so none has to wait for the previous one's result.
+    //   fragment f < NV :  r = f / DB: V^T rows 32*(f%DB).., key chunk (r/2, r%2)   -> o[f%DB] += frag * pb[r/2][r%2]
+    //   fragment f >= NV:  g = f - NV: K rows 32*(g%2).., dims 16*(g/2) ..          -> s[g%2] += frag * qf[g/2]
 #define LVX_ATTN_FRAG(f_)                                                                                              \
-    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 32 * V_LD + ((((f_) / DB) >> 1) & 1) * 32 + (((f_) / DB) & 1) * 8) \
-               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 1) * 32 * K_LD + (((f_) - NV) >> 1) * 16))
+    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 32 * V_ROW_B + vfo[((f_) / DB) & 3])            \
+               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 1) * 32 * K_ROW_B + kfo[(((f_) - NV) >> 1) % MK]))
 #define LVX_ATTN_X(j_)                                                                                         \
     {                                                                                                          \
         __builtin_amdgcn_s_setprio(2); /* the matrix phase wins instruction arbitration over the other wave's VALU */ \
-        const int tn_ = (j_) + 1 < n_tiles ? (j_) + 1 : (j_);                                                  \
-        const bf16_t *vr = &vs[((j_) & 1) * V_STAGE + l32 * V_LD + 16 * hh];                                   \
-        const bf16_t *kr = &ks[(tn_ & 1) * K_STAGE + l32 * K_LD + hh * 8];                                     \
+        const char *vr = vs + ((j_) & (NS - 1)) * TILE_B;                                                      \
+        const char *kr = ks + (((j_) + 1) & (NS - 1)) * TILE_B;                                                \
         bf16x8_t fr[PD];                                                                                       \
         _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
         _Pragma("unroll") for (int j = 0; j < 16; ++j) s[0][j] = 0.f;                                          \
@@ -203,56 +241,49 @@ __global__ void __launch_bounds__(64 * NWAVES)
         }                                                                                                      \
         l_run += lsum;                                                                                         \
     }
-    // stage(i): registers (loaded one period ago) -> LDS, then start the loads of stage i+1
-#define LVX_ATTN_STAGE(i_)                                        \
-    {                                                             \
-        if ((i_) < n_tiles) {                                     \
-            LVX_ATTN_LSTORE_V((i_) & 1);                          \
-            if ((i_) + 1 < n_tiles) {                             \
-                LVX_ATTN_LSTORE_K(((i_) + 1) & 1);                \
-                LVX_ATTN_GLOAD_V((i_) + 1);                       \
-                if ((i_) + 2 < n_tiles) LVX_ATTN_GLOAD_K((i_) + 2); \
-            }                                                     \
-        }                                                         \
-    }
 
-    LVX_ATTN_GLOAD_K(0);
-    LVX_ATTN_LSTORE_K(0);
-    LVX_ATTN_GLOAD_V(0);
-    if (n_tiles > 1) LVX_ATTN_GLOAD_K(1);
+    LVX_ATTN_DMA_K(0);
+    LVX_ATTN_STAGE_DMA(0);
+    LVX_ATTN_STAGE_DMA(1);
+    LVX_ATTN_WAIT_DMA(4 * DPW);  // K(0) landed; stages 0 and 1 may be in flight
     __syncthreads();
 
-    // Each group runs its own straight-line loop (no per-phase branching inside the loop body); both execute the same
-    // number of barriers: 2 before the loop and 2 per iteration.
+    // Each group runs its own straight-line loop; both execute the same number of barriers (2 per iteration) and the same
+    // DMA issue / wait sequence (issue in the first half, wait in the second half of every iteration).
     if (grp == 0) {
         LVX_ATTN_S0();
         __syncthreads();
         LVX_ATTN_Y(0);
-        LVX_ATTN_STAGE(0);
+        LVX_ATTN_STAGE_DMA(2);
+        LVX_ATTN_WAIT_DMA(4 * DPW);  // stage 0 landed
         __syncthreads();
         for (int i = 1; i < n_tiles; ++i) {
             LVX_ATTN_X(i - 1);
+            LVX_ATTN_STAGE_DMA(i + 2);
             __syncthreads();
             LVX_ATTN_Y(i);
-            LVX_ATTN_STAGE(i);
+            LVX_ATTN_WAIT_DMA(4 * DPW);  // stage i landed
             __syncthreads();
         }
         LVX_ATTN_X(n_tiles - 1);
         __syncthreads();
         __syncthreads();
     } else {
-        LVX_ATTN_STAGE(0);
         __syncthreads();
         LVX_ATTN_S0();
+        LVX_ATTN_STAGE_DMA(2);
+        LVX_ATTN_WAIT_DMA(4 * DPW);
         __syncthreads();
         for (int i = 1; i <= n_tiles; ++i) {
             LVX_ATTN_Y(i - 1);
-            LVX_ATTN_STAGE(i);
+            if (i < n_tiles) LVX_ATTN_STAGE_DMA(i + 2);
             __syncthreads();
             LVX_ATTN_X(i - 1);
+            if (i < n_tiles) LVX_ATTN_WAIT_DMA(4 * DPW);
             __syncthreads();
         }
     }
+    LVX_ATTN_WAIT_DMA(0);  // no DMA may still be in flight when the workgroup releases its LDS
 
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / l_tot;
