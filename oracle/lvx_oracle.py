@@ -17,7 +17,12 @@ What the paper fixes and where (own words):
     ("History Corrupt", Sec. 3.3); the latent moves by an Euler step ``x <- x + v*dt``, ``dt = -1/T``.
   * Sec. 3.3 / Sec. 4.1: one sink frame stays in the cache for ever; ``w = 4``; blocks of 3 latents.
   * Appendix D, "Rolling RoPE": rotary position indices grow per generated frame; the sink carries
-    its own temporal index (0 unless re-assigned).
+    its own temporal index (0 unless re-assigned); with Rolling RoPE that index is re-assigned at
+    every block step to a value slightly ahead of the current block's, by recomputing the rotary
+    embedding of the cached sink keys (Phi(sink) in Alg. 3 / Alg. 4).  The offset itself is not
+    given: the caller supplies the index ("parity unpinned" for its value, the transform is pinned).
+  * Sec. 3.3 / Appendix D, Adaptive Attention Sink: after the first block the sink is replaced by
+    the model's own first generated latent, which needs a second warm-up to produce its K/V.
 
 What the paper does not give (hidden size, heads, FFN width, norm placement, RoPE split, GELU form) is
 taken from the build's workload description; every such reading is listed in the design doc.
@@ -145,11 +150,28 @@ class RollingKVCache:
     def __init__(self, window):
         self.window = int(window)
         self.sink = None                 # (k, v) of the sink frame, never evicted (Sec. 3.3)
+        self.sink_source = None          # un-rotated sink keys when the sink's RoPE index is re-assigned per step
         self.blocks = deque()            # (chunk_index, k, v), oldest first
         self.evicted = []                # chunk indices dropped so far, in order
 
     def set_sink(self, k, v):
         self.sink = (np.asarray(k, F64), np.asarray(v, F64))
+        self.sink_source = None
+
+    def set_sink_source(self, k_src, v):
+        """Install a sink whose keys are kept UN-rotated (normalised, before RoPE), so that its temporal index can be
+        re-assigned at every block step (Appendix D, "Rolling RoPE"); also what the sink swap of the Adaptive
+        Attention Sink installs (Sec. 3.3; Alg. 3, the assignment after the first block).  The sink keys are
+        undefined until ``roll_sink`` is called."""
+        self.sink_source = np.asarray(k_src, F64)
+        self.sink = (None, np.asarray(v, F64))
+
+    def roll_sink(self, t_sink, cfg):
+        """Phi(sink) of Alg. 3 / Alg. 4: the sink keys become RoPE(source) with the sink's first frame at temporal
+        index ``t_sink`` (spatial indices are those of the frame grid).  Always recomputed from the un-rotated
+        source, never from the previous rotation; the sink values are not touched."""
+        k = rope3d(self.sink_source, int(t_sink), cfg.frame_h, cfg.frame_w, cfg.rope_axes, cfg.theta)
+        self.sink = (k, self.sink[1])
 
     def visible(self, k_cur, v_cur):
         """Keys/values a forward of the current block sees: sink, cached blocks (oldest first), itself."""
@@ -303,6 +325,45 @@ def dit_block_rows(x_rows, positions, w, k_visible, v_visible, ctx, mod6, cfg):
     u2 = modulate(x, sh2, sc2, cfg.eps)
     x = x + g2 * ffn(u2, w)
     return x, k, v
+
+
+def sink_keys_values(u, w, cfg):
+    """Un-rotated sink keys and sink values of one layer: K projection + RMSNorm (no RoPE), V projection."""
+    H, D = cfg.n_heads, cfg.head_dim
+    d = H * D
+    qkv = linear(u, w["W_qkv"])
+    k, v = qkv[:, d:2 * d], qkv[:, 2 * d:]
+    if w.get("g_k") is not None:
+        k = rmsnorm(k, w["g_k"], cfg.eps)
+    n = u.shape[0]
+    return k.reshape(n, H, D), v.reshape(n, H, D)
+
+
+def sink_prefill(x_sink, layers, caches, ctx, mod6_per_layer, t_sink, cfg):
+    """Run the sink frame's tokens x_sink [sink_tokens, d] through the stack and install, per layer, the sink's
+    un-rotated keys and its values in ``caches`` (the warm-up that the sink swap of the Adaptive Attention Sink needs,
+    Appendix D).  Reading (the paper does not say what the sink attends to): the sink frame attends to itself only,
+    with its own frame at temporal index ``t_sink``; every other step of the block is the one of ``dit_block``.
+    The ring of past blocks is not touched.  Returns the stack's output for the sink tokens (not used by the method)."""
+    x = np.asarray(x_sink, F64)
+    H, D = cfg.n_heads, cfg.head_dim
+    d = H * D
+    for l, w in enumerate(layers):
+        sh1, sc1, g1, sh2, sc2, g2 = _mod6(None if mod6_per_layer is None else mod6_per_layer[l], d)
+        u = modulate(x, sh1, sc1, cfg.eps)
+        k_src, v = sink_keys_values(u, w, cfg)
+        caches[l].set_sink_source(k_src, v)
+        caches[l].roll_sink(t_sink, cfg)
+        q = linear(u, w["W_qkv"])[:, :d]
+        if w.get("g_q") is not None:
+            q = rmsnorm(q, w["g_q"], cfg.eps)
+        q = rope3d(q.reshape(-1, H, D), t_sink, cfg.frame_h, cfg.frame_w, cfg.rope_axes, cfg.theta)
+        o = attention(q, caches[l].sink[0], caches[l].sink[1], 1.0 / np.sqrt(D))
+        x = x + g1 * linear(o.reshape(-1, d), w["W_o"])
+        x = x + cross_attention(x, np.asarray(ctx, F64), w, cfg)
+        u2 = modulate(x, sh2, sc2, cfg.eps)
+        x = x + g2 * ffn(u2, w)
+    return x
 
 
 def denoise_stage(x, layers, caches, ctx, mod6_per_layer, dt, chunk_index, t0, cfg):

@@ -336,3 +336,134 @@ def test_block_rows_form_equals_whole_chunk_block():
         np.testing.assert_allclose(yr, y[rows], rtol=1e-11, atol=1e-12)
         np.testing.assert_array_equal(kr, k_new[rows])
         np.testing.assert_array_equal(vr, v_new[rows])
+
+
+# ---------------------------------------------------------------- Rolling RoPE / adaptive attention sink (Appendix D)
+def test_rolling_sink_keeps_query_to_sink_scores_independent_of_rollout_position():
+    """With the sink's temporal index held a fixed offset ahead of the current block's, the logits between a block's
+    queries and the sink do not depend on how far the rollout has advanced (the relative distance stays bounded);
+    with the sink left at index 0 they do."""
+    cfg = tiny_cfg()
+    H, D, n = cfg.n_heads, cfg.head_dim, cfg.frame_tokens
+    q_raw = rng.standard_normal((n, H, D))
+    c = O.RollingKVCache(cfg.window)
+    c.set_sink_source(rng.standard_normal((n, H, D)), rng.standard_normal((n, H, D)))
+    delta = 2
+
+    def logits(t_q, t_sink):
+        c.roll_sink(t_sink, cfg)
+        q = O.rope3d(q_raw, t_q, cfg.frame_h, cfg.frame_w, cfg.rope_axes, cfg.theta)
+        return np.einsum("nhd,mhd->hnm", q, c.sink[0])
+
+    a = logits(1, 1 + delta)
+    b = logits(40001, 40001 + delta)
+    np.testing.assert_allclose(a, b, rtol=0, atol=1e-9)          # fp64 angles at 4e4 lose ~1e-11
+    assert np.abs(logits(40001, 0) - logits(1, 0)).max() > 1e-2   # a static sink index drifts
+
+
+def test_roll_sink_rotates_only_temporal_pairs_from_the_source():
+    cfg = tiny_cfg()                       # rope axes (4, 2, 2): pairs 0,1 temporal; pair 2 row; pair 3 column
+    H, D, n = cfg.n_heads, cfg.head_dim, cfg.frame_tokens
+    src = rng.standard_normal((n, H, D))
+    v = rng.standard_normal((n, H, D))
+    c = O.RollingKVCache(cfg.window)
+    c.set_sink_source(src, v)
+    c.roll_sink(5, cfg)
+    k5 = c.sink[0].copy()
+    c.roll_sink(9, cfg)
+    k9 = c.sink[0].copy()
+    # values never change; spatial pairs do not depend on the temporal index
+    np.testing.assert_array_equal(c.sink[1], v)
+    np.testing.assert_array_equal(k5[..., 4:], k9[..., 4:])
+    # temporal pair k as a complex number: index 9 = index 5 turned by 4 * theta^(-2k/4)
+    for k in range(2):
+        z5 = k5[..., 2 * k] + 1j * k5[..., 2 * k + 1]
+        z9 = k9[..., 2 * k] + 1j * k9[..., 2 * k + 1]
+        np.testing.assert_allclose(z9, z5 * np.exp(1j * 4 * cfg.theta ** (-2.0 * k / 4)), rtol=1e-12, atol=1e-13)
+    # rolling is recomputed from the source: going 5 -> 9 -> 5 gives back the first result bit for bit
+    c.roll_sink(5, cfg)
+    np.testing.assert_array_equal(c.sink[0], k5)
+    # index 0 on a one-row, one-column grid is no rotation at all
+    one = O.StageConfig(n_heads=H, head_dim=D, frame_h=1, frame_w=1, chunk_frames=1, window=1, rope_axes=cfg.rope_axes)
+    c1 = O.RollingKVCache(1)
+    c1.set_sink_source(src[:1], v[:1])
+    c1.roll_sink(0, one)
+    np.testing.assert_array_equal(c1.sink[0], src[:1])
+
+
+def test_sink_prefill_special_cases_and_reduction_to_block_rows():
+    cfg = tiny_cfg()
+    d, H, D = cfg.d_model, cfg.n_heads, cfg.head_dim
+    layers = [tiny_weights(cfg), tiny_weights(cfg)]
+    ctx = rng.standard_normal((5, d))
+    mod6 = [rng.standard_normal((6, d)) * 0.3 + np.array([0, 0, 1, 0, 0, 1])[:, None] for _ in layers]
+    x = rng.standard_normal((cfg.frame_tokens, d))
+    caches = [fresh_cache(cfg, 20 + l) for l in range(2)]
+    for c in caches:                                            # a ring with history, which prefill must not touch
+        c.append(0, rng.standard_normal((cfg.chunk_tokens, H, D)), rng.standard_normal((cfg.chunk_tokens, H, D)))
+    ring_before = [list(c.blocks) for c in caches]
+    t_sink = 7
+    y = O.sink_prefill(x, layers, caches, ctx, mod6, t_sink, cfg)
+    for c, rb in zip(caches, ring_before):
+        assert len(c.blocks) == len(rb) and all(a is b for a, b in zip(c.blocks, rb)) and c.evicted == []
+    # layer by layer this is the block evaluated on the sink's tokens with the sink's own K/V as the only visible keys
+    h = x
+    pos = O.token_positions(cfg.frame_tokens, t_sink, cfg.frame_h, cfg.frame_w)
+    for l, w in enumerate(layers):
+        u = O.modulate(h, mod6[l][0], mod6[l][1], cfg.eps)
+        q, k, v = O.qkv_for_cache(u, w, cfg, t_sink)
+        np.testing.assert_allclose(caches[l].sink[0], k, rtol=1e-13, atol=1e-14)
+        np.testing.assert_array_equal(caches[l].sink[1], v)
+        # the stored source is K before RoPE: row block [d, 2d) of the fused weight, normalised over all channels
+        k_lin = u @ w["W_qkv"][d:2 * d].T
+        k_src = k_lin / np.sqrt((k_lin ** 2).mean(-1, keepdims=True) + cfg.eps) * w["g_k"]
+        np.testing.assert_allclose(caches[l].sink_source.reshape(-1, d), k_src, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(v.reshape(-1, d), u @ w["W_qkv"][2 * d:].T, rtol=1e-12, atol=1e-13)
+        h, _, _ = O.dit_block_rows(h, pos, w, k, v, ctx, mod6[l], cfg)
+    np.testing.assert_allclose(y, h, rtol=1e-11, atol=1e-12)
+    # one-token sink: softmax over a single key is 1, so the attention output is that token's V
+    one = O.StageConfig(n_heads=H, head_dim=D, frame_h=1, frame_w=1, chunk_frames=1, window=1, rope_axes=cfg.rope_axes)
+    w = layers[0]
+    x1 = rng.standard_normal((1, d))
+    c1 = [O.RollingKVCache(1)]
+    y1 = O.sink_prefill(x1, [w], c1, ctx, None, 3, one)
+    u = O.layernorm(x1, one.eps)
+    mid = x1 + (u @ w["W_qkv"][2 * d:].T) @ w["W_o"].T
+    mid = mid + O.cross_attention(mid, ctx, w, one)
+    np.testing.assert_allclose(y1, mid + O.ffn(O.layernorm(mid, one.eps), w), rtol=1e-12, atol=1e-13)
+
+
+def test_streaming_with_sink_swap_and_rolling_index_runs_the_documented_sequence():
+    """Alg. 3 with both mechanisms, on the stage level: prefill the reference sink, run block 0, swap the sink for the
+    model's own output (second warm-up), then run blocks 1.. with the sink index re-assigned before every forward.
+    Checked against the same blocks evaluated row-wise with explicitly assembled visible keys."""
+    cfg = tiny_cfg()
+    d, H, D = cfg.d_model, cfg.n_heads, cfg.head_dim
+    layers = [tiny_weights(cfg)]
+    ctx = rng.standard_normal((5, d))
+    caches = [O.RollingKVCache(cfg.window)]
+    delta = 1
+    t0 = lambda i: 1 + cfg.chunk_frames * i
+    t_sink = lambda i: t0(i) + cfg.chunk_frames - 1 + delta
+    O.sink_prefill(rng.standard_normal((cfg.frame_tokens, d)), layers, caches, ctx, None, t_sink(0), cfg)
+    src_ref = caches[0].sink_source.copy()
+    outs = []
+    for i in range(5):
+        caches[0].roll_sink(t_sink(i), cfg)
+        x = rng.standard_normal((cfg.chunk_tokens, d))
+        # expected: rows form with the visible set assembled by hand
+        k_sink = O.rope3d(caches[0].sink_source, t_sink(i), cfg.frame_h, cfg.frame_w, cfg.rope_axes, cfg.theta)
+        u = O.modulate(x, 0.0, 0.0, cfg.eps)
+        q, k, v = O.qkv_for_cache(u, layers[0], cfg, t0(i))
+        kv = np.concatenate([k_sink] + [b[1] for b in caches[0].blocks] + [k], 0)
+        vv = np.concatenate([caches[0].sink[1]] + [b[2] for b in caches[0].blocks] + [v], 0)
+        want, _, _ = O.dit_block_rows(x, O.token_positions(cfg.chunk_tokens, t0(i), cfg.frame_h, cfg.frame_w), layers[0], kv, vv,
+                                      ctx, None, cfg)
+        y = O.denoise_stage(x, layers, caches, ctx, None, -0.25, i, t0(i), cfg)
+        np.testing.assert_allclose(y, x - 0.25 * want, rtol=1e-11, atol=1e-12)
+        outs.append(y)
+        if i == 0:   # sink swap: the first generated frame becomes the sink; its K/V come from a second warm-up
+            assert np.array_equal(caches[0].sink_source, src_ref)
+            O.sink_prefill(y[:cfg.frame_tokens], layers, caches, ctx, None, t_sink(1), cfg)
+            assert not np.array_equal(caches[0].sink_source, src_ref)
+            assert caches[0].chunk_ids() == [0]
