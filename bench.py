@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the denoise-stage hot path on one MI355X.
 
-A step = one pass of the whole hot path over one chunk: lvx_denoise_stage on 40 DiT blocks at the 14B shape
+A step = one pass of the whole hot path over one chunk: the sink's rotary re-indexing (all layers) followed by
+lvx_denoise_stage on 40 DiT blocks at the 14B shape
 (3 latent frames x 1560 tokens against the rolling cache: sink 1560 + 4 past chunks + self = 24 960 keys),
 synthetic seeded inputs and random-init weights, everything resident in HBM before the timed region.
 Prints ONE JSON line: latent frames/s (whole job, one GPU), plus
@@ -109,10 +110,11 @@ def main():
     rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
     stage = lvx.StageHandle(layers, rope, p["ffn"], ldw_d=d + ROW_PAD, ldw_ffn=p["ffn"] + ROW_PAD)
     cache = lvx.KVCache(lvx.cache_desc(L, H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"]), dev)
+    cache.attach_sink_source()   # un-rotated sink keys: the sink's rotary index is re-assigned before every forward (Rolling RoPE)
     for l in range(L):
         sk = S.randn_bf16_device((sink_n, d), S.seed_of("bench_sk", l), 1.0, dev)
         sv = S.randn_bf16_device((sink_n, d), S.seed_of("bench_sv", l), 1.0, dev)
-        lvx.lvx_kvcache_set_sink(cache, l, sk, sv)
+        lvx.lvx_kvcache_reset_sink(cache, l, sk, sv)
     ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, p["n_ctx"]), dtype=torch.uint8, device=dev)
     n_inputs = 8
     xs = [S.randn_bf16_device((n, d), S.seed_of("bench_x", i), 1.0, dev) for i in range(n_inputs)]
@@ -128,7 +130,9 @@ def main():
     def step():
         i = chunk[0]
         x.copy_(xs[i % n_inputs])
-        lvx.lvx_denoise_stage(stage, cache, x, ctxs[i % n_inputs], None, -0.25, i, 1 + 3 * i, ws)
+        t0 = 1 + p["chunk_frames"] * i
+        lvx.lvx_sink_rope_update(cache, rope, -1, t0 + p["chunk_frames"] + 1)   # Phi(sink): two frames ahead of the block's last
+        lvx.lvx_denoise_stage(stage, cache, x, ctxs[i % n_inputs], None, -0.25, i, t0, ws)
         chunk[0] += 1
 
     # fill the ring (setup, untimed): the steady state the paper's stage runs in has all window+1 slots occupied

@@ -146,6 +146,37 @@ lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc /* host */, const void *dev_
                         void *dev_q_out, void *dev_k_out, int64_t ld_out, lvx_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Rolling RoPE and the adaptive attention sink (Sec. 3.3; Appendix D; Phi(sink) and the sink assignment of Alg. 3 /
+ * Alg. 4).  The sink's rotary temporal index is re-assigned at every block step so that its distance to the current
+ * block stays bounded; the paper rewrites the cached sink keys in place.  Here the un-rotated (normalised) sink keys are
+ * kept beside the cache and every re-assignment rotates them afresh into the cache's sink rows, so rotations never
+ * compound their bf16 roundings over a long rollout.  The index itself ("slightly ahead of the current block") is the
+ * caller's: the paper gives no value.
+ *
+ *   lvx_sink_source_bytes           device bytes for the un-rotated sink keys of all layers ([layer][sink_keys][d] bf16)
+ *   lvx_kvcache_attach_sink_source  hands that storage (caller-owned, 256-byte aligned, alive as long as the handle) over
+ *   lvx_kvcache_reset_sink          installs a sink for `layer`: dev_k_src = normalised, NOT rotated keys, dev_v = values,
+ *                                   both token-major [sink_keys][ld] bf16 (bit-exact copies).  The ring is untouched.  Until
+ *                                   the next lvx_sink_rope_update the layer's sink keys are stale and lvx_chunk_attention /
+ *                                   lvx_dit_block / lvx_denoise_stage return LVX_ERR_STATE for it.
+ *   lvx_sink_rope_update            Phi: sink keys of `layer` (-1: every layer) := RoPE(source) with the sink's first frame
+ *                                   at temporal index t_sink, spatial indices from the frame grid; values untouched.
+ *   lvx_kvcache_get_sink_index      last t_sink applied to `layer`; -1 = reset but not rotated; -2 = static sink / none
+ *   lvx_kvcache_gather_sink_source  reads the stored source back, token-major [sink_keys][ld] (bit-exact)
+ * Errors: STATE without attached storage, on a layer whose sink came from lvx_kvcache_set_sink (already rotated, no
+ * source) or on a cache without sink segment; SHAPE if the rope descriptor disagrees with the cache; INVALID_ARG else.
+ * ------------------------------------------------------------------------------------------------ */
+size_t lvx_sink_source_bytes(const lvx_cache_desc_t *desc /* host */);
+lvx_status_t lvx_kvcache_attach_sink_source(lvx_kvcache_t *cache, void *dev_storage, size_t bytes);
+lvx_status_t lvx_kvcache_reset_sink(lvx_kvcache_t *cache, int32_t layer, const void *dev_k_src, const void *dev_v, int64_t ld,
+                                    lvx_stream_t stream);
+lvx_status_t lvx_sink_rope_update(lvx_kvcache_t *cache, const lvx_rope_desc_t *rope /* host */, int32_t layer, int32_t t_sink,
+                                  lvx_stream_t stream);
+lvx_status_t lvx_kvcache_get_sink_index(const lvx_kvcache_t *cache, int32_t layer, int32_t *out /* host */);
+lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *cache, int32_t layer, void *dev_k_src_out, int64_t ld,
+                                            lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Chunk-to-cache attention (Eq. 1; Appendix C attention paragraph: current tokens against the concatenation
  * of cached K/V and themselves):  O[n,h,:] = softmax_m(scale * <q[n,h,:], K[m,h,:]>) V[m,h,:] over the visible
  * prefix of `layer` (every key visible, no mask).  q, out: [n_q][ld] bf16.  bf16 MFMA, fp32 online softmax.
@@ -225,6 +256,16 @@ lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage /* host */, int32_t laye
 lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage /* host */, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
                                const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
+/* Warm-up of a sink frame (Appendix D: the sink swap of the adaptive attention sink needs a second warm-up to produce the
+ * new sink's K/V): the sink frame's tokens x_sink [sink_keys][d] bf16 run through all blocks; per layer the un-rotated,
+ * normalised keys and the values of these tokens are installed as the sink (as lvx_kvcache_reset_sink does) and rotated to
+ * temporal index t_sink.  Reading (the paper does not say): the sink frame attends to itself only; every other step is the
+ * block's.  The ring of past blocks is untouched.  dev_x_out (may be NULL) receives the stack's output for the sink tokens,
+ * [sink_keys][d] bf16.  workspace: lvx_workspace_bytes(stage, sink_keys, n_ctx).  Needs attached sink source storage. */
+lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage /* host */, lvx_kvcache_t *cache, const void *dev_x_sink, const void *dev_ctx,
+                              int32_t n_ctx, const float *dev_mod6_per_layer, int32_t t_sink, void *dev_x_out,
+                              void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Optional timing of the kernel classes inside lvx_dit_block / lvx_denoise_stage with HIP events recorded on the

@@ -75,6 +75,13 @@ SIGNATURES = {
     "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_dit_block_f32": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_denoise_stage": (C.c_int, [C.POINTER(Stage), _vp, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _vp, _sz, _vp]),
+    "lvx_sink_source_bytes": (_sz, [C.POINTER(CacheDesc)]),
+    "lvx_kvcache_attach_sink_source": (C.c_int, [_vp, _vp, _sz]),
+    "lvx_kvcache_reset_sink": (C.c_int, [_vp, _i32, _vp, _vp, _i64, _vp]),
+    "lvx_sink_rope_update": (C.c_int, [_vp, C.POINTER(RopeDesc), _i32, _i32, _vp]),
+    "lvx_kvcache_get_sink_index": (C.c_int, [_vp, _i32, C.POINTER(C.c_int32)]),
+    "lvx_kvcache_gather_sink_source": (C.c_int, [_vp, _i32, _vp, _i64, _vp]),
+    "lvx_sink_prefill": (C.c_int, [C.POINTER(Stage), _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "lvx_profile_set": (C.c_int, [_i32]),
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
@@ -147,6 +154,14 @@ class KVCache:
         h = C.c_void_p()
         _check(load().lvx_kvcache_init(C.byref(desc), _ptr(self.storage), nbytes, _stream(), C.byref(h)))
         self.handle = h
+        self.sink_source = None
+
+    def attach_sink_source(self):
+        """Allocates and hands over the storage for the un-rotated sink keys (Rolling RoPE / sink swap)."""
+        import torch
+        nbytes = load().lvx_sink_source_bytes(C.byref(self.desc))
+        self.sink_source = torch.empty(nbytes, dtype=torch.uint8, device=self.storage.device)
+        _check(load().lvx_kvcache_attach_sink_source(self.handle, _ptr(self.sink_source), nbytes))
 
     def close(self):
         if self.handle is not None:
@@ -162,6 +177,24 @@ class KVCache:
 
 def lvx_kvcache_set_sink(cache, layer, k, v, ld=None):
     _check(load().lvx_kvcache_set_sink(cache.handle, layer, _ptr(k), _ptr(v), ld if ld is not None else k.stride(0), _stream()))
+
+
+def lvx_kvcache_reset_sink(cache, layer, k_src, v, ld=None):
+    _check(load().lvx_kvcache_reset_sink(cache.handle, layer, _ptr(k_src), _ptr(v), ld if ld is not None else k_src.stride(0), _stream()))
+
+
+def lvx_sink_rope_update(cache, rope, layer, t_sink):
+    _check(load().lvx_sink_rope_update(cache.handle, C.byref(rope), layer, t_sink, _stream()))
+
+
+def lvx_kvcache_get_sink_index(cache, layer):
+    out = C.c_int32()
+    _check(load().lvx_kvcache_get_sink_index(cache.handle, layer, C.byref(out)))
+    return out.value
+
+
+def lvx_kvcache_gather_sink_source(cache, layer, k_src_out):
+    _check(load().lvx_kvcache_gather_sink_source(cache.handle, layer, _ptr(k_src_out), k_src_out.stride(0), _stream()))
 
 
 def lvx_chunk_append_evict(cache, layer, k, v, chunk_index, ld=None):
@@ -243,6 +276,11 @@ def lvx_denoise_stage(stage, cache, x, ctx, mod6_per_layer, dt, chunk_index, t0,
     _check(load().lvx_denoise_stage(C.byref(stage.c), cache.handle, _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0],
                                     _ptr(mod6_per_layer), dt, chunk_index, t0, _ptr(workspace),
                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def lvx_sink_prefill(stage, cache, x_sink, ctx, mod6_per_layer, t_sink, workspace, x_out=None):
+    _check(load().lvx_sink_prefill(C.byref(stage.c), cache.handle, _ptr(x_sink), _ptr(ctx), ctx.shape[0], _ptr(mod6_per_layer), t_sink,
+                                   _ptr(x_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def lvx_profile_set(level):

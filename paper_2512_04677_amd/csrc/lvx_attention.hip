@@ -343,6 +343,8 @@ extern "C" lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *c, int32_t laye
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "scale must be positive");
     const lvx_ring_state_t &s = c->state[layer];
     LVX_REQUIRE(s.key_count > 0, LVX_ERR_STATE, "layer %d has no visible keys (set the sink / append a chunk first)", layer);
+    LVX_REQUIRE(c->sink_t[layer] != LVX_SINK_STALE, LVX_ERR_STATE,
+                "layer %d: the sink was reset and its keys are not rotated yet (lvx_sink_rope_update)", layer);
     return lvx_launch_attention((const bf16_t *)dev_q, ld_q, n_q, c->desc.n_heads, c->desc.head_dim, lvx_cache_k(c, layer),
                                 lvx_cache_vt(c, layer), c->cap_keys, s.key_count, scale, (bf16_t *)dev_out, ld_out, (hipStream_t)stream);
 }

@@ -74,7 +74,7 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     return w;
 }
 
-lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_tokens, int n_ctx) {
+lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_tokens, int n_ctx, bool allow_sink_rows = false) {
     LVX_REQUIRE(s != nullptr, LVX_ERR_INVALID_ARG, "stage descriptor is NULL");
     LVX_REQUIRE(s->blocks != nullptr && s->n_layers > 0, LVX_ERR_INVALID_ARG, "stage has no blocks");
     LVX_REQUIRE(s->rope.n_heads > 0 && (s->rope.head_dim == 64 || s->rope.head_dim == 128), LVX_ERR_UNSUPPORTED,
@@ -90,7 +90,8 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
                         c->desc.frame_w == s->rope.frame_w,
                     LVX_ERR_SHAPE, "stage and cache descriptors disagree on heads / head_dim / frame size");
         LVX_REQUIRE(c->desc.n_layers >= s->n_layers, LVX_ERR_SHAPE, "cache has %d layers, stage has %d", c->desc.n_layers, s->n_layers);
-        LVX_REQUIRE(n_tokens == c->chunk_keys, LVX_ERR_SHAPE, "n_tokens %d must equal the cache's chunk size %d", n_tokens, c->chunk_keys);
+        LVX_REQUIRE(n_tokens == c->chunk_keys || (allow_sink_rows && n_tokens == c->sink_keys), LVX_ERR_SHAPE,
+                    "n_tokens %d must equal the cache's chunk size %d", n_tokens, c->chunk_keys);
     }
     return LVX_OK;
 }
@@ -101,9 +102,14 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
         if (st_ != LVX_OK) return st_;   \
     } while (0)
 
-// x: the fp32 residual stream [n][d]
+// x: the fp32 residual stream [n][d].
+// sink_prefill = false: the chunk's forward (its K-hat / V go to the ring slot of chunk_index, attention over the visible prefix).
+// sink_prefill = true : the sink frame's forward (Appendix D, warm-up of the adaptive attention sink): the n = sink_keys rows
+//   install the layer's un-rotated sink keys and its values, the sink keys are rotated to temporal index t0, and the rows
+//   attend to the sink segment only; the ring is not touched.
 lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
-                       const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st) {
+                       const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st,
+                       bool sink_prefill = false) {
     const lvx_block_weights_t &w = s->blocks[layer];
     const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
     const float eps = s->rope.eps;
@@ -122,9 +128,20 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     // self-attention branch
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
     { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(lvx_linear(u, ldu, w.W_qkv, ldw, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
-    { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, ldq, n, scale, u, ldu, st)); }
+    if (!sink_prefill) {
+        { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
+        { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
+        { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, ldq, n, scale, u, ldu, st)); }
+    } else {
+        lvx_rope_desc_t k_norm_only = s->rope;
+        k_norm_only.apply_rope = 0;
+        LVX_TRY(lvx_rope3d(&s->rope, big, nullptr, ldq, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));                   // q: norm + RoPE
+        if (w.g_k) LVX_TRY(lvx_rope3d(&k_norm_only, nullptr, big + d, ldq, nullptr, w.g_k, n, 0, nullptr, big + d, ldq, st));  // k: norm only
+        LVX_TRY(lvx_kvcache_reset_sink(c, layer, big + d, big + 2 * d, ldq, st));
+        LVX_TRY(lvx_sink_rope_update(c, &s->rope, layer, t0, st));
+        LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->sink_keys, scale, u,
+                                     ldu, st));
+    }
     { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(lvx_linear(u, ldu, w.W_o, ldw, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st)); }
 
     // cross-attention to the audio + text context
@@ -242,4 +259,36 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
     }
     // Euler step of Alg. 3 / Alg. 4:  x <- x + v dt, the stack output standing in for the velocity
     return lvx_launch_euler(x, h, dt, x, n_elems, (hipStream_t)stream);
+}
+
+// Warm-up of a (new) sink frame, Appendix D: after the first block the model's own output replaces the reference image as
+// the sink and "a second warm-up" produces its K/V.  The sink's tokens go through every block attending to themselves.
+extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t *cache, const void *dev_x_sink, const void *dev_ctx,
+                                         int32_t n_ctx, const float *dev_mod6_per_layer, int32_t t_sink, void *dev_x_out,
+                                         void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
+    LVX_REQUIRE(cache != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    const int n = cache->sink_keys;
+    LVX_REQUIRE(n > 0, LVX_ERR_STATE, "this cache has no sink segment (sink_frames = 0)");
+    LVX_TRY(check_stage(stage, cache, n, n_ctx, true));
+    LVX_REQUIRE(cache->sink_src != nullptr, LVX_ERR_STATE, "no sink source storage attached (lvx_kvcache_attach_sink_source)");
+    LVX_REQUIRE(dev_x_sink != nullptr && dev_ctx != nullptr && dev_workspace != nullptr, LVX_ERR_INVALID_ARG, "x_sink, ctx or workspace is NULL");
+    LVX_REQUIRE(lvx_aligned16(dev_x_sink) && lvx_aligned16(dev_ctx) && (((uintptr_t)dev_workspace) & 255u) == 0, LVX_ERR_INVALID_ARG,
+                "x_sink / ctx must be 16-byte and workspace 256-byte aligned");
+    LVX_REQUIRE(t_sink >= 0, LVX_ERR_INVALID_ARG, "t_sink must be non-negative");
+    const size_t need = lvx_workspace_bytes(stage, n, n_ctx);
+    LVX_REQUIRE(ws_bytes >= need, LVX_ERR_SHAPE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    const ws_layout_t L = ws_layout(stage, n, n_ctx);
+    const int d = stage->rope.n_heads * stage->rope.head_dim;
+    float *h = (float *)((char *)dev_workspace + L.h);
+    LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_sink, h, (size_t)n * d, (hipStream_t)stream));
+    for (int l = 0; l < stage->n_layers; ++l) {
+        const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
+        LVX_TRY(run_block(stage, l, cache, h, n, (const bf16_t *)dev_ctx, n_ctx, m6, 0, t_sink, (char *)dev_workspace, L, (hipStream_t)stream,
+                          true));
+    }
+    if (dev_x_out != nullptr) {
+        LVX_REQUIRE(lvx_aligned16(dev_x_out), LVX_ERR_INVALID_ARG, "x_out must be 16-byte aligned");
+        return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_out, (size_t)n * d, (hipStream_t)stream);
+    }
+    return LVX_OK;
 }

@@ -138,6 +138,15 @@ __global__ void __launch_bounds__(256) lvx_widen_kernel(const uint4 *__restrict_
     }
 }
 
+__global__ void __launch_bounds__(256) lvx_copy_rows_kernel(const bf16_t *__restrict__ src, int64_t ld_src, bf16_t *__restrict__ dst,
+                                                            int64_t ld_dst, int n_rows, int chunks_per_row) {
+    const size_t total = (size_t)n_rows * chunks_per_row;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t r = i / chunks_per_row, c = i % chunks_per_row;
+        reinterpret_cast<uint4 *>(dst + r * ld_dst)[c] = reinterpret_cast<const uint4 *>(src + r * ld_src)[c];
+    }
+}
+
 static int grid_for(size_t n_items) {
     size_t g = (n_items + 255) / 256;
     if (g > 256 * 32) g = 256 * 32;
@@ -155,6 +164,15 @@ lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t 
 lvx_status_t lvx_launch_widen(const bf16_t *src, float *dst, size_t n_elems, hipStream_t stream) {
     const size_t n8 = n_elems / 8;
     hipLaunchKernelGGL(lvx_widen_kernel, dim3(grid_for(n8)), dim3(256), 0, stream, (const uint4 *)src, (float4 *)dst, n8);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst, int64_t ld_dst, int n_rows, int row_elems,
+                                  hipStream_t stream) {
+    if (n_rows == 0) return LVX_OK;
+    const size_t total = (size_t)n_rows * (row_elems / 8);
+    hipLaunchKernelGGL(lvx_copy_rows_kernel, dim3(grid_for(total)), dim3(256), 0, stream, src, ld_src, dst, ld_dst, n_rows, row_elems / 8);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
@@ -249,6 +267,14 @@ extern "C" lvx_status_t lvx_kvcache_init(const lvx_cache_desc_t *desc, void *dev
         delete c;
         return lvx_fail(LVX_ERR_INVALID_ARG, "out of host memory");
     }
+    c->sink_src = nullptr;
+    c->sink_t = new (std::nothrow) int32_t[desc->n_layers];
+    if (!c->sink_t) {
+        delete[] c->state;
+        delete c;
+        return lvx_fail(LVX_ERR_INVALID_ARG, "out of host memory");
+    }
+    for (int l = 0; l < desc->n_layers; ++l) c->sink_t[l] = LVX_SINK_STATIC;
     for (int l = 0; l < desc->n_layers; ++l) {
         lvx_ring_state_t &s = c->state[l];
         memset(&s, 0, sizeof(s));
@@ -262,6 +288,7 @@ extern "C" lvx_status_t lvx_kvcache_init(const lvx_cache_desc_t *desc, void *dev
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         delete[] c->state;
+        delete[] c->sink_t;
         delete c;
         return lvx_fail(LVX_ERR_HIP, "zero fill launch: %s", hipGetErrorString(e));
     }
@@ -272,6 +299,7 @@ extern "C" lvx_status_t lvx_kvcache_init(const lvx_cache_desc_t *desc, void *dev
 extern "C" lvx_status_t lvx_kvcache_destroy(lvx_kvcache_t *cache) {
     LVX_REQUIRE(cache != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
     delete[] cache->state;
+    delete[] cache->sink_t;
     delete cache;
     return LVX_OK;
 }
@@ -297,7 +325,85 @@ extern "C" lvx_status_t lvx_kvcache_set_sink(lvx_kvcache_t *c, int32_t layer, co
     lvx_ring_state_t &s = c->state[layer];
     s.sink_set = 1;
     s.key_count = c->sink_keys + s.n_valid_chunks * c->chunk_keys;
+    c->sink_t[layer] = LVX_SINK_STATIC;
     return LVX_OK;
+}
+
+// ---- Rolling RoPE / adaptive attention sink (paper Sec. 3.3, Appendix D) ------------------------------------------
+extern "C" size_t lvx_sink_source_bytes(const lvx_cache_desc_t *desc) {
+    if (check_desc(desc) != LVX_OK) return 0;
+    return (size_t)desc->n_layers * desc->frame_h * desc->frame_w * desc->sink_frames * desc->n_heads * desc->head_dim * sizeof(bf16_t);
+}
+
+extern "C" lvx_status_t lvx_kvcache_attach_sink_source(lvx_kvcache_t *c, void *dev_storage, size_t bytes) {
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    LVX_REQUIRE(c->sink_keys > 0, LVX_ERR_STATE, "this cache has no sink segment (sink_frames = 0)");
+    LVX_REQUIRE(dev_storage != nullptr && (((uintptr_t)dev_storage) & 255u) == 0, LVX_ERR_INVALID_ARG,
+                "sink source storage must be non-NULL and 256-byte aligned");
+    const size_t need = lvx_sink_source_bytes(&c->desc);
+    LVX_REQUIRE(bytes >= need, LVX_ERR_SHAPE, "sink source storage too small: %zu bytes given, %zu needed", bytes, need);
+    c->sink_src = (bf16_t *)dev_storage;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_reset_sink(lvx_kvcache_t *c, int32_t layer, const void *dev_k_src, const void *dev_v, int64_t ld,
+                                               lvx_stream_t stream) {
+    lvx_status_t st = check_layer_and_rows(c, layer, dev_k_src, dev_v, ld);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(c->sink_keys > 0, LVX_ERR_STATE, "this cache has no sink segment (sink_frames = 0)");
+    LVX_REQUIRE(c->sink_src != nullptr, LVX_ERR_STATE, "no sink source storage attached (lvx_kvcache_attach_sink_source)");
+    const int d = c->desc.n_heads * c->desc.head_dim;
+    st = lvx_launch_copy_rows((const bf16_t *)dev_k_src, ld, c->sink_src + (size_t)layer * c->sink_keys * d, d, c->sink_keys, d,
+                              (hipStream_t)stream);
+    if (st != LVX_OK) return st;
+    // V goes to its final place; the K rows receive the un-rotated source and are overwritten by the next rotation
+    st = lvx_launch_pack_kv((const bf16_t *)dev_k_src, (const bf16_t *)dev_v, ld, c->sink_keys, c->desc.n_heads, c->desc.head_dim,
+                            c->cap_keys, 0, (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer), (hipStream_t)stream);
+    if (st != LVX_OK) return st;
+    lvx_ring_state_t &s = c->state[layer];
+    s.sink_set = 1;
+    s.key_count = c->sink_keys + s.n_valid_chunks * c->chunk_keys;
+    c->sink_t[layer] = LVX_SINK_STALE;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_sink_rope_update(lvx_kvcache_t *c, const lvx_rope_desc_t *rope, int32_t layer, int32_t t_sink,
+                                             lvx_stream_t stream) {
+    LVX_REQUIRE(c != nullptr && rope != nullptr, LVX_ERR_INVALID_ARG, "cache handle or rope descriptor is NULL");
+    LVX_REQUIRE(layer >= -1 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [-1,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(t_sink >= 0, LVX_ERR_INVALID_ARG, "t_sink must be non-negative");
+    LVX_REQUIRE(rope->n_heads == c->desc.n_heads && rope->head_dim == c->desc.head_dim && rope->frame_h == c->desc.frame_h &&
+                    rope->frame_w == c->desc.frame_w && rope->apply_rope,
+                LVX_ERR_SHAPE, "rope descriptor disagrees with the cache (heads / head_dim / frame size) or has apply_rope = 0");
+    LVX_REQUIRE(c->sink_src != nullptr, LVX_ERR_STATE, "no sink source storage attached (lvx_kvcache_attach_sink_source)");
+    const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? c->desc.n_layers : layer + 1;
+    for (int l = l0; l < l1; ++l)
+        LVX_REQUIRE(c->sink_t[l] != LVX_SINK_STATIC, LVX_ERR_STATE, "layer %d has no sink source (lvx_kvcache_reset_sink / lvx_sink_prefill)", l);
+    const int d = c->desc.n_heads * c->desc.head_dim;
+    lvx_status_t st = lvx_launch_rope_to_packed_k(rope, c->sink_src + (size_t)l0 * c->sink_keys * d, d, c->sink_keys, t_sink,
+                                                  (bf16_t *)lvx_cache_k(c, l0), c->cap_keys, l1 - l0, (int64_t)c->sink_keys * d,
+                                                  (int64_t)c->layer_k_elems, (hipStream_t)stream);
+    if (st != LVX_OK) return st;
+    for (int l = l0; l < l1; ++l) c->sink_t[l] = t_sink;
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_get_sink_index(const lvx_kvcache_t *c, int32_t layer, int32_t *out) {
+    LVX_REQUIRE(c != nullptr && out != nullptr, LVX_ERR_INVALID_ARG, "cache handle or out is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    *out = c->sink_t[layer];
+    return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *c, int32_t layer, void *dev_k_src_out, int64_t ld,
+                                                       lvx_stream_t stream) {
+    LVX_REQUIRE(c != nullptr && dev_k_src_out != nullptr, LVX_ERR_INVALID_ARG, "cache handle or output is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(c->sink_src != nullptr && c->sink_t[layer] != LVX_SINK_STATIC, LVX_ERR_STATE, "layer %d has no sink source", layer);
+    const int d = c->desc.n_heads * c->desc.head_dim;
+    LVX_REQUIRE(lvx_aligned16(dev_k_src_out) && ld >= d && ld % 8 == 0, LVX_ERR_INVALID_ARG, "output must be 16-byte aligned, ld a multiple of 8 >= d");
+    return lvx_launch_copy_rows(c->sink_src + (size_t)layer * c->sink_keys * d, d, (bf16_t *)dev_k_src_out, ld, c->sink_keys, d,
+                                (hipStream_t)stream);
 }
 
 extern "C" lvx_status_t lvx_chunk_append_evict(lvx_kvcache_t *c, int32_t layer, const void *dev_k, const void *dev_v, int64_t ld,

@@ -53,7 +53,11 @@ struct lvx_kvcache {
     bf16_t *k_base;                                    // [layer][head][cap_keys][D]
     bf16_t *vt_base;                                   // [layer][head][cap_keys/64][D][64]
     lvx_ring_state_t *state;                           // [n_layers]
+    bf16_t *sink_src;                                  // [layer][sink_keys][d] un-rotated sink keys, NULL until attached
+    int32_t *sink_t;                                   // [n_layers] temporal index the sink keys are rotated to; < 0: see LVX_SINK_*
 };
+#define LVX_SINK_STATIC (-2)  /* keys were given already rotated (lvx_kvcache_set_sink) or there is no sink yet */
+#define LVX_SINK_STALE (-1)   /* a source is installed, the cache's sink keys are not yet rotated */
 
 static inline const bf16_t *lvx_cache_k(const lvx_kvcache *c, int layer) { return c->k_base + (size_t)layer * c->layer_k_elems; }
 static inline const bf16_t *lvx_cache_vt(const lvx_kvcache *c, int layer) { return c->vt_base + (size_t)layer * c->layer_k_elems; }
@@ -72,5 +76,13 @@ lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t 
 lvx_status_t lvx_launch_widen(const bf16_t *src, float *dst, size_t n_elems, hipStream_t stream);
 lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,
                                   int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream);
+// Strided row copy [n_rows][row_elems] (row_elems % 8 == 0), bit-exact.
+lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst, int64_t ld_dst, int n_rows, int row_elems,
+                                  hipStream_t stream);
+// RoPE of token-major rows written straight into packed K rows [H][cap][D] starting at key 0 (no norm), for n_layers
+// consecutive layers in one launch (strides in elements between the layers' sources and between their packed K arrays).
+lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
+                                         bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
+                                         hipStream_t stream);
 // Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
 lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);

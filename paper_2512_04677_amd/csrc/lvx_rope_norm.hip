@@ -30,11 +30,15 @@ template <int CPL>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     lvx_rope_norm_kernel(const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in,
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
-                         bf16_t *k_out, int64_t ld_out, int d_model, int head_dim, int frame_h, int frame_w, float eps,
-                         int apply_rope, rope_table_t tab) {
+                         bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
+                         float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out) {
+    // n_batch independent row sets of n_tokens rows each (the sink keys of several layers in one launch); positions and t0
+    // are those of the row inside its set
     const int lane = threadIdx.x & 63;
-    const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
-    if (token >= n_tokens) return;
+    const int64_t row = (int64_t)blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
+    if (row >= (int64_t)n_tokens * n_batch) return;
+    const int batch = (int)(row / n_tokens);
+    const int token = (int)(row % n_tokens);
     const int n_chunks = d_model / 8;
     const int cph = head_dim / 8;  // chunks per head: 8 or 16, divides 64, so (lane + 64 j) % cph == lane % cph
 
@@ -61,7 +65,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
         bf16_t *outp = which == 0 ? q_out : k_out;
         const float *g = which == 0 ? g_q : g_k;
         if (in == nullptr) continue;
-        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(in + (size_t)token * ld_in);
+        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(in + (size_t)batch * batch_stride_in + (size_t)token * ld_in);
         u32x4_t x[CPL];
         float ss = 0.f;
 #pragma unroll
@@ -81,7 +85,9 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
             ss = wave_sum(ss);
             rinv = 1.0f / sqrtf(ss / (float)d_model + eps);
         }
-        u32x4_t *dst = reinterpret_cast<u32x4_t *>(outp + (size_t)token * ld_out);
+        // element (token, head, e) of the output lives at token*ld_out + head*ld_out_head + e: token-major rows have
+        // ld_out_head = head_dim, packed cache K rows [head][key][head_dim] have ld_out = head_dim, ld_out_head = cap*head_dim
+        bf16_t *dst = outp + (size_t)batch * batch_stride_out + (size_t)token * ld_out;
 #pragma unroll
         for (int j = 0; j < CPL; ++j) {
             const int c = lane + 64 * j;
@@ -99,7 +105,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                     const float b = bf16_hi(x[j][e]) * rinv * gg[2 * e + 1];
                     y[e] = pack_bf16x2(a * c4[e] - b * s4[e], a * s4[e] + b * c4[e]);
                 }
-                dst[c] = y;
+                *reinterpret_cast<u32x4_t *>(dst + (size_t)(c / cph) * ld_out_head + (c % cph) * 8) = y;
             }
         }
     }
@@ -195,6 +201,40 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
     return LVX_OK;
 }
 
+static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
+                                const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
+                                hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0) {
+    const int d = desc->n_heads * desc->head_dim;
+    rope_table_t tab;
+    for (int p = 0; p < 64; ++p) {
+        tab.inv_freq[p] = 0.0;
+        tab.axis[p] = 0;
+    }
+    if (desc->apply_rope) {
+        int p = 0;
+        for (int ax = 0; ax < 3; ++ax)
+            for (int k = 0; k < desc->axes[ax] / 2; ++k, ++p) {
+                tab.inv_freq[p] = pow((double)desc->theta, -2.0 * k / (double)desc->axes[ax]);
+                tab.axis[p] = ax;
+            }
+    }
+    const dim3 grid((unsigned)(((int64_t)n_tokens * n_batch + ROWS_PER_WG - 1) / ROWS_PER_WG)), block(64 * ROWS_PER_WG);
+    const int cpl = (d / 8 + 63) / 64;
+#define LVX_ROPE_LAUNCH(CPL)                                                                                                     \
+    hipLaunchKernelGGL(lvx_rope_norm_kernel<CPL>, grid, block, 0, stream, q_in, k_in, ld_in, g_q, g_k, n_tokens, t0, q_out, k_out, \
+                       ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab, n_batch,  \
+                       batch_stride_in, batch_stride_out)
+    if (cpl <= 2)
+        LVX_ROPE_LAUNCH(2);
+    else if (cpl <= 10)
+        LVX_ROPE_LAUNCH(10);
+    else
+        LVX_ROPE_LAUNCH(16);
+#undef LVX_ROPE_LAUNCH
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
 extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
                                    const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
                                    void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
@@ -212,34 +252,18 @@ extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_
     LVX_REQUIRE(n_tokens >= 0 && t0 >= 0, LVX_ERR_INVALID_ARG, "n_tokens and t0 must be non-negative");
     if (n_tokens == 0) return LVX_OK;
 
-    rope_table_t tab;
-    for (int p = 0; p < 64; ++p) {
-        tab.inv_freq[p] = 0.0;
-        tab.axis[p] = 0;
-    }
-    if (desc->apply_rope) {
-        int p = 0;
-        for (int ax = 0; ax < 3; ++ax)
-            for (int k = 0; k < desc->axes[ax] / 2; ++k, ++p) {
-                tab.inv_freq[p] = pow((double)desc->theta, -2.0 * k / (double)desc->axes[ax]);
-                tab.axis[p] = ax;
-            }
-    }
-    const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
-    const int cpl = (d / 8 + 63) / 64;
-#define LVX_ROPE_LAUNCH(CPL)                                                                                                      \
-    hipLaunchKernelGGL(lvx_rope_norm_kernel<CPL>, grid, block, 0, (hipStream_t)stream, (const bf16_t *)dev_q_in,                 \
-                       (const bf16_t *)dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out, (bf16_t *)dev_k_out, \
-                       ld_out, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab)
-    if (cpl <= 2)
-        LVX_ROPE_LAUNCH(2);
-    else if (cpl <= 10)
-        LVX_ROPE_LAUNCH(10);
-    else
-        LVX_ROPE_LAUNCH(16);
-#undef LVX_ROPE_LAUNCH
-    LVX_CHECK_HIP(hipGetLastError());
-    return LVX_OK;
+    return launch_rope(desc, (const bf16_t *)dev_q_in, (const bf16_t *)dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out,
+                       (bf16_t *)dev_k_out, ld_out, desc->head_dim, (hipStream_t)stream);
+}
+
+lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
+                                         bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
+                                         hipStream_t stream) {
+    lvx_status_t st = check_rope_desc(desc);
+    if (st != LVX_OK) return st;
+    if (n_tokens == 0 || n_layers == 0) return LVX_OK;
+    return launch_rope(desc, nullptr, src, ld_src, nullptr, nullptr, n_tokens, t0, nullptr, k_packed, desc->head_dim,
+                       (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst);
 }
 
 lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,

@@ -127,3 +127,23 @@ def test_error_paths_without_a_device():
     assert lib.lvx_workspace_bytes(C.byref(st_bad), 4680, 544) == 0
     assert lib.lvx_dit_block(C.byref(st), 0, None, p, 4680, p, 544, None, 0, 1, p, ws, None) == 1
     assert lib.lvx_denoise_stage(None, None, p, 4680, p, 544, None, -0.25, 0, 1, p, ws, None) == 1
+
+
+def test_sink_management_host_checks():
+    lib = lvx.load()
+    d = desc14b()
+    # un-rotated sink keys of all layers: 40 layers x 1560 tokens x 5120 channels x bf16 = 639 MB
+    assert lvx.load().lvx_sink_source_bytes(C.byref(d)) == 40 * 1560 * 5120 * 2
+    assert lvx.load().lvx_sink_source_bytes(C.byref(desc14b(head_dim=96))) == 0
+    p = C.c_void_p(4096)
+    r = lvx.rope_desc(40, 128, (44, 42, 42), 1e4, 30, 52)
+    out = C.c_int32()
+    assert lib.lvx_kvcache_attach_sink_source(None, p, 1 << 30) == 1
+    assert lib.lvx_kvcache_reset_sink(None, 0, p, p, 5120, None) == 1
+    assert lib.lvx_sink_rope_update(None, C.byref(r), 0, 1, None) == 1
+    assert lib.lvx_kvcache_get_sink_index(None, 0, C.byref(out)) == 1
+    assert lib.lvx_kvcache_gather_sink_source(None, 0, p, 5120, None) == 1
+    blocks = (lvx.BlockWeights * 1)()
+    st = lvx.Stage(1, 13824, 0, 0, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
+    assert lib.lvx_sink_prefill(C.byref(st), None, p, p, 544, None, 1, None, p, 1 << 30, None) == 1
+    assert b"NULL" in lib.lvx_last_error()

@@ -1,0 +1,155 @@
+"""GPU parity of Rolling RoPE and the adaptive-attention-sink calls (Appendix D; Phi(sink) and the sink assignment of
+Alg. 3 / Alg. 4) against the fp64 oracle, through the C ABI.  Copies (source, values) are compared bit for bit; rotated
+keys and activations to the tolerances of test_gpu_parity."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import lvx_synth as S
+from oracle import lvx_oracle as O
+from test_gpu_parity import CHAIN, DEV, assert_close, dims, make_cache
+
+pytestmark = pytest.mark.gpu
+
+
+def gather_sink(lvx, cache, layer, sink_n, d):
+    gk = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+    gv = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+    lvx.lvx_kvcache_gather(cache, layer, 0, sink_n, gk, gv)
+    torch.cuda.synchronize()
+    return gk, gv
+
+
+@pytest.mark.parametrize("preset", ["tiny", "small"])
+def test_reset_sink_and_rolling_update(lvx, preset):
+    p = S.PRESETS[preset]
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], W, p["sink_frames"], p["rope_axes"])
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    cache = make_cache(lvx, p, 2)
+    # without attached storage every call of the family refuses
+    k_src = S.randn_bf16((sink_n, d + 8), S.seed_of(preset, "sink_src"), device=DEV)[:, :d]   # strided rows
+    v = S.randn_bf16((sink_n, d + 8), S.seed_of(preset, "sink_val"), device=DEV)[:, :d]
+    with pytest.raises(lvx.LvxError) as e:
+        lvx.lvx_kvcache_reset_sink(cache, 1, k_src, v)
+    assert e.value.status == 3
+    cache.attach_sink_source()
+    assert lvx.lvx_kvcache_get_sink_index(cache, 1) == -2
+    # a ring with history next to the sink: the sink calls must leave it alone (the last sink tile is shared with slot 0)
+    ck = S.randn_bf16((chunk_n, d), S.seed_of(preset, "ring_k"), device=DEV)
+    cv = S.randn_bf16((chunk_n, d), S.seed_of(preset, "ring_v"), device=DEV)
+    lvx.lvx_kvcache_set_sink(cache, 1, k_src.contiguous(), v.contiguous())
+    with pytest.raises(lvx.LvxError):                      # a static sink has no source to rotate
+        lvx.lvx_sink_rope_update(cache, rope, 1, 3)
+    lvx.lvx_chunk_append_evict(cache, 1, ck, cv, 0)
+    lvx.lvx_kvcache_reset_sink(cache, 1, k_src, v)
+    assert lvx.lvx_kvcache_get_sink_index(cache, 1) == -1
+    q = S.randn_bf16((chunk_n, d), S.seed_of(preset, "sink_q"), device=DEV)
+    out = torch.empty_like(q)
+    with pytest.raises(lvx.LvxError) as e:                 # stale sink keys are not attended to
+        lvx.lvx_chunk_attention(cache, 1, q, 1 / math.sqrt(D), out)
+    assert e.value.status == 3
+    back = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+    lvx.lvx_kvcache_gather_sink_source(cache, 1, back)
+    torch.cuda.synchronize()
+    assert torch.equal(back.view(torch.int16), k_src.contiguous().view(torch.int16))
+
+    model = O.RollingKVCache(W)
+    model.set_sink_source(S.to_f64(k_src).reshape(sink_n, H, D), S.to_f64(v).reshape(sink_n, H, D))
+    model.append(0, S.to_f64(ck).reshape(chunk_n, H, D), S.to_f64(cv).reshape(chunk_n, H, D))
+    first = None
+    for t_sink in (0, 5, 40003, 5):
+        lvx.lvx_sink_rope_update(cache, rope, 1, t_sink)
+        assert lvx.lvx_kvcache_get_sink_index(cache, 1) == t_sink
+        model.roll_sink(t_sink, cfg)
+        gk, gv = gather_sink(lvx, cache, 1, sink_n, d)
+        assert torch.equal(gv.view(torch.int16), v.contiguous().view(torch.int16))             # values: bit-exact, untouched
+        assert_close(gk, model.sink[0].reshape(sink_n, d), "%s sink keys at t=%d" % (preset, t_sink))
+        if t_sink == 5:
+            if first is None:
+                first = gk.clone()
+            else:                                                                             # recomputed from the source
+                assert torch.equal(gk.view(torch.int16), first.view(torch.int16))
+        # ring rows next to the sink are intact and attention over {sink, chunk 0} matches the oracle
+        rk = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+        rv = torch.empty_like(rk)
+        lvx.lvx_kvcache_gather(cache, 1, sink_n, chunk_n, rk, rv)
+        torch.cuda.synchronize()
+        assert torch.equal(rk.view(torch.int16), ck.view(torch.int16)) and torch.equal(rv.view(torch.int16), cv.view(torch.int16))
+        lvx.lvx_chunk_attention(cache, 1, q, 1 / math.sqrt(D), out)
+        torch.cuda.synchronize()
+        kk = np.concatenate([model.sink[0], model.blocks[0][1]], 0)
+        vv = np.concatenate([model.sink[1], model.blocks[0][2]], 0)
+        ref = O.attention(S.to_f64(q).reshape(chunk_n, H, D), kk, vv, 1 / math.sqrt(D)).reshape(chunk_n, d)
+        assert_close(out, ref, "%s attention with rolled sink t=%d" % (preset, t_sink))
+    # layer 0 was never given a sink source
+    with pytest.raises(lvx.LvxError):
+        lvx.lvx_sink_rope_update(cache, rope, -1, 1)
+    cache.close()
+
+
+def test_stage_with_sink_prefill_swap_and_rolling_index(lvx):
+    """Alg. 3 on the stage level with both mechanisms, 2 layers of the `small` preset: warm-up of the reference sink,
+    block 0, sink swap (the first generated frame, second warm-up), blocks 1..5 with the sink index re-assigned before
+    every forward (t_sink = last frame index of the block + 2)."""
+    preset = "small"
+    p = S.PRESETS[preset]
+    d, sink_n, n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    L = 2
+    layers = [S.block_weights(d, p["ffn"], l, "sinkstage", std=1.0 / math.sqrt(d), device=DEV) for l in range(L)]
+    for l, w in enumerate(layers):                       # non-trivial gains so that the stored source is really normalised
+        w["g_k"] = (1.0 + S.randn_f32((d,), S.seed_of("sinkstage_gk", l), 0.1)).to(DEV)
+    w64 = [S.weights_to_f64(w) for w in layers]
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    cache = make_cache(lvx, p, L)
+    cache.attach_sink_source()
+    cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], W, p["sink_frames"], p["rope_axes"])
+    models = [O.RollingKVCache(W) for _ in range(L)]
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, p["n_ctx"]), dtype=torch.uint8, device=DEV)
+    mod6 = S.randn_f32((L, 6, d), 99, 0.2, device=DEV)
+    mod6[:, 2] += 1.0
+    mod6[:, 5] += 1.0
+    t0 = lambda i: 1 + p["chunk_frames"] * i
+    t_sink = lambda i: t0(i) + p["chunk_frames"] - 1 + 2
+
+    def prefill(x_sink, ctx, t):
+        x_out = torch.empty_like(x_sink)
+        lvx.lvx_sink_prefill(stage, cache, x_sink, ctx, mod6, t, ws, x_out)
+        torch.cuda.synchronize()
+        ref = O.sink_prefill(S.to_f64(x_sink), w64, models, S.to_f64(ctx), S.to_f64(mod6), t, cfg)
+        assert_close(x_out, ref, "prefill output", relative_to_rms=True, chain=CHAIN)
+        for l in range(L):
+            assert lvx.lvx_kvcache_get_sink_index(cache, l) == t
+            src = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+            lvx.lvx_kvcache_gather_sink_source(cache, l, src)
+            gk, gv = gather_sink(lvx, cache, l, sink_n, d)
+            assert_close(src, models[l].sink_source.reshape(sink_n, d), "prefill layer %d sink source" % l, chain=CHAIN)
+            assert_close(gk, models[l].sink[0].reshape(sink_n, d), "prefill layer %d sink keys" % l, chain=CHAIN)
+            assert_close(gv, models[l].sink[1].reshape(sink_n, d), "prefill layer %d sink values" % l, chain=CHAIN)
+
+    ref_img = S.randn_bf16((sink_n, d), S.seed_of("sinkstage_ref"), device=DEV)
+    ctx0 = S.randn_bf16((p["n_ctx"], d), S.seed_of("sinkstage_ctx", "p"), device=DEV)
+    prefill(ref_img, ctx0, t_sink(0))
+    for i in range(6):
+        x = S.randn_bf16((n, d), S.seed_of("sinkstage_x", i), device=DEV)
+        ctx = S.randn_bf16((p["n_ctx"], d), S.seed_of("sinkstage_ctx", i), device=DEV)
+        lvx.lvx_sink_rope_update(cache, rope, -1, t_sink(i))
+        for m in models:
+            m.roll_sink(t_sink(i), cfg)
+        ref = O.denoise_stage(S.to_f64(x), w64, models, S.to_f64(ctx), S.to_f64(mod6), -0.25, i, t0(i), cfg)
+        lvx.lvx_denoise_stage(stage, cache, x, ctx, mod6, -0.25, i, t0(i), ws)
+        torch.cuda.synchronize()
+        assert_close(x, ref, "stage chunk %d with rolling sink" % i, relative_to_rms=True, chain=CHAIN)
+        if i == 0:
+            # sink swap: both sides continue from the GPU's own first generated frame (teacher forcing of the new sink's
+            # input, so that the check of the second warm-up does not inherit block 0's rounding)
+            new_sink = x[:sink_n].clone()
+            prefill(new_sink, ctx, t_sink(1))
+            for l in range(L):
+                assert lvx.lvx_kvcache_get_state(cache, l).last_chunk == 0      # ring untouched by the swap
+    cache.close()
