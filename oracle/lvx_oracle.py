@@ -379,6 +379,21 @@ def denoise_stage(x, layers, caches, ctx, mod6_per_layer, dt, chunk_index, t0, c
     return x_in + h * dt
 
 
+def sample_chunk(x, layers, caches_per_step, ctx, mod6_per_step, dt, chunk_index, t0, cfg, t_sink=None):
+    """Alg. 3, the inner loop over the T denoising steps of ONE block on one device: step s (the s-th to run, i.e. the
+    paper's j = T - s) is a full stage forward with that step's own rolling caches ``caches_per_step[s]`` (one per
+    layer) and that step's modulation, followed by the Euler update and that cache's pop/append.  All steps share the
+    weights.  With ``t_sink`` given, every step first re-assigns its caches' sink index (Phi(sink))."""
+    x = np.asarray(x, F64)
+    for s, caches in enumerate(caches_per_step):
+        if t_sink is not None:
+            for c in caches:
+                c.roll_sink(t_sink, cfg)
+        m6 = None if mod6_per_step is None else mod6_per_step[s]
+        x = denoise_stage(x, layers, caches, ctx, m6, dt, chunk_index, t0, cfg)
+    return x
+
+
 def full_sequence_stage(x_chunks, layers, sink_kv_per_layer, ctx_per_chunk, mod6_per_layer, dt, t0_of_chunk, cfg):
     """The same stack evaluated on ALL chunks at once with an explicit block-causal windowed mask.
 

@@ -467,3 +467,39 @@ def test_streaming_with_sink_swap_and_rolling_index_runs_the_documented_sequence
             O.sink_prefill(y[:cfg.frame_tokens], layers, caches, ctx, None, t_sink(1), cfg)
             assert not np.array_equal(caches[0].sink_source, src_ref)
             assert caches[0].chunk_ids() == [0]
+
+
+def test_sample_chunk_is_T_stages_with_independent_per_step_caches():
+    """Alg. 3 inner loop: T forwards of the same weights, each with its own cache and its own modulation; T = 1 is one
+    stage; the cache of step s holds only K/V produced at step s (timestep forcing: a block and the cache it attends to
+    share the noise level), so perturbing the history of step 1 cannot change what step 0 computes."""
+    cfg = tiny_cfg()
+    d, H, D = cfg.d_model, cfg.n_heads, cfg.head_dim
+    layers = [tiny_weights(cfg)]
+    ctx = rng.standard_normal((5, d))
+    T = 3
+    mod6 = [[rng.standard_normal((6, d)) * 0.3 + np.array([0, 0, 1, 0, 0, 1])[:, None]] for _ in range(T)]
+    mk = lambda: [[fresh_cache(cfg, 40 + s)] for s in range(T)]
+    caches, twin = mk(), mk()
+    x0 = rng.standard_normal((cfg.chunk_tokens, d))
+    outs = []
+    for i in range(3):
+        x = rng.standard_normal((cfg.chunk_tokens, d))
+        want = x
+        for s in range(T):
+            want = O.denoise_stage(want, layers, twin[s], ctx, mod6[s], -1.0 / T, i, 1 + 2 * i, cfg)
+        got = O.sample_chunk(x, layers, caches, ctx, mod6, -1.0 / T, i, 1 + 2 * i, cfg)
+        np.testing.assert_array_equal(got, want)
+        for s in range(T):
+            assert caches[s][0].chunk_ids() == list(range(max(0, i + 1 - cfg.window), i + 1))
+    one = O.sample_chunk(x0, layers, [[fresh_cache(cfg, 40)]], ctx, [mod6[0]], -0.5, 0, 1, cfg)
+    np.testing.assert_array_equal(one, O.denoise_stage(x0, layers, [fresh_cache(cfg, 40)], ctx, mod6[0], -0.5, 0, 1, cfg))
+    # independence of the per-step caches
+    a, b = mk(), mk()
+    b[1][0].append(0, rng.standard_normal((cfg.chunk_tokens, H, D)), rng.standard_normal((cfg.chunk_tokens, H, D)))
+    a[1][0].append(0, rng.standard_normal((cfg.chunk_tokens, H, D)), rng.standard_normal((cfg.chunk_tokens, H, D)))
+    xa = O.denoise_stage(x0, layers, a[0], ctx, mod6[0], -1.0 / T, 0, 1, cfg)
+    xb = O.denoise_stage(x0, layers, b[0], ctx, mod6[0], -1.0 / T, 0, 1, cfg)
+    np.testing.assert_array_equal(xa, xb)
+    assert np.abs(O.denoise_stage(xa, layers, a[1], ctx, mod6[1], -1.0 / T, 1, 1, cfg)
+                  - O.denoise_stage(xb, layers, b[1], ctx, mod6[1], -1.0 / T, 1, 1, cfg)).max() > 1e-6
