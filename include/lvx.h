@@ -257,6 +257,18 @@ lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage /* host */, lvx_kvcache_
                                const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 
+/* Alg. 3, the loop over the T denoising steps of ONE block on one device: for s = 0 .. n_steps-1 (in execution order, i.e. the
+ * paper's j = T .. 1) the whole stage runs with caches[s], the rolling cache of that timestep (a block attends only to history
+ * of its own noise level, Sec. 3.3 "timestep-forcing"), and with that step's modulation; then x <- x + dt * stack(x) and the
+ * cache's pop/append.  caches: host array of n_steps distinct handles; mod6_per_step_layer: fp32 [n_steps][n_layers][6][d] or
+ * NULL.  t_sink >= 0: every step first re-assigns the sink index of its cache (lvx_sink_rope_update on all layers); t_sink < 0:
+ * sinks are left as they are.  All steps are validated before anything is enqueued (STATE if any layer of any cache does not
+ * expect chunk_index, or lacks a sink source when t_sink >= 0). */
+lvx_status_t lvx_sample_chunk(const lvx_stage_t *stage /* host */, lvx_kvcache_t *const *caches /* host */, int32_t n_steps,
+                              void *dev_x_inout, int32_t n_tokens, const void *dev_ctx, int32_t n_ctx,
+                              const float *dev_mod6_per_step_layer, float dt, int64_t chunk_index, int32_t t0, int32_t t_sink,
+                              void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
 /* Warm-up of a sink frame (Appendix D: the sink swap of the adaptive attention sink needs a second warm-up to produce the
  * new sink's K/V): the sink frame's tokens x_sink [sink_keys][d] bf16 run through all blocks; per layer the un-rotated,
  * normalised keys and the values of these tokens are installed as the sink (as lvx_kvcache_reset_sink does) and rotated to

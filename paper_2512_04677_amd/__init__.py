@@ -82,6 +82,8 @@ SIGNATURES = {
     "lvx_kvcache_get_sink_index": (C.c_int, [_vp, _i32, C.POINTER(C.c_int32)]),
     "lvx_kvcache_gather_sink_source": (C.c_int, [_vp, _i32, _vp, _i64, _vp]),
     "lvx_sink_prefill": (C.c_int, [C.POINTER(Stage), _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
+    "lvx_sample_chunk": (C.c_int, [C.POINTER(Stage), C.POINTER(_vp), _i32, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _i32, _vp, _sz,
+                                   _vp]),
     "lvx_profile_set": (C.c_int, [_i32]),
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
@@ -281,6 +283,13 @@ def lvx_denoise_stage(stage, cache, x, ctx, mod6_per_layer, dt, chunk_index, t0,
 def lvx_sink_prefill(stage, cache, x_sink, ctx, mod6_per_layer, t_sink, workspace, x_out=None):
     _check(load().lvx_sink_prefill(C.byref(stage.c), cache.handle, _ptr(x_sink), _ptr(ctx), ctx.shape[0], _ptr(mod6_per_layer), t_sink,
                                    _ptr(x_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def lvx_sample_chunk(stage, caches, x, ctx, mod6_per_step_layer, dt, chunk_index, t0, t_sink, workspace):
+    handles = (C.c_void_p * len(caches))(*[c.handle for c in caches])
+    _check(load().lvx_sample_chunk(C.byref(stage.c), handles, len(caches), _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0],
+                                   _ptr(mod6_per_step_layer), dt, chunk_index, t0, t_sink, _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream()))
 
 
 def lvx_profile_set(level):

@@ -292,3 +292,36 @@ extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t
     }
     return LVX_OK;
 }
+
+// Alg. 3, inner loop over the denoising steps of one block on one device: step s runs the whole stage with the s-th
+// timestep's own rolling cache (timestep forcing, Sec. 3.3: a block and the cache it attends to share the noise level) and the
+// s-th modulation, then the Euler update; the weights are shared.
+extern "C" lvx_status_t lvx_sample_chunk(const lvx_stage_t *stage, lvx_kvcache_t *const *caches, int32_t n_steps, void *dev_x_inout,
+                                         int32_t n_tokens, const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_step_layer,
+                                         float dt, int64_t chunk_index, int32_t t0, int32_t t_sink, void *dev_workspace,
+                                         size_t ws_bytes, lvx_stream_t stream) {
+    LVX_REQUIRE(caches != nullptr && n_steps > 0, LVX_ERR_INVALID_ARG, "caches is NULL or n_steps %d is not positive", n_steps);
+    LVX_REQUIRE(stage != nullptr, LVX_ERR_INVALID_ARG, "stage descriptor is NULL");
+    // validate every step before enqueueing anything, so a refused call leaves all caches as they were
+    for (int s = 0; s < n_steps; ++s) {
+        LVX_TRY(check_common(stage, caches[s], dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
+        for (int q = 0; q < s; ++q) LVX_REQUIRE(caches[q] != caches[s], LVX_ERR_INVALID_ARG, "steps %d and %d share a cache", q, s);
+        for (int l = 0; l < stage->n_layers; ++l) {
+            LVX_REQUIRE(caches[s]->state[l].last_chunk + 1 == chunk_index, LVX_ERR_STATE, "step %d layer %d expects chunk %lld, got %lld", s, l,
+                        (long long)(caches[s]->state[l].last_chunk + 1), (long long)chunk_index);
+            if (t_sink >= 0)
+                LVX_REQUIRE(caches[s]->sink_src != nullptr && caches[s]->sink_t[l] != LVX_SINK_STATIC, LVX_ERR_STATE,
+                            "step %d layer %d has no sink source to re-index", s, l);
+            else
+                LVX_REQUIRE(caches[s]->sink_t[l] != LVX_SINK_STALE, LVX_ERR_STATE, "step %d layer %d: sink keys not rotated", s, l);
+        }
+    }
+    const size_t per_step = (size_t)stage->n_layers * 6 * stage->rope.n_heads * stage->rope.head_dim;
+    for (int s = 0; s < n_steps; ++s) {
+        if (t_sink >= 0) LVX_TRY(lvx_sink_rope_update(caches[s], &stage->rope, -1, t_sink, stream));
+        const float *m6 = dev_mod6_per_step_layer ? dev_mod6_per_step_layer + (size_t)s * per_step : nullptr;
+        LVX_TRY(lvx_denoise_stage(stage, caches[s], dev_x_inout, n_tokens, dev_ctx, n_ctx, m6, dt, chunk_index, t0, dev_workspace, ws_bytes,
+                                  stream));
+    }
+    return LVX_OK;
+}

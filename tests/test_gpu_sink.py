@@ -153,3 +153,51 @@ def test_stage_with_sink_prefill_swap_and_rolling_index(lvx):
             for l in range(L):
                 assert lvx.lvx_kvcache_get_state(cache, l).last_chunk == 0      # ring untouched by the swap
     cache.close()
+
+
+def test_sample_chunk_T_steps_with_per_timestep_caches(lvx):
+    """Alg. 3 inner loop on the GPU: T = 3 denoising steps per block, each with its own rolling cache and modulation, sinks
+    warmed up per timestep and re-indexed before every forward; 4 blocks (warm-up and steady state of the `tiny` ring)."""
+    preset = "tiny"
+    p = S.PRESETS[preset]
+    d, sink_n, n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    L, T = 2, 3
+    layers = [S.block_weights(d, p["ffn"], l, "sampler", std=1.0 / math.sqrt(d), device=DEV) for l in range(L)]
+    w64 = [S.weights_to_f64(w) for w in layers]
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], W, p["sink_frames"], p["rope_axes"])
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, p["n_ctx"]), dtype=torch.uint8, device=DEV)
+    mod6 = S.randn_f32((T, L, 6, d), 123, 0.2, device=DEV)
+    mod6[:, :, 2] += 1.0
+    mod6[:, :, 5] += 1.0
+    caches = [make_cache(lvx, p, L) for _ in range(T)]
+    models = [[O.RollingKVCache(W) for _ in range(L)] for _ in range(T)]
+    ref_img = S.randn_bf16((sink_n, d), S.seed_of("sampler_ref"), device=DEV)
+    ctx0 = S.randn_bf16((p["n_ctx"], d), S.seed_of("sampler_ctx", "p"), device=DEV)
+    x = S.randn_bf16((n, d), S.seed_of("sampler_x", 0), device=DEV)
+    with pytest.raises(lvx.LvxError) as e:          # no sink source yet: refused before anything is enqueued
+        lvx.lvx_sample_chunk(stage, caches, x, ctx0, mod6, -1.0 / T, 0, 1, 4, ws)
+    assert e.value.status == 3 and all(lvx.lvx_kvcache_get_state(c, 0).last_chunk == -1 for c in caches)
+    for s in range(T):
+        caches[s].attach_sink_source()
+        lvx.lvx_sink_prefill(stage, caches[s], ref_img, ctx0, mod6[s], 4, ws)
+        O.sink_prefill(S.to_f64(ref_img), w64, models[s], S.to_f64(ctx0), S.to_f64(mod6[s]), 4, cfg)
+    with pytest.raises(lvx.LvxError):               # the same cache for two timesteps
+        lvx.lvx_sample_chunk(stage, [caches[0], caches[1], caches[0]], x, ctx0, mod6, -1.0 / T, 0, 1, 4, ws)
+    for i in range(4):
+        x = S.randn_bf16((n, d), S.seed_of("sampler_x", i), device=DEV)
+        ctx = S.randn_bf16((p["n_ctx"], d), S.seed_of("sampler_ctx", i), device=DEV)
+        t0 = 1 + p["chunk_frames"] * i
+        t_sink = t0 + p["chunk_frames"] + 1
+        ref = O.sample_chunk(S.to_f64(x), w64, models, S.to_f64(ctx), S.to_f64(mod6), -1.0 / T, i, t0, cfg, t_sink=t_sink)
+        lvx.lvx_sample_chunk(stage, caches, x, ctx, mod6, -1.0 / T, i, t0, t_sink, ws)
+        torch.cuda.synchronize()
+        assert_close(x, ref, "sampler block %d after %d steps" % (i, T), relative_to_rms=True, chain=CHAIN)
+        for s in range(T):
+            for l in range(L):
+                assert lvx.lvx_kvcache_get_state(caches[s], l).last_chunk == i
+                assert lvx.lvx_kvcache_get_sink_index(caches[s], l) == t_sink
+    for c in caches:
+        c.close()
