@@ -105,6 +105,49 @@ def linear(x, W):
     return np.asarray(x, F64) @ np.asarray(W, F64).T
 
 
+# --------------------------------------------------------------------------------------------------
+# FP8 (E4M3) linears with per-tensor dynamic scaling (Appendix C, "FP8 Quantization")
+# --------------------------------------------------------------------------------------------------
+E4M3_MAX = 448.0          # largest finite value of the 8-bit format: 1.75 * 2^8 (no infinities, one NaN pattern per sign)
+
+
+def e4m3_round(y):
+    """Round to the nearest value of the E4M3 grid (ties to even), saturating at +-448.
+
+    Grid: sign, 4 exponent bits (bias 7), 3 mantissa bits; normals 2^e * (1 + m/8) for e = -6 .. 8, subnormals
+    m * 2^-9.  The spacing around |y| in [2^e, 2^(e+1)) is 2^(e-3), floored at 2^-9."""
+    y = np.asarray(y, F64)
+    a = np.abs(y)
+    e = np.floor(np.log2(np.where(a > 0, a, 1.0)))
+    e = np.clip(e, -6, 8)
+    q = np.exp2(e - 3)
+    r = np.rint(a / q) * q                      # rint = ties to even; a/q is exact (power-of-two divisor)
+    return np.sign(y) * np.minimum(r, E4M3_MAX)
+
+
+def fp8_quantize_per_tensor(x):
+    """Per-tensor dynamic scaling: amax = max|x| over the whole tensor, grid value = e4m3_round(x * (448 / amax)),
+    represented value = grid value * (amax / 448).  The two scale factors and the product x * (448/amax) are formed in
+    fp32 -- the precision in which the kernel decides the 8-bit code -- so that both sides round the same number.
+    Returns (grid values as float64, scale as float64); an all-zero tensor gets scale 1."""
+    x32 = np.asarray(x, np.float32)
+    amax = np.float32(np.abs(x32).max()) if x32.size else np.float32(0)
+    if amax == 0:
+        return np.zeros(x32.shape, F64), 1.0
+    inv = np.float32(E4M3_MAX) / amax
+    scale = amax / np.float32(E4M3_MAX)
+    y = x32 * inv                                # fp32 product
+    return e4m3_round(y.astype(F64)), float(scale)
+
+
+def linear_fp8(x, W):
+    """y = dequant(quant(x)) @ dequant(quant(W))^T: both operands on the E4M3 grid with their own per-tensor scale,
+    the contraction itself exact (fp64)."""
+    xq, sx = fp8_quantize_per_tensor(x)
+    wq, sw = fp8_quantize_per_tensor(W)
+    return (xq @ wq.T) * (sx * sw)
+
+
 def token_positions(n_tokens, t0, frame_h, frame_w):
     """(t, y, x) of token n laid out frame-major, then row, then column; t = t0 + frame."""
     n = np.arange(n_tokens)
@@ -220,11 +263,15 @@ class StageConfig:
     """Shapes of the stack.  Defaults are the 14B-scale workload; tests shrink them."""
 
     def __init__(self, n_heads=40, head_dim=128, frame_h=30, frame_w=52, chunk_frames=3, window=4,
-                 sink_frames=1, rope_axes=(44, 42, 42), theta=10000.0, eps=1e-6):
+                 sink_frames=1, rope_axes=(44, 42, 42), theta=10000.0, eps=1e-6, fp8_linears=False):
         self.n_heads, self.head_dim = n_heads, head_dim
         self.frame_h, self.frame_w = frame_h, frame_w
         self.chunk_frames, self.window, self.sink_frames = chunk_frames, window, sink_frames
         self.rope_axes, self.theta, self.eps = tuple(rope_axes), theta, eps
+        # Appendix C: every linear projection of the block takes both operands on the E4M3 grid with per-tensor
+        # dynamic scales (each weight matrix as stored -- the fused QKV matrix is one tensor -- and each activation
+        # tensor as a whole).  Attention, norms, RoPE, GELU and the residual adds are not quantised.
+        self.fp8_linears = bool(fp8_linears)
 
     @property
     def d_model(self):
@@ -237,6 +284,10 @@ class StageConfig:
     @property
     def chunk_tokens(self):
         return self.chunk_frames * self.frame_tokens
+
+
+def _lin(cfg):
+    return linear_fp8 if cfg is not None and cfg.fp8_linears else linear
 
 
 def _mod6(mod6, d):
@@ -252,7 +303,7 @@ def qkv_for_cache(u, w, cfg, t0, positions=None):
     """QKV projection, Q/K RMSNorm over all channels, 3-D RoPE on Q and K; V untouched."""
     H, D = cfg.n_heads, cfg.head_dim
     d = H * D
-    qkv = linear(u, w["W_qkv"])
+    qkv = _lin(cfg)(u, w["W_qkv"])
     q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
     if w.get("g_q") is not None:
         q = rmsnorm(q, w["g_q"], cfg.eps)
@@ -268,20 +319,20 @@ def cross_attention(x, ctx, w, cfg):
     """Attention from LayerNorm(x) to the audio+text context; Q/K RMSNorm if gains given; no RoPE."""
     H, D = cfg.n_heads, cfg.head_dim
     n = x.shape[0]
-    q = linear(layernorm(x, cfg.eps), w["Wc_q"])
-    k = linear(ctx, w["Wc_k"])
-    v = linear(ctx, w["Wc_v"])
+    q = _lin(cfg)(layernorm(x, cfg.eps), w["Wc_q"])
+    k = _lin(cfg)(ctx, w["Wc_k"])
+    v = _lin(cfg)(ctx, w["Wc_v"])
     if w.get("gc_q") is not None:
         q = rmsnorm(q, w["gc_q"], cfg.eps)
     if w.get("gc_k") is not None:
         k = rmsnorm(k, w["gc_k"], cfg.eps)
     m = ctx.shape[0]
     o = attention(q.reshape(n, H, D), k.reshape(m, H, D), v.reshape(m, H, D), 1.0 / np.sqrt(D))
-    return linear(o.reshape(n, H * D), w["Wc_o"])
+    return _lin(cfg)(o.reshape(n, H * D), w["Wc_o"])
 
 
-def ffn(u, w):
-    return linear(gelu_tanh(linear(u, w["W_1"])), w["W_2"])
+def ffn(u, w, cfg=None):
+    return _lin(cfg)(gelu_tanh(_lin(cfg)(u, w["W_1"])), w["W_2"])
 
 
 def dit_block(x, w, cache, ctx, mod6, chunk_index, t0, cfg):
@@ -299,10 +350,10 @@ def dit_block(x, w, cache, ctx, mod6, chunk_index, t0, cfg):
     u = modulate(x, sh1, sc1, cfg.eps)
     q, k, v = qkv_for_cache(u, w, cfg, t0)
     o = chunk_attention_step(cache, q, k, v, 1.0 / np.sqrt(D), chunk_index)
-    x = x + g1 * linear(o.reshape(-1, d), w["W_o"])
+    x = x + g1 * _lin(cfg)(o.reshape(-1, d), w["W_o"])
     x = x + cross_attention(x, np.asarray(ctx, F64), w, cfg)
     u2 = modulate(x, sh2, sc2, cfg.eps)
-    x = x + g2 * ffn(u2, w)
+    x = x + g2 * ffn(u2, w, cfg)
     return x
 
 
@@ -320,10 +371,10 @@ def dit_block_rows(x_rows, positions, w, k_visible, v_visible, ctx, mod6, cfg):
     u = modulate(x, sh1, sc1, cfg.eps)
     q, k, v = qkv_for_cache(u, w, cfg, 0, positions)
     o = attention(q, k_visible, v_visible, 1.0 / np.sqrt(D))
-    x = x + g1 * linear(o.reshape(-1, d), w["W_o"])
+    x = x + g1 * _lin(cfg)(o.reshape(-1, d), w["W_o"])
     x = x + cross_attention(x, np.asarray(ctx, F64), w, cfg)
     u2 = modulate(x, sh2, sc2, cfg.eps)
-    x = x + g2 * ffn(u2, w)
+    x = x + g2 * ffn(u2, w, cfg)
     return x, k, v
 
 
@@ -331,7 +382,7 @@ def sink_keys_values(u, w, cfg):
     """Un-rotated sink keys and sink values of one layer: K projection + RMSNorm (no RoPE), V projection."""
     H, D = cfg.n_heads, cfg.head_dim
     d = H * D
-    qkv = linear(u, w["W_qkv"])
+    qkv = _lin(cfg)(u, w["W_qkv"])
     k, v = qkv[:, d:2 * d], qkv[:, 2 * d:]
     if w.get("g_k") is not None:
         k = rmsnorm(k, w["g_k"], cfg.eps)
@@ -354,15 +405,15 @@ def sink_prefill(x_sink, layers, caches, ctx, mod6_per_layer, t_sink, cfg):
         k_src, v = sink_keys_values(u, w, cfg)
         caches[l].set_sink_source(k_src, v)
         caches[l].roll_sink(t_sink, cfg)
-        q = linear(u, w["W_qkv"])[:, :d]
+        q = _lin(cfg)(u, w["W_qkv"])[:, :d]
         if w.get("g_q") is not None:
             q = rmsnorm(q, w["g_q"], cfg.eps)
         q = rope3d(q.reshape(-1, H, D), t_sink, cfg.frame_h, cfg.frame_w, cfg.rope_axes, cfg.theta)
         o = attention(q, caches[l].sink[0], caches[l].sink[1], 1.0 / np.sqrt(D))
-        x = x + g1 * linear(o.reshape(-1, d), w["W_o"])
+        x = x + g1 * _lin(cfg)(o.reshape(-1, d), w["W_o"])
         x = x + cross_attention(x, np.asarray(ctx, F64), w, cfg)
         u2 = modulate(x, sh2, sc2, cfg.eps)
-        x = x + g2 * ffn(u2, w)
+        x = x + g2 * ffn(u2, w, cfg)
     return x
 
 
@@ -418,11 +469,11 @@ def full_sequence_stage(x_chunks, layers, sink_kv_per_layer, ctx_per_chunk, mod6
         mask = block_causal_mask(n_chunks, nc, ks.shape[0], cfg.window)
         o = attention(q, np.concatenate([np.asarray(ks, F64), k]), np.concatenate([np.asarray(vs, F64), v]),
                       1.0 / np.sqrt(D), mask=mask)
-        h = h + g1 * linear(o.reshape(-1, d), w["W_o"])
+        h = h + g1 * _lin(cfg)(o.reshape(-1, d), w["W_o"])
         ca = [cross_attention(h[i * nc:(i + 1) * nc], np.asarray(ctx_per_chunk[i], F64), w, cfg)
               for i in range(n_chunks)]
         h = h + np.concatenate(ca, axis=0)
         u2 = modulate(h, sh2, sc2, cfg.eps)
-        h = h + g2 * ffn(u2, w)
+        h = h + g2 * ffn(u2, w, cfg)
     out = x_in + h * dt
     return [out[i * nc:(i + 1) * nc] for i in range(n_chunks)]

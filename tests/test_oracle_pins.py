@@ -503,3 +503,95 @@ def test_sample_chunk_is_T_stages_with_independent_per_step_caches():
     np.testing.assert_array_equal(xa, xb)
     assert np.abs(O.denoise_stage(xa, layers, a[1], ctx, mod6[1], -1.0 / T, 1, 1, cfg)
                   - O.denoise_stage(xb, layers, b[1], ctx, mod6[1], -1.0 / T, 1, 1, cfg)).max() > 1e-6
+
+
+# ---------------------------------------------------------------- FP8 E4M3 per-tensor linears (Appendix C)
+def e4m3_decode_table():
+    """All 256 codes decoded from the format's definition: s eeee mmm, bias 7, e = 0 subnormal, 0x7f / 0xff NaN."""
+    vals = np.empty(256)
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = np.nan
+        elif e == 0:
+            v = m * 2.0 ** -9
+        else:
+            v = (1 + m / 8.0) * 2.0 ** (e - 7)
+        vals[c] = -v if s else v
+    return vals
+
+
+def test_e4m3_rounding_against_the_code_table_and_torch():
+    import torch
+    tab = e4m3_decode_table()
+    fin = tab[np.isfinite(tab)]
+    assert fin.max() == 448.0 and np.abs(fin[fin != 0]).min() == 2.0 ** -9
+    # every grid value is a fixed point; midpoints go to the even mantissa; saturation
+    np.testing.assert_array_equal(O.e4m3_round(fin), fin)
+    pos = np.unique(np.abs(fin))                       # 127 values: 0, 7 subnormals, 119 normals
+    assert len(pos) == 127
+    mid = (pos[:-1] + pos[1:]) / 2
+    even = np.where((np.arange(len(pos) - 1) % 2) == 0, pos[:-1], pos[1:])     # code parity = mantissa parity
+    np.testing.assert_array_equal(O.e4m3_round(mid), even)
+    np.testing.assert_array_equal(O.e4m3_round(-mid), -even)
+    np.testing.assert_array_equal(O.e4m3_round(np.array([448.0, 449.0, 463.9, 1e6, -1e6])), [448, 448, 448, 448, -448])
+    # nearest-neighbour brute force on random values, and the library's conversion of the same published format
+    y = np.concatenate([rng.standard_normal(3000) * s for s in (1e-3, 0.05, 1.0, 30.0, 150.0)])
+    y = y[np.abs(y) <= 448].astype(np.float32).astype(np.float64)
+    got = O.e4m3_round(y)
+    d = np.abs(y[:, None] - fin[None, :])
+    assert np.all(np.abs(got - y) <= d.min(1) + 0.0)
+    lib = torch.from_numpy(y.astype(np.float32)).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    np.testing.assert_array_equal(got, lib)
+    # relative error of a normal value is at most half a mantissa step
+    big = np.abs(y) >= 2.0 ** -6
+    assert (np.abs(got[big] - y[big]) / np.abs(y[big])).max() <= 2.0 ** -4
+
+
+def test_fp8_per_tensor_quantisation_and_linear():
+    x = rng.standard_normal((37, 64)) * 3.0
+    x[5, 7] = -11.5                                   # the amax element
+    q, s = O.fp8_quantize_per_tensor(x)
+    assert s == float(np.float32(11.5) / np.float32(448)) and q[5, 7] == -448.0
+    assert set(np.unique(np.abs(q))) <= set(np.abs(e4m3_decode_table()[:127]))
+    # dequantised values are within half a grid step of x: |x| <= amax, step <= 2^-4 of the value (normals) or 2^-9*s
+    err = np.abs(q * s - x.astype(np.float32).astype(np.float64))
+    assert (err <= np.maximum(np.abs(x) * 2.0 ** -4, 2.0 ** -10 * s) * (1 + 1e-6)).all()
+    # scale invariance: quantising 4x gives the same grid values and 4x the scale (powers of two are exact in fp32)
+    q4, s4 = O.fp8_quantize_per_tensor(4 * x)
+    np.testing.assert_array_equal(q4, q)
+    assert s4 == 4 * s
+    zq, zs = O.fp8_quantize_per_tensor(np.zeros((3, 8)))
+    assert zs == 1.0 and not zq.any()
+    # operands already on the grid (times a power of two) pass through exactly: linear_fp8 == exact product
+    tab = e4m3_decode_table()
+    grid = tab[np.isfinite(tab)]
+    a = rng.choice(grid, size=(9, 16)); a[0, 0] = 448.0
+    w = rng.choice(grid, size=(5, 16)) * 0.25; w[0, 0] = 112.0
+    np.testing.assert_allclose(O.linear_fp8(a, w), a @ w.T, rtol=1e-6, atol=0)
+    # general operands: the error against the exact product is bounded by the two half-step bounds
+    W = rng.standard_normal((24, 64)) * 0.05
+    y, ref = O.linear_fp8(x, W), x @ W.T
+    bound = (np.abs(x) * 2.0 ** -4 + 2.0 ** -10 * s) @ np.abs(W).T + np.abs(x) @ (np.abs(W) * 2.0 ** -4 + 1e-4).T
+    assert (np.abs(y - ref) <= bound * 1.1).all() and np.abs(y - ref).max() > 1e-4
+
+
+def test_block_with_fp8_linears_is_a_small_perturbation_of_the_exact_block():
+    cfg, cfg8 = tiny_cfg(), tiny_cfg()
+    cfg8.fp8_linears = True
+    d = cfg.d_model
+    x = rng.standard_normal((cfg.chunk_tokens, d))
+    ctx = rng.standard_normal((5, d))
+    w = tiny_weights(cfg)
+    y = O.dit_block(x, w, fresh_cache(cfg, 1), ctx, None, 0, 1, cfg)
+    y8 = O.dit_block(x, w, fresh_cache(cfg, 1), ctx, None, 0, 1, cfg8)
+    rel = np.sqrt(((y8 - y) ** 2).mean() / ((y - x) ** 2).mean())       # against what the block adds to x
+    assert 1e-3 < rel < 0.12, rel                                       # 3 mantissa bits: a few per cent per linear
+    # zero output projections: an all-zero tensor quantises to zeros (scale 1), the block stays the identity
+    w0 = dict(w, W_o=np.zeros((d, d)), Wc_o=np.zeros((d, d)), W_2=np.zeros_like(w["W_2"]))
+    np.testing.assert_array_equal(O.dit_block(x, w0, fresh_cache(cfg, 1), ctx, None, 0, 1, cfg8), x)
+    # what goes into the cache is computed from the quantised QKV projection
+    c = fresh_cache(cfg, 1)
+    O.dit_block(x, w, c, ctx, None, 0, 1, cfg8)
+    qkv = O.linear_fp8(O.layernorm(x, cfg.eps), w["W_qkv"])
+    np.testing.assert_array_equal(c.blocks[0][2].reshape(-1, d), qkv[:, 2 * d:])
