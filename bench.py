@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-level", type=int, default=2, help="1: time attention launches only, 2: every kernel class")
     ap.add_argument("--cpu-sample-tokens", type=int, default=2340)
+    ap.add_argument("--fp8", action="store_true",
+                    help="NOT the headline: run every linear of the stage in FP8 E4M3 with per-tensor dynamic scaling (the paper's own "
+                         "default, Appendix C); attention, norms and the residual stream are unchanged; dtype is reported as such")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one denoise stage = one timestep of the pipeline on one GPU); "
@@ -108,7 +111,7 @@ def main():
     ROW_PAD = 64  # weight rows padded by 128 bytes (row stride in_features + 64), see include/lvx.h
     layers = [S.block_weights(d, p["ffn"], l, "bench", std=0.02, device=dev, on_device_draw=True, row_pad=ROW_PAD) for l in range(L)]
     rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
-    stage = lvx.StageHandle(layers, rope, p["ffn"], ldw_d=d + ROW_PAD, ldw_ffn=p["ffn"] + ROW_PAD)
+    stage = lvx.StageHandle(layers, rope, p["ffn"], ldw_d=d + ROW_PAD, ldw_ffn=p["ffn"] + ROW_PAD, fp8=args.fp8, keep_bf16=not args.fp8)
     cache = lvx.KVCache(lvx.cache_desc(L, H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"]), dev)
     cache.attach_sink_source()   # un-rotated sink keys: the sink's rotary index is re-assigned before every forward (Rolling RoPE)
     for l in range(L):
@@ -122,7 +125,8 @@ def main():
     x = torch.empty_like(xs[0])
     torch.cuda.synchronize()
     print("[bench] setup %.1f s: %d layers, %.1f GB weights, %.1f GB cache, %.2f GB workspace" % (
-        time.perf_counter() - t_setup, L, sum(t.numel() * t.element_size() for w in layers for t in w.values()) / 1e9,
+        time.perf_counter() - t_setup, L, (sum(t.numel() * t.element_size() for w in layers for t in w.values() if t is not None)
+                                       + sum(t.numel() * t.element_size() for t in stage.fp8_tensors)) / 1e9,
         cache.storage.numel() / 1e9, ws.numel() / 1e9), file=sys.stderr, flush=True)
 
     chunk = [0]
@@ -167,7 +171,7 @@ def main():
         "metric": "latent frames/s per denoise stage (chunk-attention TFLOP/s and % of bf16 MFMA peak in `roofline`)",
         "value": round(frames_per_s, 4), "unit": "latent frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "fp8 e4m3 linears (per-tensor dynamic scaling), bf16 attention" if args.fp8 else "bf16", "data": "synthetic",
         "config": {"workload": "configs[4]: one denoise stage on one GPU, %d DiT blocks (hidden 5120, 40 heads x 128, FFN 13824, "
                                "544 context tokens), chunk 3x1560=4680 tokens, rolling cache full: sink 1560 + 4 past chunks + self "
                                "= 24960 keys per layer (the attention inside is configs[1])" % L,

@@ -200,6 +200,20 @@ lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64
                         int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi, const void *dev_resid, int64_t ldr,
                         const float *dev_gate, lvx_stream_t stream);
 
+/* FP8 linears (Appendix C, "FP8 Quantization": all linear projections of the DiT in E4M3 with per-tensor dynamic scaling).
+ *   lvx_fp8_quantize: x bf16 [rows][ld] -> q [rows][ldq] E4M3 codes (OCP form: bias 7, largest finite value 448) and one fp32
+ *     dequantisation scale = amax/448 (1 for an all-zero tensor), amax = max|x| over the whole matrix:
+ *     code = E4M3(x * (448/amax)), nearest-even, saturating; scale factors and that product are formed in fp32.
+ *     dev_scratch16: 16 bytes of device scratch (16-byte aligned).  cols % 16 == 0, ldq % 16 == 0.  Used for weights (once)
+ *     and activations (every call) alike.
+ *   lvx_linear_fp8: C[M][N] = epilogue(scale_a * scale_w * (Aq[M][K] . Wq[N][K]^T)), fp32 accumulate on the FP8 matrix
+ *     cores, C / R / gate and the epilogues as in lvx_linear.  K % 128 == 0, N % 8 == 0, lda and ldw in bytes, % 16 == 0. */
+lvx_status_t lvx_fp8_quantize(const void *dev_x, int64_t ld, int32_t rows, int32_t cols, void *dev_q, int64_t ldq,
+                              void *dev_scratch16, float *dev_scale, lvx_stream_t stream);
+lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
+                            const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                            lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate, lvx_stream_t stream);
+
 /* u = LayerNorm(x) * (1 + scale) + shift, no affine, biased variance, eps inside the root.  shift/scale fp32 [d]
  * or NULL (0).  x, u: [n][ld] bf16. */
 lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale,
@@ -227,6 +241,13 @@ typedef struct {
     const float *gc_q, *gc_k; /* [d] cross-attention RMSNorm gains, NULL = no norm */
 } lvx_block_weights_t;
 
+/* FP8 form of a block's linear weights (Appendix C): E4M3 codes from lvx_fp8_quantize, one per-tensor scale each (the fused
+ * QKV matrix is one tensor).  Shapes as in lvx_block_weights_t, row strides ldw8_d / ldw8_ffn bytes. */
+typedef struct {
+    const void *W_qkv, *W_o, *Wc_q, *Wc_k, *Wc_v, *Wc_o, *W_1, *W_2;
+    const float *scales; /* device, 8 floats: dequantisation scales in the order of the pointers above */
+} lvx_block_weights_fp8_t;
+
 typedef struct {
     int32_t n_layers;
     int32_t d_ffn;
@@ -234,6 +255,11 @@ typedef struct {
     int32_t ldw_ffn;                   /* row stride (elements) of W_2 (in_features = d_ffn); 0 = dense */
     lvx_rope_desc_t rope;              /* n_heads*head_dim = d_model; must agree with the cache descriptor */
     const lvx_block_weights_t *blocks; /* host array [n_layers] of device pointers */
+    /* NULL: bf16 linears.  Else host array [n_layers]: every linear of the block quantises its input activation per tensor
+     * (dynamically, each call) and multiplies on the FP8 matrix cores; the bf16 weight pointers in `blocks` are then unused
+     * (may be NULL), its RMSNorm gains are still read.  d_model and d_ffn must then be multiples of 128. */
+    const lvx_block_weights_fp8_t *blocks_fp8;
+    int32_t ldw8_d, ldw8_ffn;          /* row strides (bytes) of the FP8 weights; 0 = dense */
 } lvx_stage_t;
 
 size_t lvx_workspace_bytes(const lvx_stage_t *stage /* host */, int32_t n_tokens, int32_t n_ctx);
@@ -288,7 +314,8 @@ lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage /* host */, lvx_kvcache_t
 enum {
     LVX_PROF_ATTN_SELF = 0, LVX_PROF_GEMM_QKV = 1, LVX_PROF_GEMM_O = 2, LVX_PROF_GEMM_CROSS = 3, LVX_PROF_GEMM_FFN1 = 4,
     LVX_PROF_GEMM_FFN2 = 5, LVX_PROF_ATTN_CROSS = 6, LVX_PROF_ROPE_NORM = 7, LVX_PROF_APPEND = 8, LVX_PROF_LAYERNORM = 9,
-    LVX_PROF_KINDS = 10
+    LVX_PROF_FP8_QUANT = 10, /* per-tensor quantisation of the linears' input activations (FP8 stages only) */
+    LVX_PROF_KINDS = 11
 };
 lvx_status_t lvx_profile_set(int32_t level);
 lvx_status_t lvx_profile_read(double *ms_total /* host [LVX_PROF_KINDS] */, int64_t *launches /* host [LVX_PROF_KINDS] */);

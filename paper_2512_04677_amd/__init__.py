@@ -48,9 +48,17 @@ class BlockWeights(C.Structure):
                                           "g_q", "g_k", "gc_q", "gc_k")]
 
 
+class BlockWeightsFp8(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("W_qkv", "W_o", "Wc_q", "Wc_k", "Wc_v", "Wc_o", "W_1", "W_2", "scales")]
+
+
+FP8_WEIGHT_ORDER = ("W_qkv", "W_o", "Wc_q", "Wc_k", "Wc_v", "Wc_o", "W_1", "W_2")
+
+
 class Stage(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_ffn", C.c_int32), ("ldw_d", C.c_int32), ("ldw_ffn", C.c_int32), ("rope", RopeDesc),
-                ("blocks", C.POINTER(BlockWeights))]
+                ("blocks", C.POINTER(BlockWeights)), ("blocks_fp8", C.POINTER(BlockWeightsFp8)), ("ldw8_d", C.c_int32),
+                ("ldw8_ffn", C.c_int32)]
 
 
 # name -> (restype, argtypes); the list the header declares
@@ -70,6 +78,8 @@ SIGNATURES = {
     "lvx_rope3d": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
     "lvx_chunk_attention": (C.c_int, [_vp, _i32, _vp, _i64, _i32, _f32, _vp, _i64, _vp]),
     "lvx_linear": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
+    "lvx_fp8_quantize": (C.c_int, [_vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp]),
+    "lvx_linear_fp8": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
     "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
     "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
@@ -88,7 +98,7 @@ SIGNATURES = {
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 PROF_KINDS = ["attn_self", "gemm_qkv", "gemm_o", "gemm_cross", "gemm_ffn1", "gemm_ffn2", "attn_cross", "rope_norm", "append",
-              "layernorm"]
+              "layernorm", "fp8_quant"]
 
 
 def load():
@@ -240,6 +250,24 @@ def lvx_linear(a, w, c, epi=EPI_STORE, resid=None, gate=None, M=None):
                              _ptr(resid), resid.stride(0) if resid is not None else 0, _ptr(gate), _stream()))
 
 
+def lvx_fp8_quantize(x, q=None, row_pad=0):
+    """Quantises the bf16 matrix x per tensor; returns (codes uint8 [rows][cols] view, scale fp32 [1])."""
+    import torch
+    rows, cols = x.shape
+    if q is None:
+        q = torch.empty((rows, cols + row_pad), dtype=torch.uint8, device=x.device)[:, :cols]
+    scratch = torch.empty(16, dtype=torch.uint8, device=x.device)
+    scale = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(load().lvx_fp8_quantize(_ptr(x), x.stride(0), rows, cols, _ptr(q), q.stride(0), _ptr(scratch), _ptr(scale), _stream()))
+    return q, scale
+
+
+def lvx_linear_fp8(aq, scale_a, wq, scale_w, c, epi=EPI_STORE, resid=None, gate=None):
+    M, N, K = aq.shape[0], wq.shape[0], wq.shape[1]
+    _check(load().lvx_linear_fp8(_ptr(aq), aq.stride(0), _ptr(scale_a), _ptr(wq), wq.stride(0), _ptr(scale_w), _ptr(c), c.stride(0),
+                                 M, N, K, epi, _ptr(resid), resid.stride(0) if resid is not None else 0, _ptr(gate), _stream()))
+
+
 def lvx_layernorm_modulate(x, shift, scale, eps, u):
     _check(load().lvx_layernorm_modulate(_ptr(x), x.stride(0), _ptr(shift), _ptr(scale), eps, x.shape[0], x.shape[1],
                                          _ptr(u), u.stride(0), _stream()))
@@ -248,16 +276,41 @@ def lvx_layernorm_modulate(x, shift, scale, eps, u):
 class StageHandle:
     """Host-side stage descriptor: keeps the weight tensors alive and holds the C structs."""
 
-    def __init__(self, layers, rope, d_ffn, ldw_d=0, ldw_ffn=0):
+    def __init__(self, layers, rope, d_ffn, ldw_d=0, ldw_ffn=0, fp8=False, fp8_row_pad=128, keep_bf16=True):
+        """layers: list of dicts of bf16 weight tensors (+ fp32 gains).  fp8=True quantises every linear weight per tensor
+        with lvx_fp8_quantize (E4M3 codes + one scale each) and makes the stage run its linears in FP8; with
+        keep_bf16=False the bf16 matrices are dropped from the dicts afterwards (the gains stay)."""
+        import torch
         self.layers = layers
         self.n = len(layers)
         self.blocks = (BlockWeights * self.n)()
+        self.blocks_fp8 = None
+        self.fp8_tensors = []
+        ldw8_d = ldw8_ffn = 0
+        if fp8:
+            self.blocks_fp8 = (BlockWeightsFp8 * self.n)()
+            for i, w in enumerate(layers):
+                scales = torch.empty(len(FP8_WEIGHT_ORDER), dtype=torch.float32, device=w["W_qkv"].device)
+                for j, name in enumerate(FP8_WEIGHT_ORDER):
+                    q, s = lvx_fp8_quantize(w[name], row_pad=fp8_row_pad)
+                    scales[j:j + 1].copy_(s)
+                    setattr(self.blocks_fp8[i], name, q.data_ptr())
+                    self.fp8_tensors.append(q)
+                    if name == "W_qkv":
+                        ldw8_d = q.stride(0)
+                    if name == "W_2":
+                        ldw8_ffn = q.stride(0)
+                    if not keep_bf16:
+                        w[name] = None
+                self.blocks_fp8[i].scales = scales.data_ptr()
+                self.fp8_tensors.append(scales)
         for i, w in enumerate(layers):
             for name, _ in BlockWeights._fields_:
                 t = w.get(name)
                 setattr(self.blocks[i], name, None if t is None else t.data_ptr())
         self.rope = rope
-        self.c = Stage(self.n, d_ffn, ldw_d, ldw_ffn, rope, C.cast(self.blocks, C.POINTER(BlockWeights)))
+        self.c = Stage(self.n, d_ffn, ldw_d, ldw_ffn, rope, C.cast(self.blocks, C.POINTER(BlockWeights)),
+                       C.cast(self.blocks_fp8, C.POINTER(BlockWeightsFp8)) if fp8 else None, ldw8_d, ldw8_ffn)
 
 
 def lvx_workspace_bytes(stage, n_tokens, n_ctx):

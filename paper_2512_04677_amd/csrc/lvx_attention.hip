@@ -25,11 +25,6 @@ namespace {
 
 constexpr int KT = LVX_KEY_TILE;
 
-// direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane
-__device__ __forceinline__ void lvx_attn_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
-}
-
 template <int D, int NWAVES>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
@@ -114,13 +109,13 @@ __global__ void __launch_bounds__(64 * NWAVES)
     {                                                                                                                       \
         const int tt_ = (t_) < last_tile ? (t_) : last_tile;                                                                \
         _Pragma("unroll") for (int e = 0; e < DPW; ++e)                                                                     \
-            lvx_attn_dma16(k_src + (size_t)tt_ * TILE_B, kdoff[e], ks_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
+            lvx_dma16(k_src + (size_t)tt_ * TILE_B, kdoff[e], ks_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
     }
 #define LVX_ATTN_DMA_V(t_)                                                                                                  \
     {                                                                                                                       \
         const int tt_ = (t_) < last_tile ? (t_) : last_tile;                                                                \
         _Pragma("unroll") for (int e = 0; e < DPW; ++e)                                                                     \
-            lvx_attn_dma16(v_src + (size_t)tt_ * TILE_B, vdoff[e], vs_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
+            lvx_dma16(v_src + (size_t)tt_ * TILE_B, vdoff[e], vs_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
     }
     // stage u = { V^T(u), K(u+1) }: what the matrix phase X(u) reads
 #define LVX_ATTN_STAGE_DMA(u_) \

@@ -42,7 +42,8 @@ struct prof_scope_t {
 };
 
 struct ws_layout_t {
-    size_t u, big, ctx_kv, pack_k, pack_v, h, total;  // byte offsets
+    size_t u, big, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
+    int64_t ld_q8, ld_q8c;                            // row strides (bytes) of the FP8 activation buffers
     int cap_ctx;
     int64_t ld_u, ld_qkv, ld_cq, ld_ffn, ld_ckv;      // padded row strides (elements) of the bf16 workspace matrices
 };
@@ -70,6 +71,15 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.h = off;       off += round256((size_t)n_tokens * d * 4);  // fp32 residual stream
+    w.q8 = w.q8_ctx = w.q8_misc = off;
+    const size_t wide_in = d > (size_t)s->d_ffn ? d : (size_t)s->d_ffn;
+    w.ld_q8 = (int64_t)wide_in + 128;
+    w.ld_q8c = (int64_t)d + 128;
+    if (s->blocks_fp8 != nullptr) {  // quantised input activation of the running linear, quantised context, amax scratch + scales
+        w.q8 = off;       off += round256((size_t)n_tokens * w.ld_q8);
+        w.q8_ctx = off;   off += round256((size_t)n_ctx * w.ld_q8c);
+        w.q8_misc = off;  off += 256;
+    }
     w.total = off;
     return w;
 }
@@ -85,6 +95,13 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
     LVX_REQUIRE(n_tokens > 0 && n_ctx > 0, LVX_ERR_SHAPE, "n_tokens %d and n_ctx %d must be positive", n_tokens, n_ctx);
     LVX_REQUIRE((s->ldw_d == 0 || (s->ldw_d >= d && s->ldw_d % 8 == 0)) && (s->ldw_ffn == 0 || (s->ldw_ffn >= s->d_ffn && s->ldw_ffn % 8 == 0)),
                 LVX_ERR_SHAPE, "weight row strides must be 0 (dense) or multiples of 8 not below in_features");
+    if (s->blocks_fp8 != nullptr) {
+        LVX_REQUIRE(d % 128 == 0 && s->d_ffn % 128 == 0, LVX_ERR_SHAPE, "FP8 linears need d_model %d and d_ffn %d to be multiples of 128", d,
+                    s->d_ffn);
+        LVX_REQUIRE((s->ldw8_d == 0 || (s->ldw8_d >= d && s->ldw8_d % 16 == 0)) &&
+                        (s->ldw8_ffn == 0 || (s->ldw8_ffn >= s->d_ffn && s->ldw8_ffn % 16 == 0)),
+                    LVX_ERR_SHAPE, "FP8 weight row strides must be 0 (dense) or multiples of 16 not below in_features");
+    }
     if (c != nullptr) {
         LVX_REQUIRE(c->desc.n_heads == s->rope.n_heads && c->desc.head_dim == s->rope.head_dim && c->desc.frame_h == s->rope.frame_h &&
                         c->desc.frame_w == s->rope.frame_w,
@@ -95,12 +112,6 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
     }
     return LVX_OK;
 }
-
-#define LVX_TRY(expr)                    \
-    do {                                 \
-        lvx_status_t st_ = (expr);       \
-        if (st_ != LVX_OK) return st_;   \
-    } while (0)
 
 // x: the fp32 residual stream [n][d].
 // sink_prefill = false: the chunk's forward (its K-hat / V go to the ring slot of chunk_index, attention over the visible prefix).
@@ -125,9 +136,29 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     const int64_t ldw = s->ldw_d > 0 ? s->ldw_d : d, ldw2 = s->ldw_ffn > 0 ? s->ldw_ffn : f;
     const int64_t ldu = L.ld_u, ldq = L.ld_qkv, ldc = L.ld_cq, ldf = L.ld_ffn, ldk = L.ld_ckv;
 
+    // One linear of the block: bf16, or (Appendix C) FP8 with the input activation quantised per tensor right before it.
+    // which: index into the FP8 weight pointers / scales (0 W_qkv .. 7 W_2); reuse_ctx: the context was already quantised.
+    const lvx_block_weights_fp8_t *w8 = s->blocks_fp8 ? &s->blocks_fp8[layer] : nullptr;
+    const int64_t ldw8 = s->ldw8_d > 0 ? s->ldw8_d : d, ldw8_2 = s->ldw8_ffn > 0 ? s->ldw8_ffn : f;
+    uint32_t *amax_scratch = (uint32_t *)(ws + L.q8_misc);
+    float *scale_act = (float *)(ws + L.q8_misc + 16), *scale_ctx = (float *)(ws + L.q8_misc + 32);
+    auto linear = [&](const bf16_t *A, int64_t lda, const void *Wbf, int which, void *C, int64_t ldc_, int M, int N, int K, lvx_epilogue_t epi,
+                      const void *R, int64_t ldr, const float *gate, bool is_ctx, bool reuse_ctx) -> lvx_status_t {
+        if (w8 == nullptr) return lvx_linear(A, lda, Wbf, K == f ? ldw2 : ldw, C, ldc_, M, N, K, epi, R, ldr, gate, st);
+        const void *const w8p[8] = {w8->W_qkv, w8->W_o, w8->Wc_q, w8->Wc_k, w8->Wc_v, w8->Wc_o, w8->W_1, w8->W_2};
+        uint8_t *aq = (uint8_t *)(ws + (is_ctx ? L.q8_ctx : L.q8));
+        const int64_t ldaq = is_ctx ? L.ld_q8c : L.ld_q8;
+        float *sa = is_ctx ? scale_ctx : scale_act;
+        if (!reuse_ctx) {
+            prof_scope_t ps(LVX_PROF_FP8_QUANT, st);
+            LVX_TRY(lvx_launch_fp8_quantize(A, lda, M, K, aq, ldaq, amax_scratch, sa, st));
+        }
+        return lvx_linear_fp8(aq, ldaq, sa, w8p[which], K == f ? ldw8_2 : ldw8, w8->scales + which, C, ldc_, M, N, K, epi, R, ldr, gate, st);
+    };
+
     // self-attention branch
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(lvx_linear(u, ldu, w.W_qkv, ldw, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false)); }
     if (!sink_prefill) {
         { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
         { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
@@ -142,15 +173,15 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->sink_keys, scale, u,
                                      ldu, st));
     }
-    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(lvx_linear(u, ldu, w.W_o, ldw, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(linear(u, ldu, w.W_o, 1, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, false, false)); }
 
     // cross-attention to the audio + text context
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st)); }
     {
         prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
-        LVX_TRY(lvx_linear(u, ldu, w.Wc_q, ldw, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-        LVX_TRY(lvx_linear(ctx, d, w.Wc_k, ldw, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
-        LVX_TRY(lvx_linear(ctx, d, w.Wc_v, ldw, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, st));
+        LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false));
+        LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false));
+        LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true));
     }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
@@ -162,12 +193,12 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     }
     LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
     { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(lvx_linear(u, ldu, w.Wc_o, ldw, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false)); }
 
     // feed-forward
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(lvx_linear(u, ldu, w.W_1, ldw, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(lvx_linear(big, ldf, w.W_2, ldw2, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, st)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(linear(u, ldu, w.W_1, 6, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, false, false)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(linear(big, ldf, w.W_2, 7, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, false, false)); }
     return LVX_OK;
 }
 

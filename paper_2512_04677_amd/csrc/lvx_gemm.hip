@@ -20,13 +20,6 @@ constexpr int BK = 64;
 constexpr int LDT = BK + 8;  // padded LDS row (bf16)
 constexpr int GROUP_M = 8;
 
-__device__ __forceinline__ float gelu_tanh_f32(float x) {
-    // 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
-    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-    const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
-    return x * __builtin_amdgcn_rcpf(1.0f + e);
-}
-
 // Epilogue shared by both kernels.  Accumulator register 4g+r of fragment (i,j) holds row m0 + 32i + 8g + r and column
 // n0 + 32j of C (m0, n0 already include the lane's 4*hh / l32 offsets): for a fixed register, 32 lanes write 32 consecutive
 // columns.  Interior tiles take the branch-free path; only tiles on the M or N edge check every element.
@@ -257,10 +250,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 // c ^ ((r >> 1) & 7): 16 consecutive rows then cover 16 distinct 16-byte units of the 256-byte bank row.
 // The loads are issued through inline asm with explicit s_waitcnt vmcnt(n): the compiler would otherwise wait for ALL
 // outstanding DMA before any LDS read that might alias, which would undo the multi-stage pipeline.
-__device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
-}
-
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,

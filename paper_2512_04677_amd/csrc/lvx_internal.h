@@ -31,6 +31,12 @@ lvx_status_t lvx_fail(lvx_status_t code, const char *fmt, ...);
         if (!(cond)) return lvx_fail((code), __VA_ARGS__);   \
     } while (0)
 
+#define LVX_TRY(expr)                    \
+    do {                                 \
+        lvx_status_t st_ = (expr);       \
+        if (st_ != LVX_OK) return st_;   \
+    } while (0)
+
 static inline bool lvx_aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 
 // ---- device helpers -------------------------------------------------------------------------
@@ -43,6 +49,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
     r[0] = (__bf16)a;
     r[1] = (__bf16)b;
     return *reinterpret_cast<uint32_t *>(&r);
+}
+
+// 0.5 x (1 + tanh(u)) = x / (1 + exp(-2u)),  u = sqrt(2/pi) (x + 0.044715 x^3)
+__device__ __forceinline__ float gelu_tanh_f32(float x) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
+    return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+// direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane
+__device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
 }
 
 // ---- cache handle (host) ----------------------------------------------------------------------
@@ -84,5 +101,9 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// Per-tensor dynamic FP8 quantisation of a bf16 matrix (amax, then codes and the dequantisation scale); amax_bits: 16 bytes of
+// device scratch.
+lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_bits,
+                                     float *scale, hipStream_t stream);
 // Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
 lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);
