@@ -147,3 +147,30 @@ def test_sink_management_host_checks():
     st = lvx.Stage(1, 13824, 0, 0, r, C.cast(blocks, C.POINTER(lvx.BlockWeights)))
     assert lib.lvx_sink_prefill(C.byref(st), None, p, p, 544, None, 1, None, p, 1 << 30, None) == 1
     assert b"NULL" in lib.lvx_last_error()
+
+
+def test_fp8_entry_points_host_checks():
+    lib = lvx.load()
+    p = C.c_void_p(4096)
+    f = C.c_void_p(8192)
+    assert lib.lvx_fp8_quantize(None, 64, 4, 64, p, 64, p, f, None) == 1
+    assert lib.lvx_fp8_quantize(p, 64, 4, 60, p, 64, p, f, None) == 2            # cols % 16
+    assert lib.lvx_fp8_quantize(p, 64, 4, 64, p, 72, p, f, None) == 2            # ldq % 16
+    assert lib.lvx_fp8_quantize(p, 32, 4, 64, p, 64, p, f, None) == 2            # ld < cols
+    assert lib.lvx_fp8_quantize(p, 64, 4, 64, p, 64, C.c_void_p(4100), f, None) == 1
+    assert lib.lvx_linear_fp8(p, 128, f, p, 128, f, p, 64, 4, 64, 192, 0, None, 0, None, None) == 2    # K % 128
+    assert lib.lvx_linear_fp8(p, 128, f, p, 128, f, p, 64, 4, 60, 128, 0, None, 0, None, None) == 2    # N % 8
+    assert lib.lvx_linear_fp8(p, 120, f, p, 128, f, p, 64, 4, 64, 128, 0, None, 0, None, None) == 2    # lda
+    assert lib.lvx_linear_fp8(p, 128, None, p, 128, f, p, 64, 4, 64, 128, 0, None, 0, None, None) == 1 # scale missing
+    assert lib.lvx_linear_fp8(p, 128, f, p, 128, f, p, 64, 4, 64, 128, 3, None, 0, None, None) == 1    # residual missing
+    # an FP8 stage needs d_model and d_ffn in multiples of 128 and 16-byte multiples as row strides
+    r = lvx.rope_desc(40, 128, (44, 42, 42), 1e4, 30, 52)
+    blocks = (lvx.BlockWeights * 1)()
+    b8 = (lvx.BlockWeightsFp8 * 1)()
+    cast8 = C.cast(b8, C.POINTER(lvx.BlockWeightsFp8))
+    castb = C.cast(blocks, C.POINTER(lvx.BlockWeights))
+    ok = lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 128, 13824 + 128)
+    plain = lvx.Stage(1, 13824, 0, 0, r, castb)
+    assert lib.lvx_workspace_bytes(C.byref(ok), 4680, 544) >= lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) + 4680 * 13824
+    assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824 + 64, 0, 0, r, castb, cast8, 0, 0)), 4680, 544) == 0
+    assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 8, 0)), 4680, 544) == 0
