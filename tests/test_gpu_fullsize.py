@@ -218,3 +218,75 @@ def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
     assert torch.equal(cache_a.storage, cache_b.storage)
     cache_a.close()
     cache_b.close()
+
+
+def test_fullsize_rolling_sink_update_all_layers_one_launch(lvx):
+    """Phi(sink) at the benchmark's shape and launch: 4 layers x 1560 sink tokens x 5120 channels rotated in ONE launch
+    (layer = -1) to an index near the 10 000 s rollout's; every layer's sink keys are compared with the oracle on sampled
+    tokens, its values bit for bit; the chunk stored next to the sink (sharing the sink's last 64-key tile) is untouched and
+    the attention over {sink, chunk} is checked on sampled rows."""
+    d, sink_n, n = dims(P)
+    H, D, W = P["n_heads"], P["head_dim"], P["window"]
+    L = 4
+    cfg = O.StageConfig(H, D, P["frame_h"], P["frame_w"], P["chunk_frames"], W, P["sink_frames"], P["rope_axes"])
+    rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
+    cache = make_cache(lvx, P, L)
+    cache.attach_sink_source()
+    srcs, vals = [], []
+    ck = S.randn_bf16_device((n, d), 31, 1.0, DEV)
+    cv = S.randn_bf16_device((n, d), 32, 1.0, DEV)
+    for l in range(L):
+        srcs.append(S.randn_bf16_device((sink_n, d), 40 + l, 1.0, DEV))
+        vals.append(S.randn_bf16_device((sink_n, d), 50 + l, 1.0, DEV))
+        lvx.lvx_kvcache_reset_sink(cache, l, srcs[l], vals[l])
+        lvx.lvx_chunk_append_evict(cache, l, ck, cv, 0)
+    t_sink = 39998
+    lvx.lvx_sink_rope_update(cache, rope, -1, t_sink)
+    toks = np.array(sorted(set([0, 1, 51, 52, 1535, 1536, 1559] + np.random.default_rng(3).choice(sink_n, 16, replace=False).tolist())))
+    pos = tuple(a[toks] for a in O.token_positions(sink_n, t_sink, P["frame_h"], P["frame_w"]))
+    q = S.randn_bf16_device((n, d), 33, 1.0, DEV)
+    out = torch.empty_like(q)
+    rows = sample_rows(n, 6, 9)
+    for l in range(L):
+        gk = torch.empty((sink_n + n, d), dtype=torch.bfloat16, device=DEV)
+        gv = torch.empty_like(gk)
+        lvx.lvx_kvcache_gather(cache, l, 0, sink_n + n, gk, gv)
+        torch.cuda.synchronize()
+        assert lvx.lvx_kvcache_get_sink_index(cache, l) == t_sink
+        assert torch.equal(gv[:sink_n].view(torch.int16), vals[l].view(torch.int16))
+        assert torch.equal(gk[sink_n:].view(torch.int16), ck.view(torch.int16)) and torch.equal(gv[sink_n:].view(torch.int16), cv.view(torch.int16))
+        ti = torch.as_tensor(toks, device=DEV)
+        ref = O.rope3d(S.to_f64(srcs[l][ti]).reshape(-1, H, D), 0, P["frame_h"], P["frame_w"], cfg.rope_axes, cfg.theta, pos)
+        assert_close(gk[ti], ref.reshape(len(toks), d), "layer %d sink keys at t=%d (sampled tokens)" % (l, t_sink))
+        if l in (0, L - 1):
+            lvx.lvx_chunk_attention(cache, l, q, 1 / math.sqrt(D), out)
+            torch.cuda.synchronize()
+            k_all = S.to_f64(gk).reshape(-1, H, D)        # cache contents as the GPU holds them (gated above / bit-exact)
+            v_all = S.to_f64(gv).reshape(-1, H, D)
+            ri = torch.as_tensor(rows, device=DEV)
+            want = O.attention(S.to_f64(q[ri]).reshape(-1, H, D), k_all, v_all, 1 / math.sqrt(D))
+            assert_close(out[ri], want.reshape(len(rows), d), "layer %d attention over {rolled sink, chunk 0}" % l)
+    cache.close()
+
+
+def test_fullsize_fp8_qkv_linear_sampled_rows(lvx):
+    """The FP8 QKV projection at the benchmark's shape (4680 x 15360 x 5120, padded row strides as in bench.py): codes of the
+    activation and of a slice of the weight bit for bit, the scales exactly, the output on sampled rows against the oracle's
+    quantise-dequantise product."""
+    M, N, K = 4680, 15360, 5120
+    a = S.randn_bf16_device((M, K + 64), 61, 1.0, DEV)[:, :K]
+    w = S.randn_bf16_device((N, K + 64), 62, 0.02, DEV)[:, :K]
+    aq, sa = lvx.lvx_fp8_quantize(a, row_pad=128)
+    wq, sw = lvx.lvx_fp8_quantize(w, row_pad=128)
+    c = torch.empty((M, N + 64), dtype=torch.bfloat16, device=DEV)[:, :N]
+    lvx.lvx_linear_fp8(aq, sa, wq, sw, c)
+    torch.cuda.synchronize()
+    a_grid, s_a = O.fp8_quantize_per_tensor(S.to_f64(a))
+    w_grid, s_w = O.fp8_quantize_per_tensor(S.to_f64(w))
+    assert float(sa.item()) == np.float32(s_a) and float(sw.item()) == np.float32(s_w)
+    from test_gpu_fp8 import e4m3_decode
+    np.testing.assert_array_equal(e4m3_decode(aq.cpu().numpy()), a_grid)
+    np.testing.assert_array_equal(e4m3_decode(wq[:2048].cpu().numpy()), w_grid[:2048])
+    rows = sample_rows(M, 10, 11)
+    ref = (a_grid[rows] @ w_grid.T) * (s_a * s_w)
+    assert_close(c[torch.as_tensor(rows, device=DEV)], ref, "fp8 QKV linear at 4680x15360x5120 (sampled rows)")
