@@ -180,8 +180,12 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     {
         prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
         LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false));
-        LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false));
-        LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true));
+        if (w8 == nullptr) {  // the context's K and V projections share one launch
+            LVX_TRY(lvx_launch_linear_pair(ctx, d, (const bf16_t *)w.Wc_k, (const bf16_t *)w.Wc_v, ldw, ctx_kv, ctx_kv + d, ldk, n_ctx, d, d, st));
+        } else {
+            LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false));
+            LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true));
+        }
     }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;

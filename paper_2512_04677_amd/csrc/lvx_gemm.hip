@@ -254,7 +254,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,
                         int M, int N, int K, const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n,
-                        int per_xcd) {
+                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int split_tn) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -278,7 +278,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     const int band_m = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
     const int in_band = widx - band * GROUP_M * tiles_n;
     const int tm = first_m + in_band % band_m;
-    const int tn = in_band / band_m;
+    int tn = in_band / band_m;
+    // two projections of the same activations in one launch (tiles_n counts both): column tiles past split_tn belong to the
+    // second weight matrix and its own output
+    if (tn >= split_tn) {
+        tn -= split_tn;
+        W = W2;
+        C = C2;
+    }
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -387,15 +394,16 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool DMA>
 lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, bf16_t *C, int64_t ldc, int M, int N, int K, int epi,
-                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream) {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const bf16_t *W2 = nullptr, bf16_t *C2 = nullptr) {
+    const int split_tn = W2 != nullptr ? (N + BN - 1) / BN : 0x7fffffff;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (W2 != nullptr ? 2 : 1) * ((N + BN - 1) / BN);
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
     if (DMA)                                                                                                                       \
         hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
-                           R, ldr, gate, tiles_m, tiles_n, per_xcd);                                                               \
+                           R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, split_tn);                                             \
     else                                                                                                                           \
         hipLaunchKernelGGL((lvx_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, R,  \
                            ldr, gate, tiles_m, tiles_n, per_xcd)
@@ -414,6 +422,18 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
 }
 
 }  // namespace
+
+// C1 = A W1^T and C2 = A W2^T (same shapes and strides) in one launch: two small-M projections of the same input fill the chip
+// together where each alone leaves most of it idle (the context's K and V projections: 100 tiles each on 256 CUs).
+lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
+                                    int64_t ldc, int M, int N, int K, hipStream_t stream) {
+    LVX_REQUIRE(A && W1 && W2 && C1 && C2, LVX_ERR_INVALID_ARG, "linear pair: NULL pointer");
+    LVX_REQUIRE(K % BK == 0 && N % 8 == 0 && lda >= K && ldw >= K && ldc >= N, LVX_ERR_SHAPE, "linear pair: bad shape");
+    LVX_REQUIRE((uint64_t)M * (uint64_t)lda * 2 < (1ull << 32) && (uint64_t)N * (uint64_t)ldw * 2 < (1ull << 32), LVX_ERR_SHAPE,
+                "operand larger than 4 GiB (32-bit byte offsets inside the kernel)");
+    if (M == 0) return LVX_OK;
+    return launch<128, 256, 2, 4, true>(A, lda, W1, ldw, C1, ldc, M, N, K, (int)LVX_EPI_STORE, nullptr, 0, nullptr, stream, W2, C2);
+}
 
 extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64_t ldw, void *dev_c, int64_t ldc, int32_t M,
                                    int32_t N, int32_t K, lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate,

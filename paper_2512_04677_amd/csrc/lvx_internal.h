@@ -101,6 +101,9 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// C1 = A W1^T, C2 = A W2^T in one launch (bf16, plain store).
+lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
+                                    int64_t ldc, int M, int N, int K, hipStream_t stream);
 // Per-tensor dynamic FP8 quantisation of a bf16 matrix (amax, then codes and the dequantisation scale); amax_bits: 16 bytes of
 // device scratch.
 lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_bits,
