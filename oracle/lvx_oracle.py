@@ -477,3 +477,52 @@ def full_sequence_stage(x_chunks, layers, sink_kv_per_layer, ctx_per_chunk, mod6
         h = h + g2 * ffn(u2, w, cfg)
     out = x_in + h * dt
     return [out[i * nc:(i + 1) * nc] for i in range(n_chunks)]
+
+
+# --------------------------------------------------------------------------------------------------
+# Streaming causal 3-D convolution with a two-frame feature cache (Appendix C, "Streaming VAE Feature Caching")
+# --------------------------------------------------------------------------------------------------
+def causal_conv3d(x, w, bias=None):
+    """Causal 3x3x3 convolution over a WHOLE frame sequence, channels last.
+
+    x [T, H, W, Cin], w [Cout, 3, 3, 3, Cin] (taps ordered time, row, column), bias [Cout] or None.
+    out[t, y, x, o] = bias[o] + sum_{dt,dy,dx,c} w[o, dt, dy, dx, c] * x[t + dt - 2, y + dy - 1, x + dx - 1, c],
+    with zeros outside the frame (spatial padding 1) and before the first frame (temporal padding 2 on the past side
+    only: frame t never sees a later frame).  Written as 27 shifted matrix products, nothing else."""
+    x = np.asarray(x, F64)
+    w = np.asarray(w, F64)
+    T, H, W, Cin = x.shape
+    Cout = w.shape[0]
+    xp = np.zeros((T + 2, H + 2, W + 2, Cin), F64)
+    xp[2:, 1:-1, 1:-1] = x
+    out = np.zeros((T, H, W, Cout), F64)
+    for dt in range(3):
+        for dy in range(3):
+            for dx in range(3):
+                out += xp[dt:dt + T, dy:dy + H, dx:dx + W] @ w[:, dt, dy, dx, :].T
+    if bias is not None:
+        out += np.asarray(bias, F64)
+    return out
+
+
+def silu(x):
+    x = np.asarray(x, F64)
+    return x / (1.0 + np.exp(-x))
+
+
+class CausalConvCache:
+    """Feature cache of one causal convolution layer: the two most recent INPUT frames (zeros before the first frame)."""
+
+    def __init__(self):
+        self.frames = None      # [2, H, W, Cin]
+
+    def step(self, x_chunk, w, bias=None):
+        """Decode the next frames given only the cache: prepend the two cached frames as causal context, convolve,
+        keep the outputs of the new frames, then retain the last two input frames for the next call."""
+        x = np.asarray(x_chunk, F64)
+        if self.frames is None:
+            self.frames = np.zeros((2,) + x.shape[1:], F64)
+        seq = np.concatenate([self.frames, x], axis=0)
+        out = causal_conv3d(seq, w, bias)[2:]
+        self.frames = seq[-2:]
+        return out

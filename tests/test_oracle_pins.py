@@ -595,3 +595,57 @@ def test_block_with_fp8_linears_is_a_small_perturbation_of_the_exact_block():
     O.dit_block(x, w, c, ctx, None, 0, 1, cfg8)
     qkv = O.linear_fp8(O.layernorm(x, cfg.eps), w["W_qkv"])
     np.testing.assert_array_equal(c.blocks[0][2].reshape(-1, d), qkv[:, 2 * d:])
+
+
+# ---------------------------------------------------------------- streaming causal convolution (Appendix C)
+def test_causal_conv3d_against_loops_and_the_library_convolution():
+    import torch
+    T, H, W, Ci, Co = 4, 3, 5, 2, 3
+    x = rng.standard_normal((T, H, W, Ci))
+    w = rng.standard_normal((Co, 3, 3, 3, Ci))
+    b = rng.standard_normal(Co)
+    got = O.causal_conv3d(x, w, b)
+    ref = np.zeros((T, H, W, Co))
+    for t in range(T):
+        for y in range(H):
+            for xx in range(W):
+                for o in range(Co):
+                    acc = b[o]
+                    for dt in range(3):
+                        for dy in range(3):
+                            for dx in range(3):
+                                tt, yy, xs = t + dt - 2, y + dy - 1, xx + dx - 1
+                                if tt < 0 or yy < 0 or yy >= H or xs < 0 or xs >= W:
+                                    continue
+                                for c in range(Ci):
+                                    acc += w[o, dt, dy, dx, c] * x[tt, yy, xs, c]
+                    ref[t, y, xx, o] = acc
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+    # library routine: conv3d (a cross-correlation) on the explicitly padded volume, channels first
+    xt = torch.from_numpy(x).permute(3, 0, 1, 2)[None]                       # [1, Ci, T, H, W]
+    xt = torch.nn.functional.pad(xt, (1, 1, 1, 1, 2, 0))                     # W, H by 1 each side; time by 2 in the past only
+    wt = torch.from_numpy(w).permute(0, 4, 1, 2, 3).contiguous()             # [Co, Ci, 3, 3, 3]
+    lib = torch.nn.functional.conv3d(xt, wt, torch.from_numpy(b))[0].permute(1, 2, 3, 0).numpy()
+    np.testing.assert_allclose(got, lib, rtol=1e-11, atol=1e-11)
+    # causality: a change in frame 2 leaves frames 0 and 1 of the output alone and changes frame 2
+    x2 = x.copy(); x2[2] += 1.0
+    got2 = O.causal_conv3d(x2, w, b)
+    np.testing.assert_array_equal(got2[:2], got[:2])
+    assert np.abs(got2[2] - got[2]).max() > 1e-3 and np.abs(got2[3] - got[3]).max() > 1e-3
+
+
+@pytest.mark.parametrize("chunks", [[1, 1, 1, 1, 1, 1, 1], [3, 3, 1], [2, 5], [7], [1, 4, 2]])
+def test_streaming_conv_with_two_frame_cache_equals_whole_sequence(chunks):
+    T, H, W, Ci, Co = sum(chunks), 4, 3, 3, 2
+    x = rng.standard_normal((T, H, W, Ci))
+    w = rng.standard_normal((Co, 3, 3, 3, Ci))
+    b = rng.standard_normal(Co)
+    whole = O.causal_conv3d(x, w, b)
+    cache = O.CausalConvCache()
+    outs, t = [], 0
+    for n in chunks:
+        outs.append(cache.step(x[t:t + n], w, b))
+        t += n
+        np.testing.assert_array_equal(cache.frames, np.concatenate([np.zeros((2, H, W, Ci)), x[:t]])[-2:])
+    np.testing.assert_allclose(np.concatenate(outs), whole, rtol=1e-12, atol=1e-12)
+    assert O.silu(0.0) == 0.0 and abs(O.silu(30.0) - 30.0) < 1e-11 and abs(O.silu(-1.0) + 1.0 / (1.0 + math.e)) < 1e-15
