@@ -192,7 +192,9 @@ typedef enum {
     LVX_EPI_STORE = 0,      /* C = A W^T */
     LVX_EPI_GELU_TANH = 1,  /* C = gelu_tanh(A W^T) */
     LVX_EPI_RESID_GATE = 2, /* C = R + gate[n] * (A W^T); gate NULL = 1; C may alias R */
-    LVX_EPI_RESID_GATE_F32 = 3 /* same, with C and R in fp32 (ldc, ldr in fp32 elements): the in-block residual stream */
+    LVX_EPI_RESID_GATE_F32 = 3, /* same, with C and R in fp32 (ldc, ldr in fp32 elements): the in-block residual stream */
+    LVX_EPI_BIAS = 4,       /* C = A W^T + bias[n]; the bias (fp32 [N], NULL = 0) is passed in the gate argument */
+    LVX_EPI_BIAS_SILU = 5   /* C = silu(A W^T + bias[n]) */
 } lvx_epilogue_t;
 
 /* C[M][N] = epilogue(A[M][K] * W[N][K]^T), bf16 in/out, fp32 accumulate on MFMA.  K % 64 == 0, N % 8 == 0. */
@@ -304,6 +306,33 @@ lvx_status_t lvx_sample_chunk(const lvx_stage_t *stage /* host */, lvx_kvcache_t
 lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage /* host */, lvx_kvcache_t *cache, const void *dev_x_sink, const void *dev_ctx,
                               int32_t n_ctx, const float *dev_mod6_per_layer, int32_t t_sink, void *dev_x_out,
                               void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Streaming causal convolution with a two-frame feature cache (Appendix C, "Streaming VAE Feature Caching": each causal
+ * convolution of the decoder keeps its two most recent input frames and prepends them as causal context for the next frames).
+ *   y[t, y, x, o] = act(bias[o] + sum_{dt,dy,dx,c} w[o][(dt*3+dy)*3+dx][c] * x[t+dt-2, y+dy-1, x+dx-1, c])
+ * zeros outside the frame and before the first frame of the sequence; frames arrive in order over any number of steps and the
+ * result equals the convolution of the whole sequence.  Channels last, bf16: x [n_frames][H][W][c_in], y [n_frames][H][W][c_out],
+ * w [c_out][27*c_in] with row stride ldw (taps time-major, then row, then column; channels innermost), bias fp32 [c_out] or
+ * NULL, act 0 = none, 1 = SiLU.  fp32 accumulation on the matrix cores.  c_in % 64 == 0, c_out % 8 == 0.
+ * The state (a zero-padded volume of max_frames + 2 frames, lvx_causal_conv_state_bytes) is caller-owned device memory,
+ * 256-byte aligned, alive as long as the handle; init zero-fills it (the sequence starts from a zero history), reset starts a
+ * new sequence.  Steps on one handle must be stream-ordered.
+ * ------------------------------------------------------------------------------------------------ */
+typedef struct {
+    int32_t c_in, c_out;
+    int32_t height, width; /* frame size at this layer */
+    int32_t max_frames;    /* most frames one step may carry */
+} lvx_conv_desc_t;
+typedef struct lvx_causal_conv lvx_causal_conv_t; /* opaque host-side handle */
+
+size_t lvx_causal_conv_state_bytes(const lvx_conv_desc_t *desc /* host */);
+lvx_status_t lvx_causal_conv_init(const lvx_conv_desc_t *desc /* host */, void *dev_state, size_t bytes, lvx_stream_t stream,
+                                  lvx_causal_conv_t **out /* host */);
+lvx_status_t lvx_causal_conv_destroy(lvx_causal_conv_t *conv);
+lvx_status_t lvx_causal_conv_reset(lvx_causal_conv_t *conv, lvx_stream_t stream);
+lvx_status_t lvx_causal_conv_step(lvx_causal_conv_t *conv, const void *dev_x, int32_t n_frames, const void *dev_w, int64_t ldw,
+                                  const float *dev_bias, int32_t act, void *dev_y, lvx_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Optional timing of the kernel classes inside lvx_dit_block / lvx_denoise_stage with HIP events recorded on the

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "liblvx.so")
 _lib = None
 
 LVX_MAX_SLOTS = 16
-EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE, EPI_RESID_GATE_F32 = 0, 1, 2, 3
+EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE, EPI_RESID_GATE_F32, EPI_BIAS, EPI_BIAS_SILU = 0, 1, 2, 3, 4, 5
 STATUS_NAMES = {0: "LVX_OK", 1: "LVX_ERR_INVALID_ARG", 2: "LVX_ERR_SHAPE", 3: "LVX_ERR_STATE", 4: "LVX_ERR_UNSUPPORTED",
                 5: "LVX_ERR_HIP"}
 
@@ -46,6 +46,10 @@ class RopeDesc(C.Structure):
 class BlockWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("W_qkv", "W_o", "Wc_q", "Wc_k", "Wc_v", "Wc_o", "W_1", "W_2",
                                           "g_q", "g_k", "gc_q", "gc_k")]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [("c_in", C.c_int32), ("c_out", C.c_int32), ("height", C.c_int32), ("width", C.c_int32), ("max_frames", C.c_int32)]
 
 
 class BlockWeightsFp8(C.Structure):
@@ -94,6 +98,11 @@ SIGNATURES = {
     "lvx_sink_prefill": (C.c_int, [C.POINTER(Stage), _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "lvx_sample_chunk": (C.c_int, [C.POINTER(Stage), C.POINTER(_vp), _i32, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _i32, _vp, _sz,
                                    _vp]),
+    "lvx_causal_conv_state_bytes": (_sz, [C.POINTER(ConvDesc)]),
+    "lvx_causal_conv_init": (C.c_int, [C.POINTER(ConvDesc), _vp, _sz, _vp, C.POINTER(_vp)]),
+    "lvx_causal_conv_destroy": (C.c_int, [_vp]),
+    "lvx_causal_conv_reset": (C.c_int, [_vp, _vp]),
+    "lvx_causal_conv_step": (C.c_int, [_vp, _vp, _i32, _vp, _i64, _vp, _i32, _vp, _vp]),
     "lvx_profile_set": (C.c_int, [_i32]),
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
@@ -343,6 +352,39 @@ def lvx_sample_chunk(stage, caches, x, ctx, mod6_per_step_layer, dt, chunk_index
     _check(load().lvx_sample_chunk(C.byref(stage.c), handles, len(caches), _ptr(x), x.shape[0], _ptr(ctx), ctx.shape[0],
                                    _ptr(mod6_per_step_layer), dt, chunk_index, t0, t_sink, _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream()))
+
+
+class CausalConv:
+    """One causal convolution layer's streaming state (padded volume with the two-frame feature cache) and its handle."""
+
+    def __init__(self, c_in, c_out, height, width, max_frames, device="cuda:0"):
+        import torch
+        self.desc = ConvDesc(c_in, c_out, height, width, max_frames)
+        nbytes = load().lvx_causal_conv_state_bytes(C.byref(self.desc))
+        if nbytes == 0:
+            raise LvxError(2, load().lvx_last_error().decode())
+        self.state = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        h = C.c_void_p()
+        _check(load().lvx_causal_conv_init(C.byref(self.desc), _ptr(self.state), nbytes, _stream(), C.byref(h)))
+        self.handle = h
+
+    def step(self, x, w, bias, act, y):
+        """x [n_frames][H][W][c_in], w [c_out][27*c_in] (row stride w.stride(0)), y [n_frames][H][W][c_out]."""
+        _check(load().lvx_causal_conv_step(self.handle, _ptr(x), x.shape[0], _ptr(w), w.stride(0), _ptr(bias), int(act), _ptr(y), _stream()))
+
+    def reset(self):
+        _check(load().lvx_causal_conv_reset(self.handle, _stream()))
+
+    def close(self):
+        if self.handle is not None:
+            load().lvx_causal_conv_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def lvx_profile_set(level):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblvx.so")
-SOURCES = ["lvx_cache.hip", "lvx_rope_norm.hip", "lvx_attention.hip", "lvx_gemm.hip", "lvx_fp8.hip", "lvx_block.hip"]
+SOURCES = ["lvx_cache.hip", "lvx_rope_norm.hip", "lvx_attention.hip", "lvx_gemm.hip", "lvx_fp8.hip", "lvx_conv.hip", "lvx_block.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -33,6 +33,7 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_
         if (!interior && n >= N) continue;
         float gt = 1.f;
         if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
+        if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) gt = gate != nullptr ? gate[n] : 0.f;  // the bias of column n
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const size_t row0 = (size_t)(m0 + i * 32);
@@ -46,6 +47,8 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_
                 if (!interior && m0 + i * 32 + dm >= M) continue;
                 float v = acc[i][j][e];
                 if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
+                if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) v += gt;
+                if (EPI == LVX_EPI_BIAS_SILU) v = v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * v));
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
                     cpf[(size_t)dm * ldc] = rpf[(size_t)dm * ldr] + gt * v;
@@ -250,11 +253,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 // c ^ ((r >> 1) & 7): 16 consecutive rows then cover 16 distinct 16-byte units of the 256-byte bank row.
 // The loads are issued through inline asm with explicit s_waitcnt vmcnt(n): the compiler would otherwise wait for ALL
 // outstanding DMA before any LDS read that might alias, which would undo the multi-stage pipeline.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool CONV>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,
                         int M, int N, int K, const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n,
-                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int split_tn) {
+                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int split_tn, lvx_conv_map_t cm) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -301,7 +304,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
         if (q < A_Q) {
             int r = tm * BM + row_s;
             if (r > M - 1) r = M - 1;
-            doff[q] = (uint32_t)(((size_t)r * lda + chunk * 8) * sizeof(bf16_t));
+            size_t e = (size_t)r * lda;
+            if (CONV) {  // output pixel r = (t, y, x) -> its position in the padded volume (tap (0,0,0))
+                const int hw = cm.H * cm.W;
+                const int t = r / hw, rem = r - t * hw;
+                const int y = rem / cm.W, x = rem - y * cm.W;
+                e = (size_t)t * cm.frame_pitch + (size_t)y * cm.row_pitch + (size_t)x * cm.C;
+            }
+            doff[q] = (uint32_t)((e + chunk * 8) * sizeof(bf16_t));
         } else {
             int r = tn * BN + (row_s - BM);
             if (r > N - 1) r = N - 1;
@@ -310,9 +320,17 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
     const uint32_t lds_wave = __builtin_amdgcn_readfirstlane(lds_base + wave * 1024);
+    // byte offset of K slab kt in the A operand: plain GEMM kt * 128; convolution: the tap's shift in the padded volume plus
+    // the slab's channel offset inside the tap (wave-uniform scalar arithmetic)
+    auto a_slab = [&](int kt) -> size_t {
+        if (!CONV) return (size_t)kt * ROW_B;
+        const int tap = kt / cm.slabs_per_tap, kc = kt - tap * cm.slabs_per_tap;
+        const int dt = tap / 9, dy = (tap - dt * 9) / 3, dx = tap - dt * 9 - dy * 3;
+        return ((size_t)dt * cm.frame_pitch + (size_t)dy * cm.row_pitch + (size_t)dx * cm.C) * sizeof(bf16_t) + (size_t)kc * ROW_B;
+    };
 #define LVX_DMA_ISSUE(stage_, kt_, q_)                                                                                      \
-    lvx_dma16(reinterpret_cast<const char *>((q_) < A_Q ? A : W) + (size_t)(kt_) * ROW_B, doff[q_],                         \
-              lds_wave + (uint32_t)((stage_) * STAGE_B + (q_) * NW * 1024))
+    lvx_dma16((q_) < A_Q ? reinterpret_cast<const char *>(A) + a_off_ : reinterpret_cast<const char *>(W) + (size_t)(kt_) * ROW_B, \
+              doff[q_], lds_wave + (uint32_t)((stage_) * STAGE_B + (q_) * NW * 1024))
 
     // fragment reads: lane (l32, hh) reads row l32 of a 32-row block, k-chunk 2*kk + hh at its swizzled position
     const int swz = (l32 >> 1) & 7;
@@ -339,10 +357,16 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 
     const int n_k = K / BK;
     const int last = n_k - 1;
+    {
+        const size_t a_off_ = a_slab(0);
 #pragma unroll
-    for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(0, 0, q);
+        for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(0, 0, q);
+    }
+    {
+        const size_t a_off_ = a_slab(last < 1 ? last : 1);
 #pragma unroll
-    for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(1, (last < 1 ? last : 1), q);
+        for (int q = 0; q < QPW; ++q) LVX_DMA_ISSUE(1, (last < 1 ? last : 1), q);
+    }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QPW) : "memory");
     __syncthreads();
     LVX_DMA_READ_FRAGS(0, 0);
@@ -353,6 +377,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     int cur = 0, nxt = 1, nx2 = 2;
     for (int t = 0; t < n_k; ++t) {
         const int kt_load = t + 2 < last ? t + 2 : last;
+        const size_t a_off_ = a_slab(kt_load);
         LVX_DMA_READ_FRAGS(cur, 1);
         __builtin_amdgcn_sched_barrier(0);
         LVX_DMA_MFMAS(0);
@@ -392,9 +417,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_epilogue<FM, FN, EPI>(acc, C, ldc, R, ldr, gate, M, N, tm * BM + wm * WTM + 4 * hh, tn * BN + wn * WTN + l32);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool DMA>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool DMA, bool CONV = false>
 lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, bf16_t *C, int64_t ldc, int M, int N, int K, int epi,
-                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const bf16_t *W2 = nullptr, bf16_t *C2 = nullptr) {
+                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const bf16_t *W2 = nullptr, bf16_t *C2 = nullptr,
+                    const lvx_conv_map_t *conv = nullptr) {
+    lvx_conv_map_t cm = {};
+    if (conv != nullptr) cm = *conv;
     const int split_tn = W2 != nullptr ? (N + BN - 1) / BN : 0x7fffffff;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (W2 != nullptr ? 2 : 1) * ((N + BN - 1) / BN);
     const int total = tiles_m * tiles_n;
@@ -402,8 +430,8 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
     if (DMA)                                                                                                                       \
-        hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
-                           R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, split_tn);                                             \
+        hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_, CONV>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
+                           R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, split_tn, cm);                                         \
     else                                                                                                                           \
         hipLaunchKernelGGL((lvx_gemm_kernel<BM, BN, WAVES_M, WAVES_N, EPI_>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, R,  \
                            ldr, gate, tiles_m, tiles_n, per_xcd)
@@ -413,8 +441,12 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
         LVX_GEMM_LAUNCH(LVX_EPI_GELU_TANH);
     } else if (epi == LVX_EPI_RESID_GATE) {
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE);
-    } else {
+    } else if (epi == LVX_EPI_RESID_GATE_F32) {
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE_F32);
+    } else if (epi == LVX_EPI_BIAS) {
+        LVX_GEMM_LAUNCH(LVX_EPI_BIAS);
+    } else {
+        LVX_GEMM_LAUNCH(LVX_EPI_BIAS_SILU);
     }
 #undef LVX_GEMM_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
@@ -435,6 +467,15 @@ lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *
     return launch<128, 256, 2, 4, true>(A, lda, W1, ldw, C1, ldc, M, N, K, (int)LVX_EPI_STORE, nullptr, 0, nullptr, stream, W2, C2);
 }
 
+// Implicit-GEMM 3x3x3 convolution: rows = output pixels, K = 27 taps x C channels gathered from the padded volume P.
+// 256 x 128 tiles (C_out is 128 ... 512 in the decoder this serves; 128-wide column tiles waste nothing there).
+lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, const bf16_t *Wt, int64_t ldw, const float *bias, int act,
+                                  bf16_t *Y, int64_t ldy, int M, int N, hipStream_t stream) {
+    const int K = 27 * cm.C;
+    return launch<256, 128, 4, 2, true, true>(P, 0, Wt, ldw, Y, ldy, M, N, K, act ? (int)LVX_EPI_BIAS_SILU : (int)LVX_EPI_BIAS, nullptr, 0, bias, stream,
+                                        nullptr, nullptr, &cm);
+}
+
 extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64_t ldw, void *dev_c, int64_t ldc, int32_t M,
                                    int32_t N, int32_t K, lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate,
                                    lvx_stream_t stream) {
@@ -447,8 +488,7 @@ extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *d
     LVX_REQUIRE(lda >= K && lda % 8 == 0 && ldw >= K && ldw % 8 == 0 && ldc >= N, LVX_ERR_SHAPE, "bad leading dimension");
     LVX_REQUIRE((uint64_t)M * (uint64_t)lda * 2 < (1ull << 32) && (uint64_t)N * (uint64_t)ldw * 2 < (1ull << 32), LVX_ERR_SHAPE,
                 "operand larger than 4 GiB (32-bit byte offsets inside the kernel)");
-    LVX_REQUIRE(epi == LVX_EPI_STORE || epi == LVX_EPI_GELU_TANH || epi == LVX_EPI_RESID_GATE || epi == LVX_EPI_RESID_GATE_F32,
-                LVX_ERR_INVALID_ARG, "unknown epilogue %d", (int)epi);
+    LVX_REQUIRE((int)epi >= (int)LVX_EPI_STORE && (int)epi <= (int)LVX_EPI_BIAS_SILU, LVX_ERR_INVALID_ARG, "unknown epilogue %d", (int)epi);
     if (epi == LVX_EPI_RESID_GATE || epi == LVX_EPI_RESID_GATE_F32) {
         LVX_REQUIRE(dev_resid != nullptr, LVX_ERR_INVALID_ARG, "residual epilogue needs a residual pointer");
         LVX_REQUIRE(ldr >= N, LVX_ERR_SHAPE, "bad residual leading dimension");

@@ -101,6 +101,18 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// Row addressing of the GEMM's A operand for an implicit-GEMM 3x3x3 convolution over a zero-padded channels-last volume
+// P[frame][H+2][W+2][C]: output pixel m = (t, y, x) reads, for tap (dt, dy, dx), the C channels at P[t+dt][y+dy][x+dx].
+// K runs tap-major (27 taps x C channels); C % 64 == 0 so that a 64-wide K slab lies inside one tap.
+struct lvx_conv_map_t {
+    int32_t enabled;
+    int32_t H, W, C;           // output frame size and input channels
+    int32_t slabs_per_tap;     // C / 64
+    int32_t row_pitch;         // elements between padded rows: (W + 2) * C
+    int32_t frame_pitch;       // elements between padded frames: (H + 2) * (W + 2) * C
+};
+lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, const bf16_t *Wt, int64_t ldw, const float *bias, int act,
+                                  bf16_t *Y, int64_t ldy, int M, int N, hipStream_t stream);
 // C1 = A W1^T, C2 = A W2^T in one launch (bf16, plain store).
 lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
                                     int64_t ldc, int M, int N, int K, hipStream_t stream);

@@ -174,3 +174,19 @@ def test_fp8_entry_points_host_checks():
     assert lib.lvx_workspace_bytes(C.byref(ok), 4680, 544) >= lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) + 4680 * 13824
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824 + 64, 0, 0, r, castb, cast8, 0, 0)), 4680, 544) == 0
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 8, 0)), 4680, 544) == 0
+
+
+def test_causal_conv_host_checks():
+    lib = lvx.load()
+    d = lvx.ConvDesc(384, 384, 100, 180, 4)
+    assert lib.lvx_causal_conv_state_bytes(C.byref(d)) == 6 * 102 * 182 * 384 * 2
+    assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(96, 96, 100, 180, 4))) == 0          # c_in % 64
+    assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(384, 380, 100, 180, 4))) == 0        # c_out % 8
+    assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(384, 384, 400, 720, 16))) == 0       # volume beyond 4 GiB
+    h = C.c_void_p()
+    need = lib.lvx_causal_conv_state_bytes(C.byref(d))
+    assert lib.lvx_causal_conv_init(C.byref(d), None, need, None, C.byref(h)) == 1
+    assert lib.lvx_causal_conv_init(C.byref(d), C.c_void_p(4096), need - 1, None, C.byref(h)) == 2
+    assert lib.lvx_causal_conv_init(C.byref(d), C.c_void_p(4096 + 16), need, None, C.byref(h)) == 1
+    assert lib.lvx_causal_conv_step(None, C.c_void_p(4096), 1, C.c_void_p(4096), 27 * 384, None, 0, C.c_void_p(4096), None) == 1
+    assert lib.lvx_causal_conv_reset(None, None) == 1 and lib.lvx_causal_conv_destroy(None) == 1
