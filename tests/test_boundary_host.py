@@ -182,7 +182,7 @@ def test_causal_conv_host_checks():
     assert lib.lvx_causal_conv_state_bytes(C.byref(d)) == 6 * 102 * 182 * 384 * 2
     assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(96, 96, 100, 180, 4))) == 0          # c_in % 64
     assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(384, 380, 100, 180, 4))) == 0        # c_out % 8
-    assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(384, 384, 400, 720, 16))) == 0       # volume beyond 4 GiB
+    assert lib.lvx_causal_conv_state_bytes(C.byref(lvx.ConvDesc(384, 384, 400, 720, 20))) == 0       # volume beyond 4 GiB
     h = C.c_void_p()
     need = lib.lvx_causal_conv_state_bytes(C.byref(d))
     assert lib.lvx_causal_conv_init(C.byref(d), None, need, None, C.byref(h)) == 1
