@@ -245,7 +245,24 @@ __global__ void __launch_bounds__(64 * NWAVES)
 
     // Each group runs its own straight-line loop; both execute the same number of barriers (2 per iteration) and the same
     // DMA issue / wait sequence (issue in the first half, wait in the second half of every iteration).
-    if (grp == 0) {
+    // A wave whose 32 queries all lie past n_q (ragged last query tile: 4680 = 18 x 256 + 72) only keeps up the DMA and
+    // barrier protocol: no LDS reads, no MFMAs, no softmax.  Its SIMD partner then has the matrix core to itself, so such a
+    // workgroup finishes early and frees its CU, and the padding costs no energy on a chip that is power-limited.
+    const bool active = __builtin_amdgcn_readfirstlane(qtile * QT + wave * 32) < n_q;
+    if (!active) {
+        __syncthreads();
+        LVX_ATTN_STAGE_DMA(2);
+        LVX_ATTN_WAIT_DMA(4 * DPW);
+        __syncthreads();
+        for (int i = 1; i < n_tiles; ++i) {
+            LVX_ATTN_STAGE_DMA(i + 2);
+            __syncthreads();
+            LVX_ATTN_WAIT_DMA(4 * DPW);
+            __syncthreads();
+        }
+        __syncthreads();
+        __syncthreads();
+    } else if (grp == 0) {
         LVX_ATTN_S0();
         __syncthreads();
         LVX_ATTN_Y(0);
