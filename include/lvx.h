@@ -162,6 +162,8 @@ lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc /* host */, const void *dev_
  *   lvx_sink_rope_update            Phi: sink keys of `layer` (-1: every layer) := RoPE(source) with the sink's first frame
  *                                   at temporal index t_sink, spatial indices from the frame grid; values untouched.
  *   lvx_kvcache_get_sink_index      last t_sink applied to `layer`; -1 = reset but not rotated; -2 = static sink / none
+ *   lvx_kvcache_set_sink_index      restores that bookkeeping after the caller restored the device storage (resume, as
+ *                                   lvx_kvcache_set_state does for the ring)
  *   lvx_kvcache_gather_sink_source  reads the stored source back, token-major [sink_keys][ld] (bit-exact)
  * Errors: STATE without attached storage, on a layer whose sink came from lvx_kvcache_set_sink (already rotated, no
  * source) or on a cache without sink segment; SHAPE if the rope descriptor disagrees with the cache; INVALID_ARG else.
@@ -173,6 +175,7 @@ lvx_status_t lvx_kvcache_reset_sink(lvx_kvcache_t *cache, int32_t layer, const v
 lvx_status_t lvx_sink_rope_update(lvx_kvcache_t *cache, const lvx_rope_desc_t *rope /* host */, int32_t layer, int32_t t_sink,
                                   lvx_stream_t stream);
 lvx_status_t lvx_kvcache_get_sink_index(const lvx_kvcache_t *cache, int32_t layer, int32_t *out /* host */);
+lvx_status_t lvx_kvcache_set_sink_index(lvx_kvcache_t *cache, int32_t layer, int32_t t_sink);
 lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *cache, int32_t layer, void *dev_k_src_out, int64_t ld,
                                             lvx_stream_t stream);
 

@@ -94,6 +94,7 @@ SIGNATURES = {
     "lvx_kvcache_reset_sink": (C.c_int, [_vp, _i32, _vp, _vp, _i64, _vp]),
     "lvx_sink_rope_update": (C.c_int, [_vp, C.POINTER(RopeDesc), _i32, _i32, _vp]),
     "lvx_kvcache_get_sink_index": (C.c_int, [_vp, _i32, C.POINTER(C.c_int32)]),
+    "lvx_kvcache_set_sink_index": (C.c_int, [_vp, _i32, _i32]),
     "lvx_kvcache_gather_sink_source": (C.c_int, [_vp, _i32, _vp, _i64, _vp]),
     "lvx_sink_prefill": (C.c_int, [C.POINTER(Stage), _vp, _vp, _vp, _i32, _vp, _i32, _vp, _vp, _sz, _vp]),
     "lvx_sample_chunk": (C.c_int, [C.POINTER(Stage), C.POINTER(_vp), _i32, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _i32, _vp, _sz,
@@ -212,6 +213,10 @@ def lvx_kvcache_get_sink_index(cache, layer):
     out = C.c_int32()
     _check(load().lvx_kvcache_get_sink_index(cache.handle, layer, C.byref(out)))
     return out.value
+
+
+def lvx_kvcache_set_sink_index(cache, layer, t_sink):
+    _check(load().lvx_kvcache_set_sink_index(cache.handle, layer, t_sink))
 
 
 def lvx_kvcache_gather_sink_source(cache, layer, k_src_out):

@@ -395,6 +395,15 @@ extern "C" lvx_status_t lvx_kvcache_get_sink_index(const lvx_kvcache_t *c, int32
     return LVX_OK;
 }
 
+extern "C" lvx_status_t lvx_kvcache_set_sink_index(lvx_kvcache_t *c, int32_t layer, int32_t t_sink) {
+    LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
+    LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
+    LVX_REQUIRE(t_sink >= LVX_SINK_STATIC, LVX_ERR_INVALID_ARG, "t_sink %d: -2 (static), -1 (stale) or a temporal index", t_sink);
+    LVX_REQUIRE(t_sink == LVX_SINK_STATIC || c->sink_src != nullptr, LVX_ERR_STATE, "no sink source storage attached");
+    c->sink_t[layer] = t_sink;
+    return LVX_OK;
+}
+
 extern "C" lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *c, int32_t layer, void *dev_k_src_out, int64_t ld,
                                                        lvx_stream_t stream) {
     LVX_REQUIRE(c != nullptr && dev_k_src_out != nullptr, LVX_ERR_INVALID_ARG, "cache handle or output is NULL");

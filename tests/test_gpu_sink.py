@@ -85,6 +85,13 @@ def test_reset_sink_and_rolling_update(lvx, preset):
         vv = np.concatenate([model.sink[1], model.blocks[0][2]], 0)
         ref = O.attention(S.to_f64(q).reshape(chunk_n, H, D), kk, vv, 1 / math.sqrt(D)).reshape(chunk_n, d)
         assert_close(out, ref, "%s attention with rolled sink t=%d" % (preset, t_sink))
+    # bookkeeping round trip (resume): the index can be restored, a stale mark makes attention refuse again
+    lvx.lvx_kvcache_set_sink_index(cache, 1, -1)
+    with pytest.raises(lvx.LvxError):
+        lvx.lvx_chunk_attention(cache, 1, q, 1 / math.sqrt(D), out)
+    lvx.lvx_kvcache_set_sink_index(cache, 1, 5)
+    assert lvx.lvx_kvcache_get_sink_index(cache, 1) == 5
+    lvx.lvx_chunk_attention(cache, 1, q, 1 / math.sqrt(D), out)
     # layer 0 was never given a sink source
     with pytest.raises(lvx.LvxError):
         lvx.lvx_sink_rope_update(cache, rope, -1, 1)
