@@ -209,12 +209,12 @@ lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64
  *   lvx_fp8_quantize: x bf16 [rows][ld] -> q [rows][ldq] E4M3 codes (OCP form: bias 7, largest finite value 448) and one fp32
  *     dequantisation scale = amax/448 (1 for an all-zero tensor), amax = max|x| over the whole matrix:
  *     code = E4M3(x * (448/amax)), nearest-even, saturating; scale factors and that product are formed in fp32.
- *     dev_scratch16: 16 bytes of device scratch (16-byte aligned).  cols % 16 == 0, ldq % 16 == 0.  Used for weights (once)
- *     and activations (every call) alike.
+ *     dev_scratch256: 256 bytes of device scratch (16-byte aligned).  cols % 16 == 0, ldq % 16 == 0.  Used for weights
+ *     (once) and activations (every call) alike.
  *   lvx_linear_fp8: C[M][N] = epilogue(scale_a * scale_w * (Aq[M][K] . Wq[N][K]^T)), fp32 accumulate on the FP8 matrix
  *     cores, C / R / gate and the epilogues as in lvx_linear.  K % 128 == 0, N % 8 == 0, lda and ldw in bytes, % 16 == 0. */
 lvx_status_t lvx_fp8_quantize(const void *dev_x, int64_t ld, int32_t rows, int32_t cols, void *dev_q, int64_t ldq,
-                              void *dev_scratch16, float *dev_scale, lvx_stream_t stream);
+                              void *dev_scratch256, float *dev_scale, lvx_stream_t stream);
 lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
                             const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K,
                             lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate, lvx_stream_t stream);

@@ -270,7 +270,7 @@ def lvx_fp8_quantize(x, q=None, row_pad=0):
     rows, cols = x.shape
     if q is None:
         q = torch.empty((rows, cols + row_pad), dtype=torch.uint8, device=x.device)[:, :cols]
-    scratch = torch.empty(16, dtype=torch.uint8, device=x.device)
+    scratch = torch.empty(256, dtype=torch.uint8, device=x.device)
     scale = torch.empty(1, dtype=torch.float32, device=x.device)
     _check(load().lvx_fp8_quantize(_ptr(x), x.stride(0), rows, cols, _ptr(q), q.stride(0), _ptr(scratch), _ptr(scale), _stream()))
     return q, scale

@@ -29,7 +29,7 @@ template <int D, int NWAVES>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
-                         int64_t ld_out, int n_qtiles, int total_wg, int per_xcd) {
+                         int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots) {
     constexpr int QT = 32 * NWAVES;
     constexpr int MK = D / 16;  // MFMA k-steps over head_dim
     constexpr int DB = D / 32;  // 32-row blocks of O^T
@@ -300,6 +300,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.0f / l_tot;
     const int row = qtile * QT + wave * 32 + l32;
+    uint32_t amax_b = 0;  // largest magnitude among the bf16 values this lane stores (bit pattern without sign)
     if (row < n_q) {
         bf16_t *op = out + (size_t)row * ld_out + (size_t)head * D;
         // accumulator register 4g+r of block db holds O^T[d = 32db + 8g + 4hh + r][query l32]
@@ -311,20 +312,36 @@ __global__ void __launch_bounds__(64 * NWAVES)
                 w.x = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
                 w.y = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
                 *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hh) = w;
+                if (amax_slots != nullptr) {
+                    const uint32_t a0 = w.x & 0x7fffu, a1 = (w.x >> 16) & 0x7fffu, a2 = w.y & 0x7fffu, a3 = (w.y >> 16) & 0x7fffu;
+                    uint32_t m = a0 > a1 ? a0 : a1;
+                    m = m > a2 ? m : a2;
+                    m = m > a3 ? m : a3;
+                    amax_b = amax_b > m ? amax_b : m;
+                }
             }
+    }
+    // the output feeds an FP8 linear: hand its amax to that linear's quantisation (one atomic per wave)
+    if (amax_slots != nullptr) {
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const uint32_t o2 = (uint32_t)__shfl_xor((int)amax_b, s);
+            amax_b = amax_b > o2 ? amax_b : o2;
+        }
+        if (lane == 0 && amax_b != 0) atomicMax(amax_slots + ((widx * NWAVES + wave) & (LVX_AMAX_SLOTS - 1)), amax_b << 16);
     }
 }
 
 template <int D, int NWAVES>
 lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
-                    float scale, bf16_t *out, int64_t ld_out, hipStream_t stream) {
+                    float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots) {
     constexpr int QT = 32 * NWAVES;
     const int n_qtiles = (n_q + QT - 1) / QT;
     const int total = n_qtiles * H;
     const int per_xcd = (total + 7) / 8;
     const float c = scale * 1.4426950408889634f;
     hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
-                       n_keys, c, out, ld_out, n_qtiles, total, per_xcd);
+                       n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
@@ -333,12 +350,12 @@ lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t 
 
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, uint32_t *amax_slots) {
     LVX_REQUIRE(n_q > 0 && n_keys > 0 && n_keys <= cap && cap % KT == 0, LVX_ERR_SHAPE, "attention: n_q %d, n_keys %d, cap %d", n_q,
                 n_keys, cap);
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
-    if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream);
-    if (D == 64) return launch<64, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream);
+    if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+    if (D == 64) return launch<64, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
 }
 

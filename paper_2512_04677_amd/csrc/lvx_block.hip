@@ -78,7 +78,7 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     if (s->blocks_fp8 != nullptr) {  // quantised input activation of the running linear, quantised context, amax scratch + scales
         w.q8 = off;       off += round256((size_t)n_tokens * w.ld_q8);
         w.q8_ctx = off;   off += round256((size_t)n_ctx * w.ld_q8c);
-        w.q8_misc = off;  off += 256;
+        w.q8_misc = off;  off += 1024;  // two amax slot arrays (2 x 256 bytes), activation and context scales
     }
     w.total = off;
     return w;
@@ -118,8 +118,10 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
 // sink_prefill = true : the sink frame's forward (Appendix D, warm-up of the adaptive attention sink): the n = sink_keys rows
 //   install the layer's un-rotated sink keys and its values, the sink keys are rotated to temporal index t0, and the rows
 //   attend to the sink segment only; the ring is not touched.
+// amax_cur (FP8 stages): which of the two amax slot arrays the next producer writes and the next quantisation reads; both arrays
+//   are zero when the entry point starts (fp8_begin), every quantisation clears the other one.
 lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
-                       const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st,
+                       const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st, int *amax_cur,
                        bool sink_prefill = false) {
     const lvx_block_weights_t &w = s->blocks[layer];
     const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
@@ -140,10 +142,15 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     // which: index into the FP8 weight pointers / scales (0 W_qkv .. 7 W_2); reuse_ctx: the context was already quantised.
     const lvx_block_weights_fp8_t *w8 = s->blocks_fp8 ? &s->blocks_fp8[layer] : nullptr;
     const int64_t ldw8 = s->ldw8_d > 0 ? s->ldw8_d : d, ldw8_2 = s->ldw8_ffn > 0 ? s->ldw8_ffn : f;
-    uint32_t *amax_scratch = (uint32_t *)(ws + L.q8_misc);
-    float *scale_act = (float *)(ws + L.q8_misc + 16), *scale_ctx = (float *)(ws + L.q8_misc + 32);
+    uint32_t *slots = (uint32_t *)(ws + L.q8_misc);
+    float *scale_act = (float *)(ws + L.q8_misc + 512), *scale_ctx = (float *)(ws + L.q8_misc + 528);
+    // where the kernel that produces the next linear's input leaves that tensor's amax (NULL in a bf16 stage)
+    auto amax_out = [&]() -> uint32_t * { return w8 ? slots + LVX_AMAX_SLOTS * (*amax_cur) : nullptr; };
+    // amax_ready: the producer of A already left A's amax in the current slot array (else a separate pass collects it);
+    // feeds_fp8: this linear's own output is the next linear's input, its epilogue collects that amax
     auto linear = [&](const bf16_t *A, int64_t lda, const void *Wbf, int which, void *C, int64_t ldc_, int M, int N, int K, lvx_epilogue_t epi,
-                      const void *R, int64_t ldr, const float *gate, bool is_ctx, bool reuse_ctx) -> lvx_status_t {
+                      const void *R, int64_t ldr, const float *gate, bool is_ctx, bool reuse_ctx, bool amax_ready,
+                      bool feeds_fp8) -> lvx_status_t {
         if (w8 == nullptr) return lvx_linear(A, lda, Wbf, K == f ? ldw2 : ldw, C, ldc_, M, N, K, epi, R, ldr, gate, st);
         const void *const w8p[8] = {w8->W_qkv, w8->W_o, w8->Wc_q, w8->Wc_k, w8->Wc_v, w8->Wc_o, w8->W_1, w8->W_2};
         uint8_t *aq = (uint8_t *)(ws + (is_ctx ? L.q8_ctx : L.q8));
@@ -151,18 +158,28 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         float *sa = is_ctx ? scale_ctx : scale_act;
         if (!reuse_ctx) {
             prof_scope_t ps(LVX_PROF_FP8_QUANT, st);
-            LVX_TRY(lvx_launch_fp8_quantize(A, lda, M, K, aq, ldaq, amax_scratch, sa, st));
+            uint32_t *cur = slots + LVX_AMAX_SLOTS * (*amax_cur), *other = slots + LVX_AMAX_SLOTS * (1 - *amax_cur);
+            if (!amax_ready) LVX_TRY(lvx_launch_fp8_amax(A, lda, M, K, cur, st));
+            LVX_TRY(lvx_launch_fp8_quant(A, lda, M, K, aq, ldaq, cur, other, sa, st));
+            *amax_cur ^= 1;
         }
-        return lvx_linear_fp8(aq, ldaq, sa, w8p[which], K == f ? ldw8_2 : ldw8, w8->scales + which, C, ldc_, M, N, K, epi, R, ldr, gate, st);
+        return lvx_launch_linear_fp8(aq, ldaq, sa, w8p[which], K == f ? ldw8_2 : ldw8, w8->scales + which, C, ldc_, M, N, K, epi, R, ldr, gate,
+                                     feeds_fp8 ? amax_out() : nullptr, st);
     };
 
     // self-attention branch
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false)); }
     if (!sink_prefill) {
         { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
         { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
-        { prof_scope_t ps(LVX_PROF_ATTN_SELF, st); LVX_TRY(lvx_chunk_attention(c, layer, big, ldq, n, scale, u, ldu, st)); }
+        LVX_REQUIRE(c->sink_t[layer] != LVX_SINK_STALE, LVX_ERR_STATE,
+                    "layer %d: the sink was reset and its keys are not rotated yet (lvx_sink_rope_update)", layer);
+        {
+            prof_scope_t ps(LVX_PROF_ATTN_SELF, st);
+            LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->state[layer].key_count,
+                                         scale, u, ldu, st, amax_out()));
+        }
     } else {
         lvx_rope_desc_t k_norm_only = s->rope;
         k_norm_only.apply_rope = 0;
@@ -171,20 +188,20 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         LVX_TRY(lvx_kvcache_reset_sink(c, layer, big + d, big + 2 * d, ldq, st));
         LVX_TRY(lvx_sink_rope_update(c, &s->rope, layer, t0, st));
         LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->sink_keys, scale, u,
-                                     ldu, st));
+                                     ldu, st, amax_out()));
     }
-    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(linear(u, ldu, w.W_o, 1, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, false, false)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(linear(u, ldu, w.W_o, 1, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, false, false, true, false)); }
 
     // cross-attention to the audio + text context
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st)); }
     {
         prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
-        LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false));
+        LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
         if (w8 == nullptr) {  // the context's K and V projections share one launch
             LVX_TRY(lvx_launch_linear_pair(ctx, d, (const bf16_t *)w.Wc_k, (const bf16_t *)w.Wc_v, ldw, ctx_kv, ctx_kv + d, ldk, n_ctx, d, d, st));
         } else {
-            LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false));
-            LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true));
+            LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false, false, false));
+            LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true, false, false));
         }
     }
     lvx_rope_desc_t norm_only = s->rope;
@@ -196,14 +213,20 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         LVX_TRY(lvx_launch_fill_zero(pack_v, (size_t)L.cap_ctx * d * 2, st));
     }
     LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
-    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false)); }
+    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st, amax_out())); }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false, true, false)); }
 
     // feed-forward
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(linear(u, ldu, w.W_1, 6, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, false, false)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(linear(big, ldf, w.W_2, 7, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, false, false)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(linear(u, ldu, w.W_1, 6, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, false, false, false, true)); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(linear(big, ldf, w.W_2, 7, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, false, false, true, false)); }
     return LVX_OK;
+}
+
+// FP8 stages: clears both amax slot arrays once per entry-point call
+lvx_status_t fp8_begin(const lvx_stage_t *s, char *ws, const ws_layout_t &L, hipStream_t st) {
+    if (s->blocks_fp8 == nullptr) return LVX_OK;
+    return lvx_launch_fill_zero(ws + L.q8_misc, 2 * LVX_AMAX_SLOTS * sizeof(uint32_t), st);
 }
 
 lvx_status_t check_common(const lvx_stage_t *s, lvx_kvcache *c, void *x, int n, const void *ctx, int n_ctx, void *ws, size_t ws_bytes,
@@ -259,8 +282,10 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
     const size_t n_elems = (size_t)n_tokens * stage->rope.n_heads * stage->rope.head_dim;
     float *h = (float *)((char *)dev_workspace + L.h);
     LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_inout, h, n_elems, (hipStream_t)stream));
+    int amax_cur = 0;
+    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
     LVX_TRY(run_block(stage, layer, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0, (char *)dev_workspace, L,
-                      (hipStream_t)stream));
+                      (hipStream_t)stream, &amax_cur));
     return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
 }
 
@@ -270,8 +295,10 @@ extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t laye
     LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
     LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
+    int amax_cur = 0;
+    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
     return run_block(stage, layer, cache, dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
-                     (char *)dev_workspace, L, (hipStream_t)stream);
+                     (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur);
 }
 
 extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
@@ -287,10 +314,12 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
     float *h = (float *)((char *)dev_workspace + L.h);
     const size_t n_elems = (size_t)n_tokens * d;
     LVX_TRY(lvx_launch_widen(x, h, n_elems, (hipStream_t)stream));
+    int amax_cur = 0;
+    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
     for (int l = 0; l < stage->n_layers; ++l) {
         const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
         LVX_TRY(run_block(stage, l, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, m6, chunk_index, t0, (char *)dev_workspace, L,
-                          (hipStream_t)stream));
+                          (hipStream_t)stream, &amax_cur));
     }
     // Euler step of Alg. 3 / Alg. 4:  x <- x + v dt, the stack output standing in for the velocity
     return lvx_launch_euler(x, h, dt, x, n_elems, (hipStream_t)stream);
@@ -316,10 +345,12 @@ extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t
     const int d = stage->rope.n_heads * stage->rope.head_dim;
     float *h = (float *)((char *)dev_workspace + L.h);
     LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_sink, h, (size_t)n * d, (hipStream_t)stream));
+    int amax_cur = 0;
+    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
     for (int l = 0; l < stage->n_layers; ++l) {
         const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
         LVX_TRY(run_block(stage, l, cache, h, n, (const bf16_t *)dev_ctx, n_ctx, m6, 0, t_sink, (char *)dev_workspace, L, (hipStream_t)stream,
-                          true));
+                          &amax_cur, true));
     }
     if (dev_x_out != nullptr) {
         LVX_REQUIRE(lvx_aligned16(dev_x_out), LVX_ERR_INVALID_ARG, "x_out must be 16-byte aligned");

@@ -22,9 +22,11 @@ constexpr float E4M3_MAX = 448.0f;
 typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8_t;
 
 // ---- quantisation ---------------------------------------------------------------------------------------------------
-// amax_bits: the fp32 bit pattern of max|x| (non-negative floats order like their bit patterns), zeroed by the caller
+// amax_slots: LVX_AMAX_SLOTS fp32 bit patterns whose maximum is max|x| (non-negative floats order like their bit patterns),
+// zeroed before the producers run.  Producers spread their atomic maxima over the slots (thousands of atomics on ONE address
+// would serialise in L2 and cost more than the pass itself); the quantisation kernel reduces the slots.
 __global__ void __launch_bounds__(256) lvx_fp8_amax_kernel(const bf16_t *__restrict__ x, int64_t ld, int rows, int chunks_per_row,
-                                                           uint32_t *amax_bits) {
+                                                           uint32_t *amax_slots) {
     const size_t total = (size_t)rows * chunks_per_row;
     uint32_t m = 0;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
@@ -43,7 +45,6 @@ __global__ void __launch_bounds__(256) lvx_fp8_amax_kernel(const bf16_t *__restr
         const uint32_t o = (uint32_t)__shfl_xor((int)m, s);
         m = m > o ? m : o;
     }
-    // one atomic per workgroup: thousands of atomics on one address would serialise in L2 and cost more than the pass itself
     __shared__ uint32_t wave_max[4];
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
@@ -51,15 +52,24 @@ __global__ void __launch_bounds__(256) lvx_fp8_amax_kernel(const bf16_t *__restr
         m = wave_max[0];
 #pragma unroll
         for (int w = 1; w < 4; ++w) m = m > wave_max[w] ? m : wave_max[w];
-        if (m != 0) atomicMax(amax_bits, m << 16);
+        if (m != 0) atomicMax(amax_slots + (blockIdx.x & (LVX_AMAX_SLOTS - 1)), m << 16);
     }
 }
 
 // 16 bf16 -> 16 codes per thread; also publishes the dequantisation scale amax/448 (1 for an all-zero tensor)
+// zero_slots (may be NULL): another slot array, not in use by any kernel in flight, that this kernel clears for the next
+// producer (the arrays alternate, so no separate clearing launch is needed between quantisations).
 __global__ void __launch_bounds__(256) lvx_fp8_quant_kernel(const bf16_t *__restrict__ x, int64_t ld, int rows, int chunks_per_row,
-                                                            const uint32_t *__restrict__ amax_bits, uint8_t *__restrict__ q, int64_t ldq,
-                                                            float *__restrict__ scale_out) {
-    const float amax = __uint_as_float(*amax_bits);
+                                                            const uint32_t *__restrict__ amax_slots, uint32_t *__restrict__ zero_slots,
+                                                            uint8_t *__restrict__ q, int64_t ldq, float *__restrict__ scale_out) {
+    uint32_t mb = amax_slots[threadIdx.x & (LVX_AMAX_SLOTS - 1)];
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)mb, s);
+        mb = mb > o ? mb : o;
+    }
+    if (zero_slots != nullptr && blockIdx.x == 0 && threadIdx.x < LVX_AMAX_SLOTS) zero_slots[threadIdx.x] = 0;
+    const float amax = __uint_as_float(mb);
     const float inv = amax > 0.f ? E4M3_MAX / amax : 0.f;
     if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = amax > 0.f ? amax / E4M3_MAX : 1.0f;
     const size_t total = (size_t)rows * chunks_per_row;  // chunks of 16 elements
@@ -96,7 +106,8 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_fp8_kernel(const uint8_t *__restrict__ A, int64_t lda, const uint8_t *__restrict__ W, int64_t ldw,
                         const float *__restrict__ scale_a, const float *__restrict__ scale_w, bf16_t *C, int64_t ldc, int M, int N, int K,
-                        const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n, int per_xcd) {
+                        const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n, int per_xcd,
+                        uint32_t *amax_slots) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int FM = WTM / 32, FN = WTN / 32;
@@ -220,6 +231,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     // Epilogue.  Accumulator register 4g+r of fragment (i,j) holds row m0 + 32i + 8g + r and column n0 + 32j.
     const float alpha = scale_a[0] * scale_w[0];
     const int m0 = tm * BM + wm * WTM + 4 * hh, n0 = tn * BN + wn * WTN + l32;
+    uint32_t amax_b = 0;  // largest magnitude among the bf16 values this lane stores (bit pattern without sign)
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
         const int n = n0 + j * 32;
@@ -242,45 +254,69 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
                     cpf[(size_t)dm * ldc] = rpf[(size_t)dm * ldr] + gt * v;
-                else
-                    cp[(size_t)dm * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+                else {
+                    const uint32_t b = pack_bf16x2(v, 0.f) & 0xffffu;
+                    cp[(size_t)dm * ldc] = (bf16_t)b;
+                    amax_b = amax_b > (b & 0x7fffu) ? amax_b : (b & 0x7fffu);
+                }
             }
         }
+    }
+    // the output feeds another FP8 linear: hand its amax to that linear's quantisation
+    if (amax_slots != nullptr) {
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)amax_b, s);
+            amax_b = amax_b > o ? amax_b : o;
+        }
+        if (lane == 0 && amax_b != 0) atomicMax(amax_slots + ((widx * NW + wave) & (LVX_AMAX_SLOTS - 1)), amax_b << 16);
     }
 }
 
 }  // namespace
 
-lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_bits,
-                                     float *scale, hipStream_t stream) {
+lvx_status_t lvx_launch_fp8_amax(const bf16_t *x, int64_t ld, int rows, int cols, uint32_t *amax_slots, hipStream_t stream) {
     if (rows == 0) return LVX_OK;
-    LVX_TRY(lvx_launch_fill_zero(amax_bits, 16, stream));
     int amax_grid = grid_for((size_t)rows * (cols / 8));
     if (amax_grid > 1024) amax_grid = 1024;  // 4 workgroups per CU, one atomic each
-    hipLaunchKernelGGL(lvx_fp8_amax_kernel, dim3(amax_grid), dim3(256), 0, stream, x, ld, rows, cols / 8, amax_bits);
-    LVX_CHECK_HIP(hipGetLastError());
-    hipLaunchKernelGGL(lvx_fp8_quant_kernel, dim3(grid_for((size_t)rows * (cols / 16))), dim3(256), 0, stream, x, ld, rows, cols / 16,
-                       amax_bits, q, ldq, scale);
+    hipLaunchKernelGGL(lvx_fp8_amax_kernel, dim3(amax_grid), dim3(256), 0, stream, x, ld, rows, cols / 8, amax_slots);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
 
+lvx_status_t lvx_launch_fp8_quant(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, const uint32_t *amax_slots,
+                                  uint32_t *zero_slots, float *scale, hipStream_t stream) {
+    if (rows == 0) return LVX_OK;
+    hipLaunchKernelGGL(lvx_fp8_quant_kernel, dim3(grid_for((size_t)rows * (cols / 16))), dim3(256), 0, stream, x, ld, rows, cols / 16,
+                       amax_slots, zero_slots, q, ldq, scale);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_slots,
+                                     float *scale, hipStream_t stream) {
+    if (rows == 0) return LVX_OK;
+    LVX_TRY(lvx_launch_fill_zero(amax_slots, LVX_AMAX_SLOTS * sizeof(uint32_t), stream));
+    LVX_TRY(lvx_launch_fp8_amax(x, ld, rows, cols, amax_slots, stream));
+    return lvx_launch_fp8_quant(x, ld, rows, cols, q, ldq, amax_slots, nullptr, scale, stream);
+}
+
 extern "C" lvx_status_t lvx_fp8_quantize(const void *dev_x, int64_t ld, int32_t rows, int32_t cols, void *dev_q, int64_t ldq,
-                                         void *dev_scratch16, float *dev_scale, lvx_stream_t stream) {
-    LVX_REQUIRE(dev_x != nullptr && dev_q != nullptr && dev_scratch16 != nullptr && dev_scale != nullptr, LVX_ERR_INVALID_ARG,
+                                         void *dev_scratch256, float *dev_scale, lvx_stream_t stream) {
+    LVX_REQUIRE(dev_x != nullptr && dev_q != nullptr && dev_scratch256 != nullptr && dev_scale != nullptr, LVX_ERR_INVALID_ARG,
                 "x, q, scratch or scale is NULL");
-    LVX_REQUIRE(lvx_aligned16(dev_x) && lvx_aligned16(dev_q) && lvx_aligned16(dev_scratch16) && (((uintptr_t)dev_scale) & 3u) == 0,
+    LVX_REQUIRE(lvx_aligned16(dev_x) && lvx_aligned16(dev_q) && lvx_aligned16(dev_scratch256) && (((uintptr_t)dev_scale) & 3u) == 0,
                 LVX_ERR_INVALID_ARG, "x, q and scratch must be 16-byte aligned, scale 4-byte aligned");
     LVX_REQUIRE(rows >= 0 && cols > 0 && cols % 16 == 0, LVX_ERR_SHAPE, "rows %d, cols %d (cols must be a positive multiple of 16)", rows, cols);
     LVX_REQUIRE(ld >= cols && ld % 8 == 0 && ldq >= cols && ldq % 16 == 0, LVX_ERR_SHAPE,
                 "row strides: ld a multiple of 8 and ldq a multiple of 16, both >= cols");
-    return lvx_launch_fp8_quantize((const bf16_t *)dev_x, ld, rows, cols, (uint8_t *)dev_q, ldq, (uint32_t *)dev_scratch16, dev_scale,
+    return lvx_launch_fp8_quantize((const bf16_t *)dev_x, ld, rows, cols, (uint8_t *)dev_q, ldq, (uint32_t *)dev_scratch256, dev_scale,
                                    (hipStream_t)stream);
 }
 
-extern "C" lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
-                                       const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K,
-                                       lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate, lvx_stream_t stream) {
+lvx_status_t lvx_launch_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
+                                   const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi,
+                                   const void *dev_resid, int64_t ldr, const float *dev_gate, uint32_t *amax_slots, hipStream_t stream) {
     LVX_REQUIRE(dev_aq != nullptr && dev_wq != nullptr && dev_c != nullptr && dev_scale_a != nullptr && dev_scale_w != nullptr,
                 LVX_ERR_INVALID_ARG, "A, W, C or a scale pointer is NULL");
     LVX_REQUIRE(lvx_aligned16(dev_aq) && lvx_aligned16(dev_wq) && lvx_aligned16(dev_c) && lvx_aligned16(dev_resid), LVX_ERR_INVALID_ARG,
@@ -306,7 +342,7 @@ extern "C" lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const fl
 #define LVX8_LAUNCH(EPI_)                                                                                                         \
     hipLaunchKernelGGL((lvx_gemm_fp8_kernel<BM, BN, 2, 4, EPI_>), grid, block, 0, (hipStream_t)stream, (const uint8_t *)dev_aq, lda, \
                        (const uint8_t *)dev_wq, ldw, dev_scale_a, dev_scale_w, (bf16_t *)dev_c, ldc, M, N, K, (const bf16_t *)dev_resid, \
-                       ldr, dev_gate, tiles_m, tiles_n, per_xcd)
+                       ldr, dev_gate, tiles_m, tiles_n, per_xcd, amax_slots)
     if (epi == LVX_EPI_STORE) {
         LVX8_LAUNCH(LVX_EPI_STORE);
     } else if (epi == LVX_EPI_GELU_TANH) {
@@ -319,4 +355,11 @@ extern "C" lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const fl
 #undef LVX8_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
+}
+
+extern "C" lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
+                                       const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K,
+                                       lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate, lvx_stream_t stream) {
+    return lvx_launch_linear_fp8(dev_aq, lda, dev_scale_a, dev_wq, ldw, dev_scale_w, dev_c, ldc, M, N, K, epi, dev_resid, ldr, dev_gate, nullptr,
+                                 (hipStream_t)stream);
 }

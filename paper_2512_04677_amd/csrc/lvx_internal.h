@@ -86,7 +86,7 @@ lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, in
 // Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream);
+                                  hipStream_t stream, uint32_t *amax_slots = nullptr);
 // out = bf16((x ? x : 0) + dt * h) with h in fp32: the Euler step of the stage (x given) or the narrowing of a block's
 // fp32 residual stream (x NULL, dt 1).
 lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
@@ -116,9 +116,20 @@ lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, con
 // C1 = A W1^T, C2 = A W2^T in one launch (bf16, plain store).
 lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
                                     int64_t ldc, int M, int N, int K, hipStream_t stream);
-// Per-tensor dynamic FP8 quantisation of a bf16 matrix (amax, then codes and the dequantisation scale); amax_bits: 16 bytes of
-// device scratch.
-lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_bits,
+// Per-tensor dynamic FP8 quantisation of a bf16 matrix.  The amax is collected in an array of LVX_AMAX_SLOTS fp32 bit patterns
+// (256 bytes, zero before the producers write): either by lvx_launch_fp8_amax, or by the kernel that produced x (attention,
+// the GELU epilogue of an FP8 linear), which saves the extra pass.  (The LayerNorm kernel does not: its one-row waves would
+// each need an atomic, which costs that memory-bound kernel more than the separate pass over its L2-resident output.)  lvx_launch_fp8_quant reduces the slots, writes
+// codes and scale and clears `zero_slots` (another slot array, may be NULL) for the next producer.
+#define LVX_AMAX_SLOTS 64
+lvx_status_t lvx_launch_fp8_amax(const bf16_t *x, int64_t ld, int rows, int cols, uint32_t *amax_slots, hipStream_t stream);
+lvx_status_t lvx_launch_fp8_quant(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, const uint32_t *amax_slots,
+                                  uint32_t *zero_slots, float *scale, hipStream_t stream);
+// fill + amax + quant on one slot array
+lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, uint32_t *amax_slots,
                                      float *scale, hipStream_t stream);
+lvx_status_t lvx_launch_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
+                                   const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi,
+                                   const void *dev_resid, int64_t ldr, const float *dev_gate, uint32_t *amax_slots, hipStream_t stream);
 // Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
 lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);

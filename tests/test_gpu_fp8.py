@@ -134,6 +134,14 @@ def test_dit_block_fp8_streaming(lvx, preset):
     for i in range(p["window"] + 2):
         x = S.randn_bf16((n, d), S.seed_of(preset, "blk8_x", i), device=DEV)
         ctx = S.randn_bf16((p["n_ctx"], d), S.seed_of(preset, "blk8_ctx", i), device=DEV)
+        if i % 2 == 1:
+            # Tensors of very different magnitude follow each other (a context 64x larger makes the cross-attention output and
+            # the residual stream large), and outliers sit in the first / last rows and columns: the per-tensor amax comes
+            # from the kernel that produced the tensor, through slot arrays that alternate between quantisations -- an
+            # element missed by a producer saturates, and an amax left over from the previous tensor coarsens the grid 64-fold;
+            # either breaks the gates below.
+            ctx = (ctx.float() * 64).to(torch.bfloat16)
+            x[0, 0], x[0, d - 1], x[n - 1, 0], x[n - 1, d - 1], x[n // 2, d // 2] = 40.0, -48.0, 56.0, -36.0, 44.0
         mod6 = S.randn_f32((6, d), S.seed_of(preset, "blk8_mod", i), 0.2, device=DEV)
         mod6[2] += 1.0
         mod6[5] += 1.0
