@@ -164,22 +164,26 @@ def test_config4_dit_block_sampled_rows(lvx):
 
 
 def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
-    """Full-size stage (40 blocks, 28 GB of weights), two chunks.  (a) lvx_denoise_stage must equal, bit for bit up to
-    the last-place rounding of the Euler step, the chain widen -> 40 x lvx_dit_block_f32 -> Euler run on a second
-    cache; (b) in that chain, layers 0, 20 and 39 are checked on sampled tokens against the oracle's row form, which
-    is given the layer's fp32 input rows and the keys that layer's cache holds; (c) both caches end bit-identical."""
+    """Full-size stage in the benchmark's launch configuration (40 blocks, 28 GB of weights with padded rows, sink installed
+    un-rotated and re-indexed before every forward), six chunks: warm-up key counts and, from chunk 4 on, the full ring of
+    24960 keys.  (a) lvx_denoise_stage must equal, bit for bit up to the last-place rounding of the Euler step, the chain
+    widen -> 40 x lvx_dit_block_f32 -> Euler run on a second cache; (b) in that chain, at chunks 0 and 5, layers 0, 20 and 39
+    are checked on sampled tokens against the oracle's row form, which is given the layer's fp32 input rows and the keys that
+    layer's cache holds; (c) both caches end bit-identical."""
     d, sink_n, n = dims(P)
     H, D, W = P["n_heads"], P["head_dim"], P["window"]
     L = 40
-    layers = [S.block_weights(d, P["ffn"], l, "cfg5", std=0.02, device=DEV, on_device_draw=True) for l in range(L)]
+    layers = [S.block_weights(d, P["ffn"], l, "cfg5", std=0.02, device=DEV, on_device_draw=True, row_pad=64) for l in range(L)]
     rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
-    stage = lvx.StageHandle(layers, rope, P["ffn"])
+    stage = lvx.StageHandle(layers, rope, P["ffn"], ldw_d=d + 64, ldw_ffn=P["ffn"] + 64)
     cache_a, cache_b = make_cache(lvx, P, L), make_cache(lvx, P, L)
+    cache_a.attach_sink_source()
+    cache_b.attach_sink_source()
     for l in range(L):
         sk = S.randn_bf16_device((sink_n, d), S.seed_of("cfg5_sk", l), 1.0, DEV)
         sv = S.randn_bf16_device((sink_n, d), S.seed_of("cfg5_sv", l), 1.0, DEV)
-        lvx.lvx_kvcache_set_sink(cache_a, l, sk, sv)
-        lvx.lvx_kvcache_set_sink(cache_b, l, sk, sv)
+        lvx.lvx_kvcache_reset_sink(cache_a, l, sk, sv)
+        lvx.lvx_kvcache_reset_sink(cache_b, l, sk, sv)
     ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, P["n_ctx"]), dtype=torch.uint8, device=DEV)
     cfg = O.StageConfig(H, D, P["frame_h"], P["frame_w"], P["chunk_frames"], W, P["sink_frames"], P["rope_axes"])
     rows = sample_rows(n, 4, 11)
@@ -188,22 +192,24 @@ def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
     gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
     gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
     dt = -0.25
-    for i in range(2):
+    for i in range(6):
         x = S.randn_bf16_device((n, d), S.seed_of("cfg5_x", i), 1.0, DEV)
         ctx = S.randn_bf16_device((P["n_ctx"], d), S.seed_of("cfg5_ctx", i), 1.0, DEV)
         t0 = 1 + 3 * i
         xa = x.clone()
+        lvx.lvx_sink_rope_update(cache_a, rope, -1, t0 + 4)
+        lvx.lvx_sink_rope_update(cache_b, rope, -1, t0 + 4)
         lvx.lvx_denoise_stage(stage, cache_a, xa, ctx, None, dt, i, t0, ws)
         h = x.float()
         for l in range(L):
-            check = l in (0, 20, 39)
+            check = l in (0, 20, 39) and i in (0, 5)
             h_in_rows = S.to_f64(h[rows_t]) if check else None
             lvx.lvx_dit_block_f32(stage, l, cache_b, h, ctx, None, i, t0, ws)
             if not check:
                 continue
             lvx.lvx_kvcache_gather(cache_b, l, 0, cap, gk, gv)
             torch.cuda.synchronize()
-            nk = sink_n + (i + 1) * n
+            nk = sink_n + min(i + 1, W + 1) * n
             pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
             ref, _, _ = O.dit_block_rows(h_in_rows, pos, S.weights_to_f64(layers[l]), S.to_f64(gk[:nk]).reshape(nk, H, D),
                                          S.to_f64(gv[:nk]).reshape(nk, H, D), S.to_f64(ctx), None, cfg)
