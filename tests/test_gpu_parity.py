@@ -155,6 +155,46 @@ def test_attention_peaked_logits(lvx):
     stream_attention(lvx, "tiny", 3, scale_mult=0.01)     # near-uniform softmax
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_attention_random_shapes(lvx, seed):
+    """Seeded random cache geometries: 1..3 heads of 64 or 128, frames of 1..90 tokens, 1..3 frames per chunk, windows of 1..3
+    chunks, with and without a sink segment, over warm-up and eviction.  Covers single-key and single-query cases, query
+    counts below one wave, key counts below / at / just past one 64-key tile, and chunk slots that straddle tiles."""
+    r = np.random.default_rng(1000 + seed)
+    p = dict(n_heads=int(r.integers(1, 4)), head_dim=int(r.choice([64, 128])), frame_h=int(r.integers(1, 10)),
+             frame_w=int(r.integers(1, 11)), chunk_frames=int(r.integers(1, 4)), window=int(r.integers(1, 4)),
+             sink_frames=int(r.integers(0, 2)))
+    if seed == 0:
+        p.update(frame_h=1, frame_w=1, chunk_frames=1, sink_frames=0, window=1)   # one query, one key at step 0
+    if seed == 1:
+        p.update(frame_h=8, frame_w=8, chunk_frames=1, sink_frames=1, window=2)   # everything a multiple of the 64-key tile
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    scale = 1.0 / math.sqrt(D)
+    cache = make_cache(lvx, p)
+    model = O.RollingKVCache(W)
+    if sink_n:
+        sink_k = S.randn_bf16((sink_n, d), S.seed_of("rs", seed, "sk"), device=DEV)
+        sink_v = S.randn_bf16((sink_n, d), S.seed_of("rs", seed, "sv"), device=DEV)
+        lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+        model.set_sink(S.to_f64(sink_k).reshape(sink_n, H, D), S.to_f64(sink_v).reshape(sink_n, H, D))
+    else:
+        model.set_sink(np.zeros((0, H, D)), np.zeros((0, H, D)))
+    for i in range(W + 3):
+        q = S.randn_bf16((chunk_n, d), S.seed_of("rs", seed, "q", i), device=DEV)
+        k = S.randn_bf16((chunk_n, d), S.seed_of("rs", seed, "k", i), device=DEV)
+        v = S.randn_bf16((chunk_n, d), S.seed_of("rs", seed, "v", i), device=DEV)
+        out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+        info = lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        assert info.key_count == sink_n + min(i + 1, W + 1) * chunk_n
+        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        torch.cuda.synchronize()
+        ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
+                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "random geometry %d %s step %d" % (seed, p, i))
+    cache.close()
+
+
 def test_attention_special_cases(lvx):
     """All V rows equal -> output is that row; a single dominant key -> its V."""
     p = S.PRESETS["small"]
