@@ -40,7 +40,8 @@ def test_fp8_quantize_codes_bit_exact(lvx, rows, cols, std):
     assert float(sz.item()) == 1.0 and not qz.any()
 
 
-@pytest.mark.parametrize("M,N,K", [(200, 320, 256), (48, 8, 128), (1000, 1536, 512), (129, 264, 384)])
+@pytest.mark.parametrize("M,N,K", [(200, 320, 256), (48, 8, 128), (1000, 1536, 512), (129, 264, 384), (1, 8, 128), (127, 256, 128),
+                                   (385, 520, 128), (2, 776, 1024)])
 def test_linear_fp8_epilogues(lvx, M, N, K):
     a = S.randn_bf16((M, K), S.seed_of("fp8a", M, N, K), 1.0, device=DEV)
     w = S.randn_bf16((N, K), S.seed_of("fp8w", M, N, K), 1.0 / math.sqrt(K), device=DEV)

@@ -263,7 +263,8 @@ def test_layernorm_modulate(lvx):
         assert_close(u, O.layernorm(S.to_f64(x), 1e-6), "layernorm %dx%d" % (n, d))
 
 
-@pytest.mark.parametrize("M,N,K", [(200, 320, 192), (48, 8, 64), (1000, 1536, 512), (129, 264, 128)])
+@pytest.mark.parametrize("M,N,K", [(200, 320, 192), (48, 8, 64), (1000, 1536, 512), (129, 264, 128), (1, 8, 64), (127, 256, 64),
+                                   (128, 248, 320), (385, 520, 64), (2, 776, 1024)])
 def test_linear_epilogues(lvx, M, N, K):
     a = S.randn_bf16((M, K), S.seed_of("lin_a", M, N, K), device=DEV)
     w = S.randn_bf16((N, K), S.seed_of("lin_w", M, N, K), 1.0 / math.sqrt(K), device=DEV)
