@@ -346,7 +346,8 @@ lvx_status_t lvx_causal_conv_step(lvx_causal_conv_t *conv, const void *dev_x, in
 enum {
     LVX_PROF_ATTN_SELF = 0, LVX_PROF_GEMM_QKV = 1, LVX_PROF_GEMM_O = 2, LVX_PROF_GEMM_CROSS = 3, LVX_PROF_GEMM_FFN1 = 4,
     LVX_PROF_GEMM_FFN2 = 5, LVX_PROF_ATTN_CROSS = 6, LVX_PROF_ROPE_NORM = 7, LVX_PROF_APPEND = 8, LVX_PROF_LAYERNORM = 9,
-    LVX_PROF_FP8_QUANT = 10, /* per-tensor quantisation of the linears' input activations (FP8 stages only) */
+    LVX_PROF_FP8_QUANT = 10, /* per-tensor quantisation of the linears' input activations (FP8 stages only); this time is also
+                                contained in the class of the linear it precedes */
     LVX_PROF_KINDS = 11
 };
 lvx_status_t lvx_profile_set(int32_t level);
