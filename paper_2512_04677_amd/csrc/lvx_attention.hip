@@ -204,11 +204,11 @@ __global__ void __launch_bounds__(64 * NWAVES)
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
         }                                                                                                      \
         __builtin_amdgcn_sched_group_barrier(0x008, PD, 0);                                                    \
-        __builtin_amdgcn_s_setprio(0);                                                                         \
     }
     // vector phase: accumulator register v of block kb holds key  t*64 + kb*32 + 16*hh + v  for query l32
 #define LVX_ATTN_Y(t_)                                                                                         \
     {                                                                                                          \
+        __builtin_amdgcn_s_setprio(0); /* the matrix phase's priority is kept through its DMA issue, up to here */ \
         if ((t_) == n_tiles - 1 && (n_keys % KT) != 0) {                                                       \
             int lim_ = n_keys - (t_) * KT - 16 * hh; /* keys of this lane's first block that are valid */      \
             asm volatile("" : "+v"(lim_));           /* keep the 32 compares out of the loop preheader */      \
