@@ -191,6 +191,27 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // fp32 residual epilogue: this lane's part of the residual tile is fetched before the main loop and held in registers, so
+    // that only the write is left for the end (all workgroups finish their tiles at the same time and would otherwise read
+    // and write the residual with 256 CUs at once).  Rows / columns past the matrix edge are clamped (values unused).
+    const int m0 = tm * BM + wm * WTM + 4 * hh, n0 = tn * BN + wn * WTN + l32;
+    f32x16_t rres[FM][FN];
+    if (EPI == LVX_EPI_RESID_GATE_F32) {
+        const float *Rf = reinterpret_cast<const float *>(R);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = n0 + j * 32 < N ? n0 + j * 32 : N - 1;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    int row = m0 + i * 32 + 8 * (e >> 2) + (e & 3);
+                    row = row < M ? row : M - 1;
+                    rres[i][j][e] = Rf[(size_t)row * ldr + col];
+                }
+        }
+    }
+
     const int n_k = K / ROW_B;
     const int last = n_k - 1;
 #pragma unroll
@@ -230,7 +251,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 
     // Epilogue.  Accumulator register 4g+r of fragment (i,j) holds row m0 + 32i + 8g + r and column n0 + 32j.
     const float alpha = scale_a[0] * scale_w[0];
-    const int m0 = tm * BM + wm * WTM + 4 * hh, n0 = tn * BN + wn * WTN + l32;
     uint32_t amax_b = 0;  // largest magnitude among the bf16 values this lane stores (bit pattern without sign)
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -244,7 +264,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
             bf16_t *cp = C + row0 * ldc + n;
             float *cpf = reinterpret_cast<float *>(C) + row0 * ldc + n;
             const bf16_t *rp = R + row0 * ldr + n;
-            const float *rpf = reinterpret_cast<const float *>(R) + row0 * ldr + n;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int dm = 8 * (e >> 2) + (e & 3);
@@ -253,7 +272,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
                 if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
-                    cpf[(size_t)dm * ldc] = rpf[(size_t)dm * ldr] + gt * v;
+                    cpf[(size_t)dm * ldc] = rres[i][j][e] + gt * v;
                 else {
                     const uint32_t b = pack_bf16x2(v, 0.f) & 0xffffu;
                     cp[(size_t)dm * ldc] = (bf16_t)b;

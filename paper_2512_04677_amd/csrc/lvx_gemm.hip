@@ -22,8 +22,8 @@ constexpr int GROUP_M = 8;
 // n0 + 32j of C (m0, n0 already include the lane's 4*hh / l32 offsets): for a fixed register, 32 lanes write 32 consecutive
 // columns.  Interior tiles take the branch-free path; only tiles on the M or N edge check every element.
 template <int FM, int FN, int EPI>
-__device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R, int64_t ldr,
-                                                  const float *__restrict__ gate, int M, int N, int m0, int n0) {
+__device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], f32x16_t (&rres)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R,
+                                                  int64_t ldr, const float *__restrict__ gate, int M, int N, int m0, int n0) {
     const bool interior = (m0 - (m0 & 4) + FM * 32 <= M) && (n0 - (n0 & 31) + FN * 32 <= N);
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
@@ -38,7 +38,6 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_
             bf16_t *cp = C + row0 * ldc + n;
             float *cpf = reinterpret_cast<float *>(C) + row0 * ldc + n;
             const bf16_t *rp = R + row0 * ldr + n;
-            const float *rpf = reinterpret_cast<const float *>(R) + row0 * ldr + n;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int dm = 8 * (e >> 2) + (e & 3);
@@ -49,7 +48,7 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], bf16_
                 if (EPI == LVX_EPI_BIAS_SILU) v = v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * v));
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
-                    cpf[(size_t)dm * ldc] = rpf[(size_t)dm * ldr] + gt * v;
+                    cpf[(size_t)dm * ldc] = rres[i][j][e] + gt * v;
                 else
                     cp[(size_t)dm * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
             }
@@ -168,6 +167,28 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // fp32 residual epilogue: the tile of R this lane will add to is fetched NOW, before the main loop, and held in registers.
+    // All workgroups run in lock step (equal tiles, one per CU), so an epilogue that reads and writes the residual would hit
+    // HBM with 256 CUs at once while the matrix cores idle; this way only the write is left for the end.  Rows / columns past
+    // the matrix edge are clamped (loaded values unused).
+    const int m0 = tm * BM + wm * WTM + 4 * hh, n0 = tn * BN + wn * WTN + l32;
+    f32x16_t rres[FM][FN];
+    if (EPI == LVX_EPI_RESID_GATE_F32) {
+        const float *Rf = reinterpret_cast<const float *>(R);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = n0 + j * 32 < N ? n0 + j * 32 : N - 1;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    int row = m0 + i * 32 + 8 * (e >> 2) + (e & 3);
+                    row = row < M ? row : M - 1;
+                    rres[i][j][e] = Rf[(size_t)row * ldr + col];
+                }
+        }
+    }
+
     const int n_k = K / BK;
     const int last = n_k - 1;
     {
@@ -227,7 +248,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     // no DMA may still be in flight when the workgroup releases its LDS
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    lvx_gemm_epilogue<FM, FN, EPI>(acc, C, ldc, R, ldr, gate, M, N, tm * BM + wm * WTM + 4 * hh, tn * BN + wn * WTN + l32);
+    lvx_gemm_epilogue<FM, FN, EPI>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool CONV = false>
