@@ -119,7 +119,7 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
 //   install the layer's un-rotated sink keys and its values, the sink keys are rotated to temporal index t0, and the rows
 //   attend to the sink segment only; the ring is not touched.
 // amax_cur (FP8 stages): which of the two amax slot arrays the next producer writes and the next quantisation reads; both arrays
-//   are zero when the entry point starts (fp8_begin), every quantisation clears the other one.
+//   are zero when the entry point starts (call_begin), every quantisation clears the other one.
 lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
                        const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st, int *amax_cur,
                        bool sink_prefill = false) {
@@ -208,10 +208,6 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     norm_only.apply_rope = 0;
     if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st));
     if (w.gc_k) LVX_TRY(lvx_rope3d(&norm_only, nullptr, ctx_kv, ldk, nullptr, w.gc_k, n_ctx, 0, nullptr, ctx_kv, ldk, st));
-    if (L.cap_ctx != n_ctx) {  // keys past n_ctx in the last tile must be finite
-        LVX_TRY(lvx_launch_fill_zero(pack_k, (size_t)L.cap_ctx * d * 2, st));
-        LVX_TRY(lvx_launch_fill_zero(pack_v, (size_t)L.cap_ctx * d * 2, st));
-    }
     LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
     { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st, amax_out())); }
     { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false, true, false)); }
@@ -223,8 +219,11 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     return LVX_OK;
 }
 
-// FP8 stages: clears both amax slot arrays once per entry-point call
-lvx_status_t fp8_begin(const lvx_stage_t *s, char *ws, const ws_layout_t &L, hipStream_t st) {
+// Once per entry-point call: the packed context K / V^T buffers are cleared when the context does not fill its last 64-key
+// tile (the keys past n_ctx are masked in the attention but must be finite; the per-layer pack only writes keys below n_ctx),
+// and an FP8 stage clears both amax slot arrays.
+lvx_status_t call_begin(const lvx_stage_t *s, char *ws, const ws_layout_t &L, hipStream_t st, int n_ctx) {
+    if (L.cap_ctx != n_ctx) LVX_TRY(lvx_launch_fill_zero(ws + L.pack_k, L.h - L.pack_k, st));
     if (s->blocks_fp8 == nullptr) return LVX_OK;
     return lvx_launch_fill_zero(ws + L.q8_misc, 2 * LVX_AMAX_SLOTS * sizeof(uint32_t), st);
 }
@@ -283,7 +282,7 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
     float *h = (float *)((char *)dev_workspace + L.h);
     LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_inout, h, n_elems, (hipStream_t)stream));
     int amax_cur = 0;
-    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
+    LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
     LVX_TRY(run_block(stage, layer, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0, (char *)dev_workspace, L,
                       (hipStream_t)stream, &amax_cur));
     return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
@@ -296,7 +295,7 @@ extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t laye
     LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     int amax_cur = 0;
-    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
+    LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
     return run_block(stage, layer, cache, dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
                      (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur);
 }
@@ -315,7 +314,7 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
     const size_t n_elems = (size_t)n_tokens * d;
     LVX_TRY(lvx_launch_widen(x, h, n_elems, (hipStream_t)stream));
     int amax_cur = 0;
-    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
+    LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
     for (int l = 0; l < stage->n_layers; ++l) {
         const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
         LVX_TRY(run_block(stage, l, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, m6, chunk_index, t0, (char *)dev_workspace, L,
@@ -346,7 +345,7 @@ extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t
     float *h = (float *)((char *)dev_workspace + L.h);
     LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_sink, h, (size_t)n * d, (hipStream_t)stream));
     int amax_cur = 0;
-    LVX_TRY(fp8_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream));
+    LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
     for (int l = 0; l < stage->n_layers; ++l) {
         const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
         LVX_TRY(run_block(stage, l, cache, h, n, (const bf16_t *)dev_ctx, n_ctx, m6, 0, t_sink, (char *)dev_workspace, L, (hipStream_t)stream,
