@@ -15,8 +15,11 @@
 //   * K rows are placed in LDS in the order the accumulator layout wants (lane i of the A operand reads LDS row i),
 //     which makes each half-wave's 16 scores per block belong to 16 CONSECUTIVE keys, so V^T fragments are
 //     contiguous 16-byte reads.
-//   * the running maximum is only raised when a tile exceeds it by more than 2^6 (wave-uniform branch), so the
-//     rescale of the O accumulators almost never runs; the final division by the row sum absorbs the stale maximum.
+//   * the vector phase competes with the other wave's MFMA issue for the SIMD's one VALU port, so it is kept short: the
+//     reference value that online softmax subtracts only has to keep exp2 in range, so no per-tile maximum is taken.  The
+//     reference is the first tile's row maximum; a tile whose sum of exponentials reaches 2^64 (or overflows) is redone
+//     with its own maximum as the new reference and the O accumulators rescaled (wave-uniform branch, practically never
+//     taken after the first tile); the final division by the row sum absorbs whatever reference was used.
 //   * workgroup -> (head, query tile) mapping keeps all query tiles of a head on one XCD (hardware deals consecutive
 //     workgroup ids round-robin over the 8 XCDs), so a head's K/V stream is fetched into one L2 only.
 #include "lvx_internal.h"
@@ -153,7 +156,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     for (int i = 0; i < DB; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
-    float mc = -INFINITY;  // running maximum, already multiplied by c_exp2
+    float mc = 0.f;  // the reference the softmax subtracts (a row maximum, already multiplied by c_exp2); set by the first tile
     float l_run = 0.f;
     f32x16_t s[2];
     bf16x8_t pb[2][2];
@@ -215,24 +218,38 @@ __global__ void __launch_bounds__(64 * NWAVES)
             _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v)    \
                 if (kb * 32 + v >= lim_) s[kb][v] = -INFINITY;                                                 \
         }                                                                                                      \
-        float tmax = s[0][0];                                                                                  \
-        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v)        \
-            tmax = fmaxf(tmax, s[kb][v]);                                                                      \
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));                                                              \
-        const float tmc = tmax * c_exp2;                                                                       \
-        const bool need = tmc > mc + 6.0f;                                                                     \
-        if (__any(need)) {                                                                                     \
-            const float alpha = need ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;                                \
-            if (need) mc = tmc;                                                                                \
-            l_run *= alpha;                                                                                    \
-            _Pragma("unroll") for (int i = 0; i < DB; ++i) _Pragma("unroll") for (int j = 0; j < 16; ++j)      \
-                o[i][j] *= alpha;                                                                              \
-        }                                                                                                      \
-        float lsum = 0.f;                                                                                      \
-        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) {      \
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));                     \
-            lsum += p;                                                                                         \
-            pb[kb][v >> 3][v & 7] = (__bf16)p;                                                                 \
+        /* The reference mc only has to keep exp2 inside the fp32 range, so no per-tile maximum is taken: mc is the first     \
+           tile's row maximum, and a later tile whose sum of exponentials reaches 2^64 (or overflows) is redone with its own   \
+           maximum as the new reference and the accumulators rescaled.  Both half-waves of a query decide together           \
+           (wave-wide vote); the final division by the row sum absorbs whatever reference was used. */                     \
+        float lsum;                                                                                            \
+        bool rebase_ = (t_) == 0;                                                                              \
+        for (;;) {                                                                                             \
+            if (rebase_) {                                                                                     \
+                float tmax = s[0][0];                                                                          \
+                _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) \
+                    tmax = fmaxf(tmax, s[kb][v]);                                                              \
+                {   /* the other half-wave holds the same query's other 32 keys */                             \
+                    const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false); \
+                    tmax = fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1]));                            \
+                }                                                                                              \
+                const bool first_ = (t_) == 0;                                                                 \
+                const float tmc = tmax * c_exp2;                                                               \
+                const bool need = first_ || tmc > mc + 6.0f;                                                   \
+                const float alpha = (need && !first_) ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;               \
+                if (need) mc = tmc;                                                                            \
+                l_run *= alpha;                                                                                \
+                _Pragma("unroll") for (int i = 0; i < DB; ++i) _Pragma("unroll") for (int j = 0; j < 16; ++j)  \
+                    o[i][j] *= alpha;                                                                          \
+            }                                                                                                  \
+            lsum = 0.f;                                                                                        \
+            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) {  \
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));                 \
+                lsum += p;                                                                                     \
+                pb[kb][v >> 3][v & 7] = (__bf16)p;                                                             \
+            }                                                                                                  \
+            if (rebase_ || !__any(!(lsum < 0x1p64f))) break;                                                   \
+            rebase_ = true;                                                                                    \
         }                                                                                                      \
         l_run += lsum;                                                                                         \
     }

@@ -195,6 +195,48 @@ def test_attention_random_shapes(lvx, seed):
     cache.close()
 
 
+def test_attention_growing_logits_rebase(lvx):
+    """Scores that outgrow the first key tile's maximum by 2^49, 2^98 and 2^196 (and drop below it by as much): the kernel keeps
+    the first tile's row maximum as its softmax reference and only re-bases when a tile's sum of exponentials passes 2^64 or
+    overflows; both the finite and the overflowing re-base, in a middle tile and in the ragged last tile, must still give the
+    plain softmax the oracle computes in fp64.  Second step: the large keys come first, the rest falls far below."""
+    p = S.PRESETS["small"]
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    assert D == 128
+    scale = 1.0 / math.sqrt(D)
+    cache = make_cache(lvx, p)
+    model = O.RollingKVCache(W)
+    sink_k = S.randn_bf16((sink_n, d), 31, 0.01, device=DEV)
+    sink_v = S.randn_bf16((sink_n, d), 32, device=DEV)
+    lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+    model.set_sink(S.to_f64(sink_k).reshape(sink_n, H, D), S.to_f64(sink_v).reshape(sink_n, H, D))
+    g = torch.sign(S.randn_bf16((1, d), 33, device=DEV).float()) + 0.0
+    g[g == 0] = 1.0
+    rows = torch.arange(chunk_n, device=DEV)
+    for i, order in enumerate(["small_first", "large_first"]):
+        # queries: +-2 g (aligned / anti-aligned with the large keys), every third one random
+        q = (2.0 * g).repeat(chunk_n, 1) * torch.where(rows % 2 == 0, 1.0, -1.0)[:, None]
+        qr = S.randn_bf16((chunk_n, d), 34 + i, device=DEV).float()
+        q = torch.where((rows % 3 == 2)[:, None], qr, q).to(torch.bfloat16)
+        # keys: b g with b cycling 1.5, 3, 6 (q.k * scale * log2 e = 49, 98, 196 for an aligned query), tiny elsewhere
+        b = torch.tensor([1.5, 3.0, 6.0], device=DEV)[rows % 3]
+        big = b[:, None] * g
+        tiny = S.randn_bf16((chunk_n, d), 36 + i, 0.01, device=DEV).float()
+        is_big = rows >= 70 if order == "small_first" else rows < 20
+        k = torch.where(is_big[:, None], big, tiny).to(torch.bfloat16)
+        v = S.randn_bf16((chunk_n, d), 38 + i, device=DEV)
+        out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+        lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out.float()).all())
+        ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
+                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "growing logits, %s" % order)
+    cache.close()
+
+
 def test_attention_special_cases(lvx):
     """All V rows equal -> output is that row; a single dominant key -> its V."""
     p = S.PRESETS["small"]
