@@ -3,9 +3,11 @@
 //
 // Both operands have the contraction index contiguous in memory (activations [token][in], weights [out][in]), so both
 // stream global -> LDS as 16-byte chunks (direct-to-LDS loads, three 64-wide K slabs in flight) and are read back as direct
-// v_mfma_f32_32x32x16_bf16 operands with 16-byte ds_reads.  One workgroup owns a BM x BN tile of C.  The A operand of the
-// MFMA is the activation tile, so an accumulator register holds 32 consecutive output columns across lanes: stores are
-// 64-byte contiguous runs and the per-column gate / bias of the epilogue is a per-lane scalar.
+// v_mfma_f32_16x16x32_bf16 operands with 16-byte ds_reads (the 16 x 16 x 32 form moves a fifth less through the register
+// file per flop than 32 x 32 x 16 and runs 1-5 % faster here, the chip being power-limited).  One workgroup owns a BM x BN
+// tile of C.  The A operand of the MFMA is the activation tile, so an accumulator register holds 16 consecutive output
+// columns of one row per 16 lanes: stores are 32-byte (fp32: 64-byte) runs and the per-column gate / bias of the epilogue
+// is a per-lane scalar.
 // Workgroup ids are dealt to XCDs round-robin by hardware; each XCD gets a contiguous range of tiles, walked in
 // column-major order inside bands of 8 row tiles, so concurrently running workgroups of one XCD share A and W slabs in
 // that XCD's L2.
@@ -18,39 +20,38 @@ namespace {
 constexpr int BK = 64;
 constexpr int GROUP_M = 8;
 
-// Epilogue.  Accumulator register 4g+r of fragment (i,j) holds row m0 + 32i + 8g + r and column
-// n0 + 32j of C (m0, n0 already include the lane's 4*hh / l32 offsets): for a fixed register, 32 lanes write 32 consecutive
-// columns.  Interior tiles take the branch-free path; only tiles on the M or N edge check every element.
+// Epilogue.  Accumulator register e of 16 x 16 block (i,j) holds row m0 + 16i + e and column n0 + 16j of C (m0, n0 already
+// include the lane's 4*q4 / l16 offsets): for a fixed register, each group of 16 lanes writes 16 consecutive columns of one
+// row.  Interior tiles take the branch-free path; only tiles on the M or N edge check every element.
 template <int FM, int FN, int EPI>
-__device__ __forceinline__ void lvx_gemm_epilogue(f32x16_t (&acc)[FM][FN], f32x16_t (&rres)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R,
+__device__ __forceinline__ void lvx_gemm_epilogue(f32x4_t (&acc)[FM][FN], f32x4_t (&rres)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R,
                                                   int64_t ldr, const float *__restrict__ gate, int M, int N, int m0, int n0) {
-    const bool interior = (m0 - (m0 & 4) + FM * 32 <= M) && (n0 - (n0 & 31) + FN * 32 <= N);
+    const bool interior = (m0 - (m0 & 12) + FM * 16 <= M) && (n0 - (n0 & 15) + FN * 16 <= N);
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-        const int n = n0 + j * 32;
+        const int n = n0 + j * 16;
         if (!interior && n >= N) continue;
         float gt = 1.f;
         if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
         if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) gt = gate != nullptr ? gate[n] : 0.f;  // the bias of column n
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
-            const size_t row0 = (size_t)(m0 + i * 32);
+            const size_t row0 = (size_t)(m0 + i * 16);
             bf16_t *cp = C + row0 * ldc + n;
             float *cpf = reinterpret_cast<float *>(C) + row0 * ldc + n;
             const bf16_t *rp = R + row0 * ldr + n;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int dm = 8 * (e >> 2) + (e & 3);
-                if (!interior && m0 + i * 32 + dm >= M) continue;
+            for (int e = 0; e < 4; ++e) {
+                if (!interior && m0 + i * 16 + e >= M) continue;
                 float v = acc[i][j][e];
                 if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
                 if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) v += gt;
                 if (EPI == LVX_EPI_BIAS_SILU) v = v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * v));
-                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)dm * ldr]) + gt * v;
+                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)e * ldr]) + gt * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
-                    cpf[(size_t)dm * ldc] = rres[i][j][e] + gt * v;
+                    cpf[(size_t)e * ldc] = rres[i][j][e] + gt * v;
                 else
-                    cp[(size_t)dm * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+                    cp[(size_t)e * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
             }
         }
     }
@@ -72,8 +73,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
                         int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int split_tn, lvx_conv_map_t cm) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-    constexpr int FM = WTM / 32, FN = WTN / 32;
-    constexpr int NKK = BK / 16;
+    constexpr int FM = WTM / 16, FN = WTN / 16;  // 16 x 16 accumulator blocks per wave
+    constexpr int NKS = BK / 32;                 // 32-wide MFMA k-steps per slab
     constexpr int ROW_B = BK * 2;  // bytes per LDS row (unpadded)
     constexpr int A_B = BM * ROW_B, STAGE_B = (BM + BN) * ROW_B;
     constexpr int NSTAGE = 3;
@@ -81,7 +82,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     static_assert(N_INSTR % NW == 0 && (BM / 8) % NW == 0, "DMA instructions must divide over the waves, A and W separately");
     constexpr int QPW = N_INSTR / NW;   // per wave
     constexpr int A_Q = (BM / 8) / NW;  // of which the first A_Q fetch A rows
-    static_assert(NKK == 4, "the k-step grouping below assumes 4 k-steps per slab");
+    static_assert(NKS == 2 && FM % 2 == 0, "the grouping below assumes 2 k-steps per slab, each issued as two halves");
 
     __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * STAGE_B];
 
@@ -104,7 +105,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hh = lane >> 5;
+    const int l16 = lane & 15, q4 = lane >> 4;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
 
     // DMA instruction q of this wave covers stage rows 8*(wave + NW*q) .. +7 (A rows first, then W rows); lane -> (row, position)
@@ -144,45 +145,51 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_dma16((q_) < A_Q ? reinterpret_cast<const char *>(A) + a_off_ : reinterpret_cast<const char *>(W) + (size_t)(kt_) * ROW_B, \
               doff[q_], lds_wave + (uint32_t)((stage_) * STAGE_B + (q_) * NW * 1024))
 
-    // fragment reads: lane (l32, hh) reads row l32 of a 32-row block, k-chunk 2*kk + hh at its swizzled position
-    const int swz = (l32 >> 1) & 7;
-    const char *a_rd = lds + (wm * WTM + l32) * ROW_B;
-    const char *w_rd = lds + A_B + (wn * WTN + l32) * ROW_B;
+    // fragment reads for v_mfma_f32_16x16x32_bf16: lane (l16, q4) reads row l16 of a 16-row block, k-chunk 4*ks + q4 of the
+    // slab's 8, at its swizzled position
+    const int swz = (l16 >> 1) & 7;
+    const char *a_rd = lds + (wm * WTM + l16) * ROW_B;
+    const char *w_rd = lds + A_B + (wn * WTN + l16) * ROW_B;
     bf16x8_t af[2][FM], wf[2][FN];
-#define LVX_DMA_READ_FRAGS(stage_, kk_)                                                                                     \
+#define LVX_DMA_READ_A(stage_, ks_, i0_, i1_)                                                                               \
     {                                                                                                                       \
-        const int co_ = (((kk_) * 2 + hh) ^ swz) * 16 + (stage_) * STAGE_B;                                                 \
-        _Pragma("unroll") for (int i = 0; i < FM; ++i) af[(kk_) & 1][i] = *reinterpret_cast<const bf16x8_t *>(a_rd + i * 32 * ROW_B + co_); \
-        _Pragma("unroll") for (int j = 0; j < FN; ++j) wf[(kk_) & 1][j] = *reinterpret_cast<const bf16x8_t *>(w_rd + j * 32 * ROW_B + co_); \
+        const int co_ = (((ks_) * 4 + q4) ^ swz) * 16 + (stage_) * STAGE_B;                                                 \
+        _Pragma("unroll") for (int i = i0_; i < i1_; ++i) af[(ks_) & 1][i] = *reinterpret_cast<const bf16x8_t *>(a_rd + i * 16 * ROW_B + co_); \
     }
-#define LVX_DMA_MFMAS(kk_)                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j)            \
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[(kk_) & 1][i], wf[(kk_) & 1][j], acc[i][j], 0, 0, 0);
+#define LVX_DMA_READ_W(stage_, ks_, j0_, j1_)                                                                               \
+    {                                                                                                                       \
+        const int co_ = (((ks_) * 4 + q4) ^ swz) * 16 + (stage_) * STAGE_B;                                                 \
+        _Pragma("unroll") for (int j = j0_; j < j1_; ++j) wf[(ks_) & 1][j] = *reinterpret_cast<const bf16x8_t *>(w_rd + j * 16 * ROW_B + co_); \
+    }
+    // MFMAs of k-step ks_ for accumulator rows [i0_, i1_)
+#define LVX_DMA_MFMAS(ks_, i0_, i1_)                                                                         \
+    _Pragma("unroll") for (int i = i0_; i < i1_; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j)         \
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[(ks_) & 1][i], wf[(ks_) & 1][j], acc[i][j], 0, 0, 0);
 
-    f32x16_t acc[FM][FN];
+    f32x4_t acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
     // fp32 residual epilogue: the tile of R this lane will add to is fetched NOW, before the main loop, and held in registers.
     // All workgroups run in lock step (equal tiles, one per CU), so an epilogue that reads and writes the residual would hit
     // HBM with 256 CUs at once while the matrix cores idle; this way only the write is left for the end.  Rows / columns past
     // the matrix edge are clamped (loaded values unused).
-    const int m0 = tm * BM + wm * WTM + 4 * hh, n0 = tn * BN + wn * WTN + l32;
-    f32x16_t rres[FM][FN];
+    const int m0 = tm * BM + wm * WTM + 4 * q4, n0 = tn * BN + wn * WTN + l16;
+    f32x4_t rres[FM][FN];
     if (EPI == LVX_EPI_RESID_GATE_F32) {
         const float *Rf = reinterpret_cast<const float *>(R);
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-            const int col = n0 + j * 32 < N ? n0 + j * 32 : N - 1;
+            const int col = n0 + j * 16 < N ? n0 + j * 16 : N - 1;
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    int row = m0 + i * 32 + 8 * (e >> 2) + (e & 3);
+                for (int e = 0; e < 4; ++e) {
+                    int row = m0 + i * 16 + e;
                     row = row < M ? row : M - 1;
                     rres[i][j][e] = Rf[(size_t)row * ldr + col];
                 }
@@ -203,32 +210,34 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     }
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QPW) : "memory");
     __syncthreads();
-    LVX_DMA_READ_FRAGS(0, 0);
+    LVX_DMA_READ_A(0, 0, 0, FM);
+    LVX_DMA_READ_W(0, 0, 0, FN);
 
-    // Slab t is in stage t % 3.  Per slab: three MFMA groups that each read the next k-step's fragments and issue a third
-    // of the DMA for slab t+2 (into the stage that was read during slab t-1); then wait until this wave's DMA for slab t+1
-    // has landed, one workgroup barrier, and the fourth group, which already reads k-step 0 of slab t+1.
+    // Slab t is in stage t % 3.  Per slab four MFMA groups (each k-step as two halves of the accumulator rows): the first three
+    // read the fragments still missing for what follows and issue a third of the DMA for slab t+2 each (into the stage that
+    // was read during slab t-1); then wait until this wave's DMA for slab t+1 has landed, one workgroup barrier, and the
+    // fourth group, which already reads k-step 0 of slab t+1.
     int cur = 0, nxt = 1, nx2 = 2;
     for (int t = 0; t < n_k; ++t) {
         const int kt_load = t + 2 < last ? t + 2 : last;
         const size_t a_off_ = a_slab(kt_load);
-        LVX_DMA_READ_FRAGS(cur, 1);
+        LVX_DMA_READ_W(cur, 1, 0, FN);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_MFMAS(0);
+        LVX_DMA_MFMAS(0, 0, FM / 2);
 #pragma unroll
         for (int q = 0; q < QPW; ++q)
             if ((q * 3) / QPW == 0) LVX_DMA_ISSUE(nx2, kt_load, q);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_READ_FRAGS(cur, 2);
+        LVX_DMA_READ_A(cur, 1, 0, FM / 2);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_MFMAS(1);
+        LVX_DMA_MFMAS(0, FM / 2, FM);
 #pragma unroll
         for (int q = 0; q < QPW; ++q)
             if ((q * 3) / QPW == 1) LVX_DMA_ISSUE(nx2, kt_load, q);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_READ_FRAGS(cur, 3);
+        LVX_DMA_READ_A(cur, 1, FM / 2, FM);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_MFMAS(2);
+        LVX_DMA_MFMAS(1, 0, FM / 2);
 #pragma unroll
         for (int q = 0; q < QPW; ++q)
             if ((q * 3) / QPW == 2) LVX_DMA_ISSUE(nx2, kt_load, q);
@@ -236,9 +245,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QPW) : "memory");
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_READ_FRAGS(nxt, 0);
+        LVX_DMA_READ_A(nxt, 0, 0, FM);
+        LVX_DMA_READ_W(nxt, 0, 0, FN);
         __builtin_amdgcn_sched_barrier(0);
-        LVX_DMA_MFMAS(3);
+        LVX_DMA_MFMAS(1, FM / 2, FM);
         __builtin_amdgcn_sched_barrier(0);
         const int tmp = cur;
         cur = nxt;
