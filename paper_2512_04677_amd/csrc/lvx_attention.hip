@@ -2,19 +2,20 @@
 // (paper Eq. 1 and the mask rule of Sec. 3.2: everything in the cache is visible to the current block).
 //
 // Design (MI355X-first, not the Hopper kernels the paper names):
-//   * one workgroup = one head x (32*NWAVES) queries; each 64-lane wave owns 32 queries and the full head_dim.
-//   * scores are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: in that accumulator layout a lane
-//     holds scores of ONE query (column lane%32) for 16 keys per 32-key block, so the online-softmax statistics are
-//     per-lane scalars (one cross-half exchange per tile) and the exponentiated scores are already in the B-operand
-//     layout of the second MFMA, O^T += V^T P^T, with no LDS round trip.
+//   * one workgroup = one head x (32*NWAVES) queries; each 64-lane wave owns 32 queries (two blocks of 16) and the full
+//     head_dim.
+//   * scores are produced TRANSPOSED, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16 (a fifth less register-file traffic per
+//     flop than 32x32x16 and 4 % faster here, the chip being power-limited): in that accumulator layout a lane holds
+//     scores of ONE query per 16-query block (column lane%16) for 4 keys per 16-key block, so the softmax statistics are
+//     per-lane scalars (combined across the four lane groups of a query only at the end and in the rare re-base), and the
+//     exponentiated scores are already in the B-operand layout of the second MFMA, O^T += V^T P^T, with no LDS round trip.
 //   * K tiles ([64 keys][D]) and V^T tiles ([D][64 keys], stored transposed in the cache) go global -> LDS directly
 //     (global_load_lds_dwordx4, no staging registers) into rings of four tiles each; rows are XOR-swizzled so that 16
 //     consecutive lanes reading 16 bytes each hit disjoint banks.
 //   * the two waves of each SIMD are run half a period apart (matrix phase against vector phase, see "pipeline" below),
 //     so the softmax VALU work of one wave hides under the MFMA work of the other.
-//   * K rows are placed in LDS in the order the accumulator layout wants (lane i of the A operand reads LDS row i),
-//     which makes each half-wave's 16 scores per block belong to 16 CONSECUTIVE keys, so V^T fragments are
-//     contiguous 16-byte reads.
+//   * K rows are placed in LDS in the order the accumulator layout wants, which makes the 8 scores a lane group holds per
+//     32-key MFMA step belong to 8 CONSECUTIVE keys, so V^T fragments are contiguous 16-byte reads.
 //   * the vector phase competes with the other wave's MFMA issue for the SIMD's one VALU port, so it is kept short: the
 //     reference value that online softmax subtracts only has to keep exp2 in range, so no per-tile maximum is taken.  The
 //     reference is the first tile's row maximum; a tile whose sum of exponentials reaches 2^64 (or overflows) is redone
@@ -34,11 +35,11 @@ __global__ void __launch_bounds__(64 * NWAVES)
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
                          int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots) {
     constexpr int QT = 32 * NWAVES;
-    constexpr int MK = D / 16;  // MFMA k-steps over head_dim
-    constexpr int DB = D / 32;  // 32-row blocks of O^T
-    constexpr int NV = DB * 4;  // V^T fragments (= PV MFMAs) per 64-key tile
-    constexpr int NK = 2 * MK;  // K fragments (= QK MFMAs) per 64-key tile
-    constexpr int PD = 6;       // LDS fragment prefetch distance, in MFMAs
+    constexpr int MK = D / 32;  // MFMA k-steps (32 wide) over head_dim
+    constexpr int DB = D / 16;  // 16-row blocks of O^T
+    constexpr int NV = DB * 2;  // V^T fragments per 64-key tile (each feeds two PV MFMAs, one per 16-query block)
+    constexpr int NK = 4 * MK;  // K fragments per 64-key tile (each feeds two QK MFMAs)
+    constexpr int PD = 6;       // LDS fragment prefetch distance, in fragments
     // LDS: a ring of NS K tiles ([64 keys][D], rows of D*2 bytes) and a ring of NS V^T tiles ([D][64 keys], rows of 128 bytes),
     // filled by direct-to-LDS loads.  A DMA wave-instruction writes 1024 contiguous bytes, so rows cannot be padded; a 16-byte
     // chunk c of row r is stored at position c ^ swz(r) instead (the lane fetches the matching global chunk), with
@@ -66,16 +67,18 @@ __global__ void __launch_bounds__(64 * NWAVES)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hh = lane >> 5;
+    const int l16 = lane & 15, q4 = lane >> 4;
 
-    // Q fragments (B operand of S^T = K Q^T): lane holds Q[query l32][d = 16m + 8hh .. +7]
-    bf16x8_t qf[MK];
-    {
-        int row = qtile * QT + wave * 32 + l32;
-        if (row > n_q - 1) row = n_q - 1;
-        const bf16_t *qp = q + (size_t)row * ld_q + (size_t)head * D + hh * 8;
+    // Q fragments (B operand of S^T = K Q^T, v_mfma_f32_16x16x32_bf16): for query block qb, lane (l16, q4) holds
+    // Q[query 16qb + l16][d = 32m + 8q4 .. +7]
+    bf16x8_t qf[2][MK];
 #pragma unroll
-        for (int m = 0; m < MK; ++m) qf[m] = *reinterpret_cast<const bf16x8_t *>(qp + 16 * m);
+    for (int qb = 0; qb < 2; ++qb) {
+        int row = qtile * QT + wave * 32 + 16 * qb + l16;
+        if (row > n_q - 1) row = n_q - 1;
+        const bf16_t *qp = q + (size_t)row * ld_q + (size_t)head * D + q4 * 8;
+#pragma unroll
+        for (int m = 0; m < MK; ++m) qf[qb][m] = *reinterpret_cast<const bf16x8_t *>(qp + 32 * m);
     }
 
     const int n_tiles = (n_keys + KT - 1) / KT;
@@ -84,8 +87,9 @@ __global__ void __launch_bounds__(64 * NWAVES)
 
     // ---- staging (direct to LDS) -----------------------------------------------------------------------------------------
     // DMA instruction e of this wave covers LDS rows [rows_per_instr * (wave + NWAVES*e), +rows_per_instr) of a tile.
-    // K: LDS row rr holds key r(rr) (accumulator-row order: key r = 32*blk + 16h + 4g + r4 sits at LDS row 32*blk + 8g + 4h + r4,
-    // which makes each half-wave's 16 scores per block belong to 16 consecutive keys).
+    // K: LDS row rr = 16 kb + r (row r of 16-key block kb, i.e. accumulator row r of score block kb) holds key
+    // 32 (kb >> 1) + 8 (r >> 2) + 4 (kb & 1) + (r & 3): lane group q4 then owns, in blocks 2ks and 2ks + 1 together, the eight
+    // CONSECUTIVE keys 32 ks + 8 q4 .. + 7, which is exactly its share of the B operand of the PV MFMA's k-step ks.
     uint32_t kdoff[DPW], vdoff[DPW];
 #pragma unroll
     for (int e = 0; e < DPW; ++e) {
@@ -93,7 +97,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
         {
             const int rr = K_RPI * j + lane / K_CPR;  // LDS row
             const int pos = lane % K_CPR;
-            const int key = (rr & 32) | (((rr >> 2) & 1) << 4) | (((rr >> 3) & 3) << 2) | (rr & 3);
+            const int key = (rr & 32) | (((rr >> 2) & 3) << 3) | (((rr >> 4) & 1) << 2) | (rr & 3);
             const int swz = K_CPR == 16 ? (rr & 15) : ((rr >> 1) & 7);
             kdoff[e] = (uint32_t)(key * K_ROW_B + (pos ^ swz) * 16);
         }
@@ -128,15 +132,15 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 #define LVX_ATTN_WAIT_DMA(n_) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n_) : "memory")
 
-    // fragment read offsets inside a tile (bytes): K fragment m of 32-key block kb: row kb*32 + l32, chunk (2m + hh) ^ swz;
-    // V^T fragment (db, kb, mm): row db*32 + l32, chunk (4kb + 2hh + mm) ^ swz
-    const int k_swz = K_CPR == 16 ? (l32 & 15) : ((l32 >> 1) & 7);
-    const int v_swz = (l32 >> 1) & 7;
-    int kfo[MK], vfo[4];
+    // fragment read offsets inside a tile (bytes): K fragment (kb, m): row 16 kb + l16, chunk (4m + q4) ^ swz;
+    // V^T fragment (db, ks): row 16 db + l16, chunk (4 ks + q4) ^ swz
+    const int k_swz = K_CPR == 16 ? l16 : ((l16 >> 1) & 7);
+    const int v_swz = (l16 >> 1) & 7;
+    int kfo[MK], vfo[2];
 #pragma unroll
-    for (int m = 0; m < MK; ++m) kfo[m] = l32 * K_ROW_B + (((2 * m + hh) ^ k_swz) * 16);
+    for (int m = 0; m < MK; ++m) kfo[m] = l16 * K_ROW_B + (((4 * m + q4) ^ k_swz) * 16);
 #pragma unroll
-    for (int c = 0; c < 4; ++c) vfo[c] = l32 * V_ROW_B + ((((c >> 1) * 4 + 2 * hh + (c & 1)) ^ v_swz) * 16);
+    for (int c = 0; c < 2; ++c) vfo[c] = l16 * V_ROW_B + (((4 * c + q4) ^ v_swz) * 16);
 
     // ---- pipeline -------------------------------------------------------------------------------------------------
     // A wave alternates between a matrix phase X(t) = { O += V(t)^T P(t) ; S(t+1) = K(t+1) Q^T } (MFMAs fed from LDS)
@@ -151,39 +155,45 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // last read in the second half of iteration i-1 (group 1's X(i-2)), which ended at a barrier before the issue.
     const int grp = wave / (NWAVES / 2);
 
-    f32x16_t o[DB];
+    // o[db][qb][e] = O^T[d = 16 db + 4 q4 + e][query 16 qb + l16];  s[kb][qb][e] = score of key row 4 q4 + e of block kb
+    f32x4_t o[DB][2];
 #pragma unroll
     for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) o[i][j] = 0.f;
-    float mc = 0.f;  // the reference the softmax subtracts (a row maximum, already multiplied by c_exp2); set by the first tile
-    float l_run = 0.f;
-    f32x16_t s[2];
-    bf16x8_t pb[2][2];
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[i][qb][e] = 0.f;
+    // per query block: the reference the softmax subtracts (a row maximum, already multiplied by c_exp2; set by the first
+    // tile) and this lane's share of the row sum
+    float mc[2] = {0.f, 0.f};
+    float l_run[2] = {0.f, 0.f};
+    f32x4_t s[4][2];
+    bf16x8_t pb[2][2];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
 
     // S(0) = K(0) Q^T from K slot 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
 #define LVX_ATTN_S0()                                                                                          \
     {                                                                                                          \
-        _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) {                                                     \
-            _Pragma("unroll") for (int j = 0; j < 16; ++j) s[kb][j] = 0.f;                                     \
+        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) {                                                     \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][0][e] = s[kb][1][e] = 0.f;                     \
             bf16x8_t a[MK];                                                                                    \
             _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
-                a[m] = *reinterpret_cast<const bf16x8_t *>(ks + kb * 32 * K_ROW_B + kfo[m]);                   \
-            _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], qf[m], s[kb], 0, 0, 0);                  \
+                a[m] = *reinterpret_cast<const bf16x8_t *>(ks + kb * 16 * K_ROW_B + kfo[m]);                   \
+            _Pragma("unroll") for (int m = 0; m < MK; ++m) {                                                   \
+                s[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[0][m], s[kb][0], 0, 0, 0);         \
+                s[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[1][m], s[kb][1], 0, 0, 0);         \
+            }                                                                                                  \
         }                                                                                                      \
     }
     // Matrix phase X(j): O^T += V(j)^T P(j)^T from V slot j%NS, then S(j+1) = K(j+1) Q^T from K slot (j+1)%NS (past the last
-    // tile the slot holds a copy of the last tile; that S is never used).  One basic block of NV + NK MFMAs, each fed by one
-    // 16-byte LDS fragment.  The fragment reads run PD MFMAs ahead of their use through a ring of PD registers, and the
-    // scheduler is told to keep that order (PD reads, then MFMA / read pairs, then PD MFMAs), so an MFMA never waits for a
-    // read issued just before it.  Consecutive MFMAs target different accumulators (round robin over the DB blocks of O^T,
-    // then over the two 32-key blocks of S), so none has to wait for the previous one's result.
-    //   fragment f < NV :  r = f / DB: V^T rows 32*(f%DB).., key chunk (r/2, r%2)   -> o[f%DB] += frag * pb[r/2][r%2]
-    //   fragment f >= NV:  g = f - NV: K rows 32*(g%2).., dims 16*(g/2) ..          -> s[g%2] += frag * qf[g/2]
+    // tile the slot holds a copy of the last tile; that S is never used).  One basic block of NV + NK LDS fragments, each
+    // feeding two MFMAs (the two 16-query blocks).  The fragment reads run PD fragments ahead of their use through a ring
+    // of PD registers, and the scheduler is told to keep that order (PD reads, then two MFMAs / one read, then 2 PD MFMAs),
+    // so an MFMA never waits for a read issued just before it.  Consecutive MFMAs target different accumulators.
+    //   fragment f < NV :  V^T rows 16*(f%DB).., keys 32*(f/DB) ..      -> o[f%DB][qb] += frag * pb[qb][f/DB]
+    //   fragment f >= NV:  g = f - NV: K rows 16*(g%4).., dims 32*(g/4) ..  -> s[g%4][qb] += frag * qf[qb][g/4]
 #define LVX_ATTN_FRAG(f_)                                                                                              \
-    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 32 * V_ROW_B + vfo[((f_) / DB) & 3])            \
-               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 1) * 32 * K_ROW_B + kfo[(((f_) - NV) >> 1) % MK]))
+    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 16 * V_ROW_B + vfo[((f_) / DB) & 1])            \
+               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 3) * 16 * K_ROW_B + kfo[(((f_) - NV) >> 2) % MK]))
 #define LVX_ATTN_X(j_)                                                                                         \
     {                                                                                                          \
         __builtin_amdgcn_s_setprio(2); /* the matrix phase wins instruction arbitration over the other wave's VALU */ \
@@ -191,67 +201,75 @@ __global__ void __launch_bounds__(64 * NWAVES)
         const char *kr = ks + (((j_) + 1) & (NS - 1)) * TILE_B;                                                \
         bf16x8_t fr[PD];                                                                                       \
         _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
-        _Pragma("unroll") for (int j = 0; j < 16; ++j) s[0][j] = 0.f;                                          \
-        _Pragma("unroll") for (int j = 0; j < 16; ++j) s[1][j] = 0.f;                                          \
+        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)         \
+            s[kb][0][e] = s[kb][1][e] = 0.f;                                                                   \
         _Pragma("unroll") for (int f = 0; f < NV + NK; ++f) {                                                  \
             const bf16x8_t a = fr[f % PD];                                                                     \
             if (f + PD < NV + NK) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                          \
-            if (f < NV)                                                                                        \
-                o[f % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[((f / DB) >> 1) & 1][(f / DB) & 1], o[f % DB], 0, 0, 0); \
-            else                                                                                               \
-                s[(f - NV) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[(f - NV) >> 1], s[(f - NV) & 1], 0, 0, 0); \
+            if (f < NV) {                                                                                      \
+                o[f % DB][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[0][(f / DB) & 1], o[f % DB][0], 0, 0, 0); \
+                o[f % DB][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[1][(f / DB) & 1], o[f % DB][1], 0, 0, 0); \
+            } else {                                                                                           \
+                s[(f - NV) & 3][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[0][((f - NV) >> 2) % MK], s[(f - NV) & 3][0], 0, 0, 0); \
+                s[(f - NV) & 3][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[1][((f - NV) >> 2) % MK], s[(f - NV) & 3][1], 0, 0, 0); \
+            }                                                                                                  \
         }                                                                                                      \
         __builtin_amdgcn_sched_group_barrier(0x100, PD, 0);                                                    \
         _Pragma("unroll") for (int f = 0; f < NV + NK - PD; ++f) {                                             \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                 \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                                 \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
         }                                                                                                      \
-        __builtin_amdgcn_sched_group_barrier(0x008, PD, 0);                                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * PD, 0);                                                \
     }
-    // vector phase: accumulator register v of block kb holds key  t*64 + kb*32 + 16*hh + v  for query l32
+    // vector phase: s[kb][qb][e] is the score of key  t*64 + 32 (kb >> 1) + 8 q4 + 4 (kb & 1) + e  for query 16 qb + l16
 #define LVX_ATTN_Y(t_)                                                                                         \
     {                                                                                                          \
         __builtin_amdgcn_s_setprio(0); /* the matrix phase's priority is kept through its DMA issue, up to here */ \
         if ((t_) == n_tiles - 1 && (n_keys % KT) != 0) {                                                       \
-            int lim_ = n_keys - (t_) * KT - 16 * hh; /* keys of this lane's first block that are valid */      \
-            asm volatile("" : "+v"(lim_));           /* keep the 32 compares out of the loop preheader */      \
-            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v)    \
-                if (kb * 32 + v >= lim_) s[kb][v] = -INFINITY;                                                 \
+            int lim_ = n_keys - (t_) * KT - 8 * q4; /* valid keys, counted from this lane group's first key */ \
+            asm volatile("" : "+v"(lim_));          /* keep the compares out of the loop preheader */          \
+            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)     \
+                if (32 * (kb >> 1) + 4 * (kb & 1) + e >= lim_) s[kb][0][e] = s[kb][1][e] = -INFINITY;          \
         }                                                                                                      \
         /* The reference mc only has to keep exp2 inside the fp32 range, so no per-tile maximum is taken: mc is the first     \
            tile's row maximum, and a later tile whose sum of exponentials reaches 2^64 (or overflows) is redone with its own   \
-           maximum as the new reference and the accumulators rescaled.  Both half-waves of a query decide together           \
-           (wave-wide vote); the final division by the row sum absorbs whatever reference was used. */                     \
-        float lsum;                                                                                            \
+           maximum as the new reference and the accumulators rescaled.  The four lane groups that share a query decide     \
+           together (wave-wide vote); the final division by the row sum absorbs whatever reference was used. */            \
+        float lsum0, lsum1;                                                                                    \
         bool rebase_ = (t_) == 0;                                                                              \
         for (;;) {                                                                                             \
             if (rebase_) {                                                                                     \
-                float tmax = s[0][0];                                                                          \
-                _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) \
-                    tmax = fmaxf(tmax, s[kb][v]);                                                              \
-                {   /* the other half-wave holds the same query's other 32 keys */                             \
-                    const auto sw_ = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false); \
-                    tmax = fmaxf(__uint_as_float(sw_[0]), __uint_as_float(sw_[1]));                            \
+                _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                             \
+                    float tmax = s[0][qb][0];                                                                  \
+                    _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
+                        tmax = fmaxf(tmax, s[kb][qb][e]);                                                      \
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));                                                  \
+                    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));                                                  \
+                    const bool first_ = (t_) == 0;                                                             \
+                    const float tmc = tmax * c_exp2;                                                           \
+                    const bool need = first_ || tmc > mc[qb] + 6.0f;                                           \
+                    const float alpha = (need && !first_) ? __builtin_amdgcn_exp2f(mc[qb] - tmc) : 1.0f;       \
+                    if (need) mc[qb] = tmc;                                                                    \
+                    l_run[qb] *= alpha;                                                                        \
+                    _Pragma("unroll") for (int i = 0; i < DB; ++i) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
+                        o[i][qb][e] *= alpha;                                                                  \
                 }                                                                                              \
-                const bool first_ = (t_) == 0;                                                                 \
-                const float tmc = tmax * c_exp2;                                                               \
-                const bool need = first_ || tmc > mc + 6.0f;                                                   \
-                const float alpha = (need && !first_) ? __builtin_amdgcn_exp2f(mc - tmc) : 1.0f;               \
-                if (need) mc = tmc;                                                                            \
-                l_run *= alpha;                                                                                \
-                _Pragma("unroll") for (int i = 0; i < DB; ++i) _Pragma("unroll") for (int j = 0; j < 16; ++j)  \
-                    o[i][j] *= alpha;                                                                          \
             }                                                                                                  \
-            lsum = 0.f;                                                                                        \
-            _Pragma("unroll") for (int kb = 0; kb < 2; ++kb) _Pragma("unroll") for (int v = 0; v < 16; ++v) {  \
-                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][v], c_exp2, -mc));                 \
-                lsum += p;                                                                                     \
-                pb[kb][v >> 3][v & 7] = (__bf16)p;                                                             \
+            lsum0 = 0.f;                                                                                       \
+            lsum1 = 0.f;                                                                                       \
+            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) {   \
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][0][e], c_exp2, -mc[0]));          \
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][1][e], c_exp2, -mc[1]));          \
+                lsum0 += p0;                                                                                   \
+                lsum1 += p1;                                                                                   \
+                pb[0][kb >> 1][4 * (kb & 1) + e] = (__bf16)p0;                                                 \
+                pb[1][kb >> 1][4 * (kb & 1) + e] = (__bf16)p1;                                                 \
             }                                                                                                  \
-            if (rebase_ || !__any(!(lsum < 0x1p64f))) break;                                                   \
+            if (rebase_ || !__any(!(lsum0 < 0x1p64f && lsum1 < 0x1p64f))) break;                               \
             rebase_ = true;                                                                                    \
         }                                                                                                      \
-        l_run += lsum;                                                                                         \
+        l_run[0] += lsum0;                                                                                     \
+        l_run[1] += lsum1;                                                                                     \
     }
 
     LVX_ATTN_DMA_K(0);
@@ -314,21 +332,22 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
     LVX_ATTN_WAIT_DMA(0);  // no DMA may still be in flight when the workgroup releases its LDS
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = 1.0f / l_tot;
-    const int row = qtile * QT + wave * 32 + l32;
     uint32_t amax_b = 0;  // largest magnitude among the bf16 values this lane stores (bit pattern without sign)
-    if (row < n_q) {
-        bf16_t *op = out + (size_t)row * ld_out + (size_t)head * D;
-        // accumulator register 4g+r of block db holds O^T[d = 32db + 8g + 4hh + r][query l32]
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int qb = 0; qb < 2; ++qb) {
+        float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16);
+        l_tot += __shfl_xor(l_tot, 32);
+        const float inv = 1.0f / l_tot;
+        const int row = qtile * QT + wave * 32 + 16 * qb + l16;
+        if (row < n_q) {
+            bf16_t *op = out + (size_t)row * ld_out + (size_t)head * D;
+            // accumulator register e of block (db, qb) holds O^T[d = 16db + 4q4 + e][query 16qb + l16]
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int db = 0; db < DB; ++db) {
                 uint2 w;
-                w.x = pack_bf16x2(o[db][4 * g + 0] * inv, o[db][4 * g + 1] * inv);
-                w.y = pack_bf16x2(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv);
-                *reinterpret_cast<uint2 *>(op + 32 * db + 8 * g + 4 * hh) = w;
+                w.x = pack_bf16x2(o[db][qb][0] * inv, o[db][qb][1] * inv);
+                w.y = pack_bf16x2(o[db][qb][2] * inv, o[db][qb][3] * inv);
+                *reinterpret_cast<uint2 *>(op + 16 * db + 4 * q4) = w;
                 if (amax_slots != nullptr) {
                     const uint32_t a0 = w.x & 0x7fffu, a1 = (w.x >> 16) & 0x7fffu, a2 = w.y & 0x7fffu, a3 = (w.y >> 16) & 0x7fffu;
                     uint32_t m = a0 > a1 ? a0 : a1;
@@ -337,6 +356,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
                     amax_b = amax_b > m ? amax_b : m;
                 }
             }
+        }
     }
     // the output feeds an FP8 linear: hand its amax to that linear's quantisation (one atomic per wave)
     if (amax_slots != nullptr) {
