@@ -39,7 +39,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     constexpr int DB = D / 16;  // 16-row blocks of O^T
     constexpr int NV = DB * 2;  // V^T fragments per 64-key tile (each feeds two PV MFMAs, one per 16-query block)
     constexpr int NK = 4 * MK;  // K fragments per 64-key tile (each feeds two QK MFMAs)
-    constexpr int PD = 6;       // LDS fragment prefetch distance, in fragments
+    constexpr int PD = 4;       // LDS fragment prefetch distance, in fragments (2, 3, 6, 8, 10 measured: 4 is best by 1 %)
     // LDS: a ring of NS K tiles ([64 keys][D], rows of D*2 bytes) and a ring of NS V^T tiles ([D][64 keys], rows of 128 bytes),
     // filled by direct-to-LDS loads.  A DMA wave-instruction writes 1024 contiguous bytes, so rows cannot be padded; a 16-byte
     // chunk c of row r is stored at position c ^ swz(r) instead (the lane fetches the matching global chunk), with
