@@ -25,7 +25,7 @@ What the paper fixes and where (own words):
     the model's own first generated latent, which needs a second warm-up to produce its K/V.
 
 What the paper does not give (hidden size, heads, FFN width, norm placement, RoPE split, GELU form) is
-taken from the build's workload description; every such reading is listed in the design doc.
+taken from the build's workload description; each such reading is stated where the function that uses it is defined.
 
 Parity pins live in tests/test_oracle_*.py.  Unpinned by anything the paper prints (the paper has no
 worked numeric example): the *placement* of RMSNorm / LayerNorm / gates inside the block ("parity
