@@ -188,8 +188,9 @@ def main():
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE); algorithmic: %d" % (2 * d * (2 * n + 2 * n_k)),
                      "flops_per_launch": attn_fl, "avg_launch_ms": round(attn_avg_ms, 4), "launches": attn_n,
-                     "peak_note": "published dense bf16 MFMA peak; a register-only MFMA loop on random operands sustains 1700 TFLOP/s "
-                                  "on this chip (power-limited, 1.6 GHz), 2290 on constant operands"},
+                     "peak_note": "published dense bf16 MFMA peak (2.4 GHz); in the stage this kernel runs at about 2.0 GHz with the matrix "
+                                  "cores busy in 64 % of the cycles (its softmax VALU phase and its MFMA phase do not overlap on a SIMD); "
+                                  "with the softmax removed the same kernel reaches 89 % of this peak"},
     }
     if args.profile_level >= 2:
         out["kernel_ms_per_step"] = {k: round(v[0] / args.steps, 3) for k, v in prof.items() if v[1]}
