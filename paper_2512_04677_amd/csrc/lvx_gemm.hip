@@ -27,31 +27,37 @@ template <int FM, int FN, int EPI>
 __device__ __forceinline__ void lvx_gemm_epilogue(f32x4_t (&acc)[FM][FN], f32x4_t (&rres)[FM][FN], bf16_t *C, int64_t ldc, const bf16_t *R,
                                                   int64_t ldr, const float *__restrict__ gate, int M, int N, int m0, int n0) {
     const bool interior = (m0 - (m0 & 12) + FM * 16 <= M) && (n0 - (n0 & 15) + FN * 16 <= N);
+    float gt[FN];  // per column block: the gate (residual epilogues) or the bias of this lane's column
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
-        const int n = n0 + j * 16;
-        if (!interior && n >= N) continue;
-        float gt = 1.f;
-        if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt = gate[n];
-        if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) gt = gate != nullptr ? gate[n] : 0.f;  // the bias of column n
+        const int n = n0 + j * 16 < N ? n0 + j * 16 : N - 1;
+        gt[j] = 1.f;
+        if ((EPI == LVX_EPI_RESID_GATE || EPI == LVX_EPI_RESID_GATE_F32) && gate != nullptr) gt[j] = gate[n];
+        if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) gt[j] = gate != nullptr ? gate[n] : 0.f;
+    }
+    // rows outermost, column blocks innermost: the FN stores of one row follow each other, so neighbouring 32-byte (fp32:
+    // 64-byte) runs of a cache line reach L2 together
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const size_t row0 = (size_t)(m0 + i * 16);
-            bf16_t *cp = C + row0 * ldc + n;
-            float *cpf = reinterpret_cast<float *>(C) + row0 * ldc + n;
-            const bf16_t *rp = R + row0 * ldr + n;
+    for (int i = 0; i < FM; ++i) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (!interior && m0 + i * 16 + e >= M) continue;
+        for (int e = 0; e < 4; ++e) {
+            const int m = m0 + i * 16 + e;
+            if (!interior && m >= M) continue;
+            bf16_t *cp = C + (size_t)m * ldc + n0;
+            float *cpf = reinterpret_cast<float *>(C) + (size_t)m * ldc + n0;
+            const bf16_t *rp = R + (size_t)m * ldr + n0;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if (!interior && n0 + j * 16 >= N) continue;
                 float v = acc[i][j][e];
                 if (EPI == LVX_EPI_GELU_TANH) v = gelu_tanh_f32(v);
-                if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) v += gt;
+                if (EPI == LVX_EPI_BIAS || EPI == LVX_EPI_BIAS_SILU) v += gt[j];
                 if (EPI == LVX_EPI_BIAS_SILU) v = v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * v));
-                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[(size_t)e * ldr]) + gt * v;
+                if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[j * 16]) + gt[j] * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
-                    cpf[(size_t)e * ldc] = rres[i][j][e] + gt * v;
+                    cpf[j * 16] = rres[i][j][e] + gt[j] * v;
                 else
-                    cp[(size_t)e * ldc] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
+                    cp[j * 16] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
             }
         }
     }
