@@ -188,18 +188,19 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     f32x4_t rres[FM][FN];
     if (EPI == LVX_EPI_RESID_GATE_F32) {
         const float *Rf = reinterpret_cast<const float *>(R);
+        // rows outermost, column blocks innermost: the FN loads of one row are neighbouring 64-byte runs
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = n0 + j * 16 < N ? n0 + j * 16 : N - 1;
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+            for (int e = 0; e < 4; ++e) {
+                int row = m0 + i * 16 + e;
+                row = row < M ? row : M - 1;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    int row = m0 + i * 16 + e;
-                    row = row < M ? row : M - 1;
+                for (int j = 0; j < FN; ++j) {
+                    const int col = n0 + j * 16 < N ? n0 + j * 16 : N - 1;
                     rres[i][j][e] = Rf[(size_t)row * ldr + col];
                 }
-        }
+            }
     }
 
     const int n_k = K / BK;
