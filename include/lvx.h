@@ -50,7 +50,7 @@ const char *lvx_version(void);
  * chunk_frames*frame_h*frame_w keys each.  The forward of chunk i must see its own K/V (blocks attend
  * to themselves in full, Sec. 3.2) and the `window_chunks` chunks before it, so the chunk's K/V are
  * written first, into slot i mod (window_chunks+1), overwriting chunk i-(window_chunks+1): that is the
- * "pop oldest, append" of Alg. 3 with the append moved before the attention.  Attention is invariant to
+ * cache update of Alg. 3 (drop the oldest entry of a full cache, then append) with the append moved before the attention.  Attention is invariant to
  * key order (no mask, K carries its rotary phase), so the visible keys are always the contiguous prefix
  *   [0, sink_keys + min(i+1, window_chunks+1)*chunk_keys).
  * ------------------------------------------------------------------------------------------------ */
@@ -107,7 +107,7 @@ lvx_status_t lvx_kvcache_destroy(lvx_kvcache_t *cache);
 lvx_status_t lvx_kvcache_set_sink(lvx_kvcache_t *cache, int32_t layer, const void *dev_k, const void *dev_v,
                                   int64_t ld, lvx_stream_t stream);
 
-/* Alg. 3 "pop(0) if full; append": writes chunk `chunk_index`'s K-hat and V, token-major
+/* Cache update of Alg. 3 (a full cache drops its oldest entry, then the new one is appended): writes chunk `chunk_index`'s K-hat and V, token-major
  * [chunk_keys][ld], into its ring slot of `layer`; the oldest chunk is overwritten once the ring is full; the
  * sink segment is untouched.  chunk_index must be last_chunk+1 for that layer (0 first) else LVX_ERR_STATE.
  * `out` (host, may be NULL) receives the slot arithmetic.  The copy is bit-exact. */
@@ -144,19 +144,25 @@ typedef struct {
 lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc /* host */, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
                         const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0,
                         void *dev_q_out, void *dev_k_out, int64_t ld_out, lvx_stream_t stream);
+/* The same with q_in / k_in in fp32 (ld_in in fp32 elements; outputs bf16): what the block runs on the un-rounded q | k
+ * columns of its QKV projection. */
+lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc /* host */, const float *dev_q_in, const float *dev_k_in, int64_t ld_in,
+                              const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0,
+                              void *dev_q_out, void *dev_k_out, int64_t ld_out, lvx_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Rolling RoPE and the adaptive attention sink (Sec. 3.3; Appendix D; Phi(sink) and the sink assignment of Alg. 3 /
  * Alg. 4).  The sink's rotary temporal index is re-assigned at every block step so that its distance to the current
  * block stays bounded; the paper rewrites the cached sink keys in place.  Here the un-rotated (normalised) sink keys are
- * kept beside the cache and every re-assignment rotates them afresh into the cache's sink rows, so rotations never
- * compound their bf16 roundings over a long rollout.  The index itself ("slightly ahead of the current block") is the
- * caller's: the paper gives no value.
+ * kept beside the cache, in fp32, and every re-assignment rotates them afresh into the cache's sink rows, so rotations never
+ * compound their bf16 roundings over a long rollout and a sink key is rounded to bf16 once, after its rotation.  The index
+ * itself (App. D leaves it at a small offset ahead of the current block) is the caller's: the paper gives no value.
  *
- *   lvx_sink_source_bytes           device bytes for the un-rotated sink keys of all layers ([layer][sink_keys][d] bf16)
+ *   lvx_sink_source_bytes           device bytes for the un-rotated sink keys of all layers ([layer][sink_keys][d] fp32)
  *   lvx_kvcache_attach_sink_source  hands that storage (caller-owned, 256-byte aligned, alive as long as the handle) over
  *   lvx_kvcache_reset_sink          installs a sink for `layer`: dev_k_src = normalised, NOT rotated keys, dev_v = values,
- *                                   both token-major [sink_keys][ld] bf16 (bit-exact copies).  The ring is untouched.  Until
+ *                                   both token-major [sink_keys][ld] bf16 (the keys widened exactly to fp32, the values copied
+ *                                   bit for bit).  The ring is untouched.  Until
  *                                   the next lvx_sink_rope_update the layer's sink keys are stale and lvx_chunk_attention /
  *                                   lvx_dit_block / lvx_denoise_stage return LVX_ERR_STATE for it.
  *   lvx_sink_rope_update            Phi: sink keys of `layer` (-1: every layer) := RoPE(source) with the sink's first frame
@@ -164,7 +170,7 @@ lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc /* host */, const void *dev_
  *   lvx_kvcache_get_sink_index      last t_sink applied to `layer`; -1 = reset but not rotated; -2 = static sink / none
  *   lvx_kvcache_set_sink_index      restores that bookkeeping after the caller restored the device storage (resume, as
  *                                   lvx_kvcache_set_state does for the ring)
- *   lvx_kvcache_gather_sink_source  reads the stored source back, token-major [sink_keys][ld] (bit-exact)
+ *   lvx_kvcache_gather_sink_source  reads the stored source back, token-major fp32 [sink_keys][ld] (ld in fp32 elements; bit-exact)
  * Errors: STATE without attached storage, on a layer whose sink came from lvx_kvcache_set_sink (already rotated, no
  * source) or on a cache without sink segment; SHAPE if the rope descriptor disagrees with the cache; INVALID_ARG else.
  * ------------------------------------------------------------------------------------------------ */
@@ -197,7 +203,8 @@ typedef enum {
     LVX_EPI_RESID_GATE = 2, /* C = R + gate[n] * (A W^T); gate NULL = 1; C may alias R */
     LVX_EPI_RESID_GATE_F32 = 3, /* same, with C and R in fp32 (ldc, ldr in fp32 elements): the in-block residual stream */
     LVX_EPI_BIAS = 4,       /* C = A W^T + bias[n]; the bias (fp32 [N], NULL = 0) is passed in the gate argument */
-    LVX_EPI_BIAS_SILU = 5   /* C = silu(A W^T + bias[n]) */
+    LVX_EPI_BIAS_SILU = 5,  /* C = silu(A W^T + bias[n]) */
+    LVX_EPI_STORE_F32 = 6   /* C = A W^T with C in fp32 (ldc in fp32 elements): no rounding of the accumulator */
 } lvx_epilogue_t;
 
 /* C[M][N] = epilogue(A[M][K] * W[N][K]^T), bf16 in/out, fp32 accumulate on MFMA.  K % 64 == 0, N % 8 == 0. */
@@ -205,7 +212,15 @@ lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64
                         int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi, const void *dev_resid, int64_t ldr,
                         const float *dev_gate, lvx_stream_t stream);
 
-/* FP8 linears (Appendix C, "FP8 Quantization": all linear projections of the DiT in E4M3 with per-tensor dynamic scaling).
+/* Two projections of the same activations in one launch (App. C linears; the block uses it for the fused QKV projection and for
+ * the context's K and V projections):  C1[M][N1] = A W1^T,  C2[M][N2] = A W2^T, plain store, W1 / W2 share the row stride ldw.
+ * c1_is_f32 != 0: C1 is fp32 (ldc1 in fp32 elements) -- the q | k columns of the QKV projection go to the RMSNorm + RoPE kernel
+ * un-rounded, so the cached keys are rounded to bf16 once, after the rotation.  C2 is always bf16.  K % 64 == 0, N1, N2 % 8 == 0. */
+lvx_status_t lvx_linear_dual(const void *dev_a, int64_t lda, const void *dev_w1, const void *dev_w2, int64_t ldw, void *dev_c1,
+                             int64_t ldc1, int32_t c1_is_f32, void *dev_c2, int64_t ldc2, int32_t M, int32_t N1, int32_t N2, int32_t K,
+                             lvx_stream_t stream);
+
+/* FP8 linears (Appendix C, FP8 quantisation paragraph: every linear of the DiT runs in E4M3 with one dynamic scale per tensor).
  *   lvx_fp8_quantize: x bf16 [rows][ld] -> q [rows][ldq] E4M3 codes (OCP form: bias 7, largest finite value 448) and one fp32
  *     dequantisation scale = amax/448 (1 for an all-zero tensor), amax = max|x| over the whole matrix:
  *     code = E4M3(x * (448/amax)), nearest-even, saturating; scale factors and that product are formed in fp32.
@@ -300,7 +315,7 @@ lvx_status_t lvx_sample_chunk(const lvx_stage_t *stage /* host */, lvx_kvcache_t
                               const float *dev_mod6_per_step_layer, float dt, int64_t chunk_index, int32_t t0, int32_t t_sink,
                               void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 
-/* Warm-up of a sink frame (Appendix D: the sink swap of the adaptive attention sink needs a second warm-up to produce the
+/* Warm-up of a sink frame (Appendix D: after the sink swap of the adaptive attention sink the stack is run once more to produce the
  * new sink's K/V): the sink frame's tokens x_sink [sink_keys][d] bf16 run through all blocks; per layer the un-rotated,
  * normalised keys and the values of these tokens are installed as the sink (as lvx_kvcache_reset_sink does) and rotated to
  * temporal index t_sink.  Reading (the paper does not say): the sink frame attends to itself only; every other step is the

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "liblvx.so")
 _lib = None
 
 LVX_MAX_SLOTS = 16
-EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE, EPI_RESID_GATE_F32, EPI_BIAS, EPI_BIAS_SILU = 0, 1, 2, 3, 4, 5
+EPI_STORE, EPI_GELU_TANH, EPI_RESID_GATE, EPI_RESID_GATE_F32, EPI_BIAS, EPI_BIAS_SILU, EPI_STORE_F32 = 0, 1, 2, 3, 4, 5, 6
 STATUS_NAMES = {0: "LVX_OK", 1: "LVX_ERR_INVALID_ARG", 2: "LVX_ERR_SHAPE", 3: "LVX_ERR_STATE", 4: "LVX_ERR_UNSUPPORTED",
                 5: "LVX_ERR_HIP"}
 
@@ -80,8 +80,10 @@ SIGNATURES = {
     "lvx_kvcache_set_state": (C.c_int, [_vp, _i32, C.POINTER(RingState)]),
     "lvx_kvcache_gather": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
     "lvx_rope3d": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "lvx_rope3d_f32in": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
     "lvx_chunk_attention": (C.c_int, [_vp, _i32, _vp, _i64, _i32, _f32, _vp, _i64, _vp]),
     "lvx_linear": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
+    "lvx_linear_dual": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32, _vp]),
     "lvx_fp8_quantize": (C.c_int, [_vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp]),
     "lvx_linear_fp8": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
@@ -252,6 +254,15 @@ def lvx_rope3d(desc, q_in, k_in, g_q, g_k, n_tokens, t0, q_out, k_out, ld_in=Non
                              ld_out if ld_out is not None else ref_out.stride(0), _stream()))
 
 
+def lvx_rope3d_f32in(desc, q_in, k_in, g_q, g_k, n_tokens, t0, q_out, k_out, ld_in=None, ld_out=None):
+    """q_in / k_in fp32 (row stride in fp32 elements), outputs bf16."""
+    ref_in = q_in if q_in is not None else k_in
+    ref_out = q_out if q_out is not None else k_out
+    _check(load().lvx_rope3d_f32in(C.byref(desc), _ptr(q_in), _ptr(k_in), ld_in if ld_in is not None else ref_in.stride(0),
+                                   _ptr(g_q), _ptr(g_k), n_tokens, t0, _ptr(q_out), _ptr(k_out),
+                                   ld_out if ld_out is not None else ref_out.stride(0), _stream()))
+
+
 def lvx_chunk_attention(cache, layer, q, scale, out, n_q=None):
     _check(load().lvx_chunk_attention(cache.handle, layer, _ptr(q), q.stride(0), q.shape[0] if n_q is None else n_q,
                                       scale, _ptr(out), out.stride(0), _stream()))
@@ -262,6 +273,15 @@ def lvx_linear(a, w, c, epi=EPI_STORE, resid=None, gate=None, M=None):
     N, K = w.shape[0], w.shape[1]
     _check(load().lvx_linear(_ptr(a), a.stride(0), _ptr(w), w.stride(0), _ptr(c), c.stride(0), M, N, K, epi,
                              _ptr(resid), resid.stride(0) if resid is not None else 0, _ptr(gate), _stream()))
+
+
+def lvx_linear_dual(a, w1, w2, c1, c2):
+    """c1 = a w1^T (bf16 or fp32, by c1's dtype), c2 = a w2^T (bf16); w1 and w2 must share their row stride."""
+    import torch
+    assert w1.stride(0) == w2.stride(0) and w1.shape[1] == w2.shape[1]
+    _check(load().lvx_linear_dual(_ptr(a), a.stride(0), _ptr(w1), _ptr(w2), w1.stride(0), _ptr(c1), c1.stride(0),
+                                  1 if c1.dtype == torch.float32 else 0, _ptr(c2), c2.stride(0), a.shape[0], w1.shape[0], w2.shape[0],
+                                  w1.shape[1], _stream()))
 
 
 def lvx_fp8_quantize(x, q=None, row_pad=0):

@@ -42,10 +42,11 @@ struct prof_scope_t {
 };
 
 struct ws_layout_t {
-    size_t u, big, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
+    size_t u, big, qk32, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
     int64_t ld_q8, ld_q8c;                            // row strides (bytes) of the FP8 activation buffers
     int cap_ctx;
     int64_t ld_u, ld_qkv, ld_cq, ld_ffn, ld_ckv;      // padded row strides (elements) of the bf16 workspace matrices
+    int64_t ld_qk32;                                  // row stride (fp32 elements) of the un-rounded q | k columns
 };
 
 // Rows of the workspace matrices are padded by 64 elements (128 bytes): with d_model = 5120 or d_ffn = 13824 a dense row is
@@ -64,9 +65,12 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.ld_cq = (int64_t)d + WS_PAD;
     w.ld_ffn = (int64_t)s->d_ffn + WS_PAD;
     w.ld_ckv = (int64_t)2 * d + WS_PAD;
+    w.ld_qk32 = (int64_t)2 * d + WS_PAD / 2;
     size_t off = 0;
     w.u = off;       off += round256((size_t)n_tokens * w.ld_u * 2);
     w.big = off;     off += round256((size_t)n_tokens * (wide + WS_PAD) * 2);
+    w.qk32 = off;    // fp32 q | k columns of the QKV projection (bf16 stages only; an FP8 stage stores them in bf16)
+    if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * w.ld_qk32 * 4);
     w.ctx_kv = off;  off += round256((size_t)n_ctx * w.ld_ckv * 2);
     w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
     w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
@@ -167,25 +171,49 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
                                      feeds_fp8 ? amax_out() : nullptr, st);
     };
 
-    // self-attention branch
+    // self-attention branch.  bf16 stage: the q | k columns of the QKV projection leave the GEMM in fp32 and are rounded to bf16
+    // once, by the RMSNorm + RoPE kernel, after the rotation (the cached K-hat then carries two bf16 roundings, u and itself,
+    // instead of three); the v columns are stored in bf16, as the cache holds them.  FP8 stage: all three in bf16.
+    float *qk32 = (float *)(ws + L.qk32);
+    const int64_t ld32 = L.ld_qk32;
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_QKV, st); LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false)); }
+    {
+        prof_scope_t ps(LVX_PROF_GEMM_QKV, st);
+        if (w8 == nullptr)
+            LVX_TRY(lvx_launch_linear_dual(u, ldu, (const bf16_t *)w.W_qkv, (const bf16_t *)w.W_qkv + (size_t)2 * d * ldw, ldw, qk32, ld32, 1,
+                                           big + 2 * d, ldq, n, 2 * d, d, d, st));
+        else
+            LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
+    }
     if (!sink_prefill) {
-        { prof_scope_t ps(LVX_PROF_ROPE_NORM, st); LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st)); }
+        {
+            prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
+            if (w8 == nullptr)
+                LVX_TRY(lvx_rope3d_f32in(&s->rope, qk32, qk32 + d, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
+            else
+                LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
+        }
         { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
-        LVX_REQUIRE(c->sink_t[layer] != LVX_SINK_STALE, LVX_ERR_STATE,
-                    "layer %d: the sink was reset and its keys are not rotated yet (lvx_sink_rope_update)", layer);
         {
             prof_scope_t ps(LVX_PROF_ATTN_SELF, st);
             LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->state[layer].key_count,
                                          scale, u, ldu, st, amax_out()));
         }
     } else {
-        lvx_rope_desc_t k_norm_only = s->rope;
-        k_norm_only.apply_rope = 0;
-        LVX_TRY(lvx_rope3d(&s->rope, big, nullptr, ldq, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));                   // q: norm + RoPE
-        if (w.g_k) LVX_TRY(lvx_rope3d(&k_norm_only, nullptr, big + d, ldq, nullptr, w.g_k, n, 0, nullptr, big + d, ldq, st));  // k: norm only
-        LVX_TRY(lvx_kvcache_reset_sink(c, layer, big + d, big + 2 * d, ldq, st));
+        // the sink's un-rotated keys go into the cache's fp32 source storage: un-rounded from the projection in a bf16 stage,
+        // widened from the bf16 projection in an FP8 stage
+        float *src32 = c->sink_src + (size_t)layer * c->sink_keys * d;
+        if (w8 == nullptr) {
+            LVX_TRY(lvx_rope3d_f32in(&s->rope, qk32, nullptr, ld32, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));  // q: norm + RoPE
+            LVX_TRY(lvx_launch_rmsnorm_f32(&s->rope, qk32 + d, ld32, w.g_k, n, src32, d, st));                       // k: norm only
+        } else {
+            lvx_rope_desc_t k_norm_only = s->rope;
+            k_norm_only.apply_rope = 0;
+            LVX_TRY(lvx_rope3d(&s->rope, big, nullptr, ldq, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));
+            if (w.g_k) LVX_TRY(lvx_rope3d(&k_norm_only, nullptr, big + d, ldq, nullptr, w.g_k, n, 0, nullptr, big + d, ldq, st));
+            LVX_TRY(lvx_launch_widen_rows(big + d, ldq, src32, d, n, d, st));
+        }
+        LVX_TRY(lvx_sink_install_values(c, layer, big + 2 * d, ldq, st));
         LVX_TRY(lvx_sink_rope_update(c, &s->rope, layer, t0, st));
         LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->sink_keys, scale, u,
                                      ldu, st, amax_out()));
@@ -198,7 +226,7 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
         LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
         if (w8 == nullptr) {  // the context's K and V projections share one launch
-            LVX_TRY(lvx_launch_linear_pair(ctx, d, (const bf16_t *)w.Wc_k, (const bf16_t *)w.Wc_v, ldw, ctx_kv, ctx_kv + d, ldk, n_ctx, d, d, st));
+            LVX_TRY(lvx_launch_linear_dual(ctx, d, (const bf16_t *)w.Wc_k, (const bf16_t *)w.Wc_v, ldw, ctx_kv, ldk, 0, ctx_kv + d, ldk, n_ctx, d, d, d, st));
         } else {
             LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false, false, false));
             LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true, false, false));
@@ -241,6 +269,20 @@ lvx_status_t check_common(const lvx_stage_t *s, lvx_kvcache *c, void *x, int n, 
     return LVX_OK;
 }
 
+// Everything the forward of chunk `chunk_index` will ask of layers [l0, l1) of the cache, checked before the first launch so
+// that a refused call leaves the ring bookkeeping of every layer as it was: the layer expects this chunk, has its sink, and
+// the sink keys are rotated (not left stale by lvx_kvcache_reset_sink).
+lvx_status_t check_layers_ready(const lvx_kvcache *c, int l0, int l1, int64_t chunk_index) {
+    for (int l = l0; l < l1; ++l) {
+        LVX_REQUIRE(c->state[l].last_chunk + 1 == chunk_index, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", l,
+                    (long long)(c->state[l].last_chunk + 1), (long long)chunk_index);
+        LVX_REQUIRE(c->sink_keys == 0 || c->state[l].sink_set, LVX_ERR_STATE, "layer %d: sink not set before the first append", l);
+        LVX_REQUIRE(c->sink_t[l] != LVX_SINK_STALE, LVX_ERR_STATE,
+                    "layer %d: the sink was reset and its keys are not rotated yet (lvx_sink_rope_update)", l);
+    }
+    return LVX_OK;
+}
+
 }  // namespace
 
 extern "C" lvx_status_t lvx_profile_set(int32_t level) {
@@ -277,6 +319,7 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
                                       void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
     LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
     LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
+    LVX_TRY(check_layers_ready(cache, layer, layer + 1, chunk_index));
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     const size_t n_elems = (size_t)n_tokens * stage->rope.n_heads * stage->rope.head_dim;
     float *h = (float *)((char *)dev_workspace + L.h);
@@ -293,6 +336,7 @@ extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t laye
                                           void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
     LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
     LVX_REQUIRE(layer >= 0 && layer < stage->n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, stage->n_layers);
+    LVX_TRY(check_layers_ready(cache, layer, layer + 1, chunk_index));
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     int amax_cur = 0;
     LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
@@ -304,9 +348,7 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
                                           const void *dev_ctx, int32_t n_ctx, const float *dev_mod6_per_layer, float dt,
                                           int64_t chunk_index, int32_t t0, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
     LVX_TRY(check_common(stage, cache, dev_x_inout, n_tokens, dev_ctx, n_ctx, dev_workspace, ws_bytes, chunk_index, t0));
-    for (int l = 0; l < stage->n_layers; ++l)
-        LVX_REQUIRE(cache->state[l].last_chunk + 1 == chunk_index, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", l,
-                    (long long)(cache->state[l].last_chunk + 1), (long long)chunk_index);
+    LVX_TRY(check_layers_ready(cache, 0, stage->n_layers, chunk_index));
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     const int d = stage->rope.n_heads * stage->rope.head_dim;
     bf16_t *x = (bf16_t *)dev_x_inout;
@@ -325,7 +367,7 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
 }
 
 // Warm-up of a (new) sink frame, Appendix D: after the first block the model's own output replaces the reference image as
-// the sink and "a second warm-up" produces its K/V.  The sink's tokens go through every block attending to themselves.
+// the sink and the stack is run once more to produce its K/V.  The sink's tokens go through every block attending to themselves.
 extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t *cache, const void *dev_x_sink, const void *dev_ctx,
                                          int32_t n_ctx, const float *dev_mod6_per_layer, int32_t t_sink, void *dev_x_out,
                                          void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {

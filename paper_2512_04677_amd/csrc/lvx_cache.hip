@@ -1,6 +1,6 @@
 // Rolling KV cache: host ring bookkeeping + the append / sink / gather kernels.
 //
-// Protocol (paper Alg. 3 / Alg. 4: "if the cache holds L entries pop the oldest, then append"; Sec. 3.3: one sink
+// Protocol (cache update of Alg. 3 / Alg. 4: a cache that already holds L entries drops its oldest, then appends; Sec. 3.3: one sink
 // frame stays for ever; Sec. 3.2: a block attends to itself in full).  The forward of chunk i has to see chunk i's own
 // K/V, so the write happens before the attention and the ring has window+1 slots: chunk i lands in slot
 // i mod (window+1) and physically overwrites chunk i-(window+1), which the list protocol had already dropped after
@@ -62,8 +62,7 @@ __global__ void __launch_bounds__(256) lvx_pack_kv_kernel(const bf16_t *__restri
         uint4 val = make_uint4(0, 0, 0, 0);
         if (src >= 0 && src < n) {
             const size_t so = (size_t)src * ld + (size_t)h * D + c * 8;
-            const uint4 kv = *reinterpret_cast<const uint4 *>(k + so);
-            *reinterpret_cast<uint4 *>(kp + ((size_t)h * cap + key) * D + c * 8) = kv;
+            if (k != nullptr) *reinterpret_cast<uint4 *>(kp + ((size_t)h * cap + key) * D + c * 8) = *reinterpret_cast<const uint4 *>(k + so);
             val = *reinterpret_cast<const uint4 *>(v + so);
         }
         *reinterpret_cast<uint4 *>(&vs[r * LDS_LD + c * 8]) = val;
@@ -138,6 +137,19 @@ __global__ void __launch_bounds__(256) lvx_widen_kernel(const uint4 *__restrict_
     }
 }
 
+// bf16 rows [n_rows][ld_src] -> fp32 rows [n_rows][ld_dst], 8 elements per thread (exact widening)
+__global__ void __launch_bounds__(256) lvx_widen_rows_kernel(const bf16_t *__restrict__ src, int64_t ld_src, float *__restrict__ dst,
+                                                             int64_t ld_dst, int n_rows, int chunks_per_row) {
+    const size_t total = (size_t)n_rows * chunks_per_row;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const size_t r = i / chunks_per_row, c = i % chunks_per_row;
+        const uint4 a = reinterpret_cast<const uint4 *>(src + r * ld_src)[c];
+        float4 *o = reinterpret_cast<float4 *>(dst + r * ld_dst) + 2 * c;
+        o[0] = make_float4(bf16_lo(a.x), bf16_hi(a.x), bf16_lo(a.y), bf16_hi(a.y));
+        o[1] = make_float4(bf16_lo(a.z), bf16_hi(a.z), bf16_lo(a.w), bf16_hi(a.w));
+    }
+}
+
 __global__ void __launch_bounds__(256) lvx_copy_rows_kernel(const bf16_t *__restrict__ src, int64_t ld_src, bf16_t *__restrict__ dst,
                                                             int64_t ld_dst, int n_rows, int chunks_per_row) {
     const size_t total = (size_t)n_rows * chunks_per_row;
@@ -173,6 +185,15 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
     if (n_rows == 0) return LVX_OK;
     const size_t total = (size_t)n_rows * (row_elems / 8);
     hipLaunchKernelGGL(lvx_copy_rows_kernel, dim3(grid_for(total)), dim3(256), 0, stream, src, ld_src, dst, ld_dst, n_rows, row_elems / 8);
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_widen_rows(const bf16_t *src, int64_t ld_src, float *dst, int64_t ld_dst, int n_rows, int row_elems,
+                                   hipStream_t stream) {
+    if (n_rows == 0) return LVX_OK;
+    const size_t total = (size_t)n_rows * (row_elems / 8);
+    hipLaunchKernelGGL(lvx_widen_rows_kernel, dim3(grid_for(total)), dim3(256), 0, stream, src, ld_src, dst, ld_dst, n_rows, row_elems / 8);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
@@ -332,7 +353,7 @@ extern "C" lvx_status_t lvx_kvcache_set_sink(lvx_kvcache_t *c, int32_t layer, co
 // ---- Rolling RoPE / adaptive attention sink (paper Sec. 3.3, Appendix D) ------------------------------------------
 extern "C" size_t lvx_sink_source_bytes(const lvx_cache_desc_t *desc) {
     if (check_desc(desc) != LVX_OK) return 0;
-    return (size_t)desc->n_layers * desc->frame_h * desc->frame_w * desc->sink_frames * desc->n_heads * desc->head_dim * sizeof(bf16_t);
+    return (size_t)desc->n_layers * desc->frame_h * desc->frame_w * desc->sink_frames * desc->n_heads * desc->head_dim * sizeof(float);
 }
 
 extern "C" lvx_status_t lvx_kvcache_attach_sink_source(lvx_kvcache_t *c, void *dev_storage, size_t bytes) {
@@ -342,7 +363,19 @@ extern "C" lvx_status_t lvx_kvcache_attach_sink_source(lvx_kvcache_t *c, void *d
                 "sink source storage must be non-NULL and 256-byte aligned");
     const size_t need = lvx_sink_source_bytes(&c->desc);
     LVX_REQUIRE(bytes >= need, LVX_ERR_SHAPE, "sink source storage too small: %zu bytes given, %zu needed", bytes, need);
-    c->sink_src = (bf16_t *)dev_storage;
+    c->sink_src = (float *)dev_storage;
+    return LVX_OK;
+}
+
+// Shared tail of lvx_kvcache_reset_sink and of the sink warm-up: the layer's fp32 source is already in place; V goes to its
+// final place, the K rows of the sink segment stay as they are until the next rotation overwrites them.
+lvx_status_t lvx_sink_install_values(lvx_kvcache *c, int layer, const bf16_t *v, int64_t ld, hipStream_t stream) {
+    LVX_TRY(lvx_launch_pack_kv(nullptr, v, ld, c->sink_keys, c->desc.n_heads, c->desc.head_dim, c->cap_keys, 0,
+                               (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer), stream));
+    lvx_ring_state_t &s = c->state[layer];
+    s.sink_set = 1;
+    s.key_count = c->sink_keys + s.n_valid_chunks * c->chunk_keys;
+    c->sink_t[layer] = LVX_SINK_STALE;
     return LVX_OK;
 }
 
@@ -353,18 +386,10 @@ extern "C" lvx_status_t lvx_kvcache_reset_sink(lvx_kvcache_t *c, int32_t layer, 
     LVX_REQUIRE(c->sink_keys > 0, LVX_ERR_STATE, "this cache has no sink segment (sink_frames = 0)");
     LVX_REQUIRE(c->sink_src != nullptr, LVX_ERR_STATE, "no sink source storage attached (lvx_kvcache_attach_sink_source)");
     const int d = c->desc.n_heads * c->desc.head_dim;
-    st = lvx_launch_copy_rows((const bf16_t *)dev_k_src, ld, c->sink_src + (size_t)layer * c->sink_keys * d, d, c->sink_keys, d,
-                              (hipStream_t)stream);
-    if (st != LVX_OK) return st;
-    // V goes to its final place; the K rows receive the un-rotated source and are overwritten by the next rotation
-    st = lvx_launch_pack_kv((const bf16_t *)dev_k_src, (const bf16_t *)dev_v, ld, c->sink_keys, c->desc.n_heads, c->desc.head_dim,
-                            c->cap_keys, 0, (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer), (hipStream_t)stream);
-    if (st != LVX_OK) return st;
-    lvx_ring_state_t &s = c->state[layer];
-    s.sink_set = 1;
-    s.key_count = c->sink_keys + s.n_valid_chunks * c->chunk_keys;
-    c->sink_t[layer] = LVX_SINK_STALE;
-    return LVX_OK;
+    // the source is kept in fp32 (exact widening of the bf16 keys given here; the sink warm-up stores un-rounded fp32 keys)
+    LVX_TRY(lvx_launch_widen_rows((const bf16_t *)dev_k_src, ld, c->sink_src + (size_t)layer * c->sink_keys * d, d, c->sink_keys, d,
+                                  (hipStream_t)stream));
+    return lvx_sink_install_values(c, layer, (const bf16_t *)dev_v, ld, (hipStream_t)stream);
 }
 
 extern "C" lvx_status_t lvx_sink_rope_update(lvx_kvcache_t *c, const lvx_rope_desc_t *rope, int32_t layer, int32_t t_sink,
@@ -411,8 +436,9 @@ extern "C" lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *c, i
     LVX_REQUIRE(c->sink_src != nullptr && c->sink_t[layer] != LVX_SINK_STATIC, LVX_ERR_STATE, "layer %d has no sink source", layer);
     const int d = c->desc.n_heads * c->desc.head_dim;
     LVX_REQUIRE(lvx_aligned16(dev_k_src_out) && ld >= d && ld % 8 == 0, LVX_ERR_INVALID_ARG, "output must be 16-byte aligned, ld a multiple of 8 >= d");
-    return lvx_launch_copy_rows(c->sink_src + (size_t)layer * c->sink_keys * d, d, (bf16_t *)dev_k_src_out, ld, c->sink_keys, d,
-                                (hipStream_t)stream);
+    // fp32 rows copied as pairs of bf16-sized elements
+    return lvx_launch_copy_rows((const bf16_t *)(c->sink_src + (size_t)layer * c->sink_keys * d), 2 * (int64_t)d, (bf16_t *)dev_k_src_out,
+                                2 * ld, c->sink_keys, 2 * d, (hipStream_t)stream);
 }
 
 extern "C" lvx_status_t lvx_chunk_append_evict(lvx_kvcache_t *c, int32_t layer, const void *dev_k, const void *dev_v, int64_t ld,

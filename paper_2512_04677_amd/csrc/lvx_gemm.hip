@@ -1,5 +1,5 @@
 // bf16 MFMA GEMM for the DiT linears:  C[M][N] = epilogue(A[M][K] * W[N][K]^T), fp32 accumulate.
-// (The paper's "all linear projections in the DiT", Appendix C; shapes are the workload's.)
+// (The linears of the DiT blocks, Appendix C; shapes are the workload's.)
 //
 // Both operands have the contraction index contiguous in memory (activations [token][in], weights [out][in]), so both
 // stream global -> LDS as 16-byte chunks (direct-to-LDS loads, three 64-wide K slabs in flight) and are read back as direct
@@ -56,6 +56,8 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x4_t (&acc)[FM][FN], f32x4_
                 if (EPI == LVX_EPI_RESID_GATE) v = bf16_bits_to_f32(rp[j * 16]) + gt[j] * v;
                 if (EPI == LVX_EPI_RESID_GATE_F32)
                     cpf[j * 16] = rres[i][j][e] + gt[j] * v;
+                else if (EPI == LVX_EPI_STORE_F32)
+                    cpf[j * 16] = v;
                 else
                     cp[j * 16] = (bf16_t)(pack_bf16x2(v, 0.f) & 0xffffu);
             }
@@ -76,7 +78,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool CONV>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,
                         int M, int N, int K, const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n,
-                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int split_tn, lvx_conv_map_t cm) {
+                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int64_t ldc2, int N2, int split_tn, lvx_conv_map_t cm) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int FM = WTM / 16, FN = WTN / 16;  // 16 x 16 accumulator blocks per wave
@@ -102,11 +104,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     const int tm = first_m + in_band % band_m;
     int tn = in_band / band_m;
     // two projections of the same activations in one launch (tiles_n counts both): column tiles past split_tn belong to the
-    // second weight matrix and its own output
-    if (tn >= split_tn) {
+    // second weight matrix and its own output (its own width and row stride)
+    const bool second = tn >= split_tn;
+    if (second) {
         tn -= split_tn;
         W = W2;
         C = C2;
+        ldc = ldc2;
+        N = N2;
     }
 
     const int tid = threadIdx.x;
@@ -265,23 +270,30 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     // no DMA may still be in flight when the workgroup releases its LDS
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    lvx_gemm_epilogue<FM, FN, EPI>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+    if (EPI == LVX_EPI_DUAL_F32_BF16) {  // first projection stored in fp32, second in bf16 (workgroup-uniform branch)
+        if (second)
+            lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+        else
+            lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE_F32>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+    } else {
+        lvx_gemm_epilogue<FM, FN, EPI>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+    }
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool CONV = false>
 lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, bf16_t *C, int64_t ldc, int M, int N, int K, int epi,
                     const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const bf16_t *W2 = nullptr, bf16_t *C2 = nullptr,
-                    const lvx_conv_map_t *conv = nullptr) {
+                    int64_t ldc2 = 0, int N2 = 0, const lvx_conv_map_t *conv = nullptr) {
     lvx_conv_map_t cm = {};
     if (conv != nullptr) cm = *conv;
     const int split_tn = W2 != nullptr ? (N + BN - 1) / BN : 0x7fffffff;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (W2 != nullptr ? 2 : 1) * ((N + BN - 1) / BN);
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN + (W2 != nullptr ? (N2 + BN - 1) / BN : 0);
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
     hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_, CONV>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
-                       R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, split_tn, cm)
+                       R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, ldc2, N2, split_tn, cm)
     if (epi == LVX_EPI_STORE) {
         LVX_GEMM_LAUNCH(LVX_EPI_STORE);
     } else if (epi == LVX_EPI_GELU_TANH) {
@@ -292,6 +304,10 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
         LVX_GEMM_LAUNCH(LVX_EPI_RESID_GATE_F32);
     } else if (epi == LVX_EPI_BIAS) {
         LVX_GEMM_LAUNCH(LVX_EPI_BIAS);
+    } else if (epi == LVX_EPI_STORE_F32) {
+        LVX_GEMM_LAUNCH(LVX_EPI_STORE_F32);
+    } else if (epi == LVX_EPI_DUAL_F32_BF16) {
+        LVX_GEMM_LAUNCH(LVX_EPI_DUAL_F32_BF16);
     } else {
         LVX_GEMM_LAUNCH(LVX_EPI_BIAS_SILU);
     }
@@ -302,16 +318,37 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
 
 }  // namespace
 
-// C1 = A W1^T and C2 = A W2^T (same shapes and strides) in one launch: two small-M projections of the same input fill the chip
-// together where each alone leaves most of it idle (the context's K and V projections: 100 tiles each on 256 CUs).
-lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
-                                    int64_t ldc, int M, int N, int K, hipStream_t stream) {
-    LVX_REQUIRE(A && W1 && W2 && C1 && C2, LVX_ERR_INVALID_ARG, "linear pair: NULL pointer");
-    LVX_REQUIRE(K % BK == 0 && N % 8 == 0 && lda >= K && ldw >= K && ldc >= N, LVX_ERR_SHAPE, "linear pair: bad shape");
-    LVX_REQUIRE((uint64_t)M * (uint64_t)lda * 2 < (1ull << 32) && (uint64_t)N * (uint64_t)ldw * 2 < (1ull << 32), LVX_ERR_SHAPE,
+// C1 = A W1^T ([M][N1]) and C2 = A W2^T ([M][N2]) in one launch (same K and weight row stride).  Two uses: two small-M
+// projections of the same input fill the chip together where each alone leaves most of it idle (the context's K and V
+// projections: 100 tiles each on 256 CUs); and the fused QKV projection with its q | k columns stored in fp32 (they go on to
+// the RMSNorm + RoPE kernel, which rounds to bf16 once, after the rotation) and its v columns in bf16.
+static lvx_status_t check_dual(const void *A, int64_t lda, const void *W1, const void *W2, int64_t ldw, const void *C1, int64_t ldc1,
+                               const void *C2, int64_t ldc2, int M, int N1, int N2, int K) {
+    LVX_REQUIRE(A && W1 && W2 && C1 && C2, LVX_ERR_INVALID_ARG, "linear dual: NULL pointer");
+    LVX_REQUIRE(lvx_aligned16(A) && lvx_aligned16(W1) && lvx_aligned16(W2) && lvx_aligned16(C1) && lvx_aligned16(C2), LVX_ERR_INVALID_ARG,
+                "pointers must be 16-byte aligned");
+    LVX_REQUIRE(M >= 0 && N1 > 0 && N2 > 0 && K > 0 && K % BK == 0 && N1 % 8 == 0 && N2 % 8 == 0, LVX_ERR_SHAPE,
+                "linear dual: M %d, N1 %d, N2 %d, K %d (K %% 64 == 0, N %% 8 == 0)", M, N1, N2, K);
+    LVX_REQUIRE(lda >= K && lda % 8 == 0 && ldw >= K && ldw % 8 == 0 && ldc1 >= N1 && ldc2 >= N2, LVX_ERR_SHAPE, "bad leading dimension");
+    const uint64_t n_max = (uint64_t)(N1 > N2 ? N1 : N2);
+    LVX_REQUIRE((uint64_t)M * (uint64_t)lda * 2 < (1ull << 32) && n_max * (uint64_t)ldw * 2 < (1ull << 32), LVX_ERR_SHAPE,
                 "operand larger than 4 GiB (32-bit byte offsets inside the kernel)");
+    return LVX_OK;
+}
+
+lvx_status_t lvx_launch_linear_dual(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, void *C1, int64_t ldc1,
+                                    int c1_is_f32, bf16_t *C2, int64_t ldc2, int M, int N1, int N2, int K, hipStream_t stream) {
+    LVX_TRY(check_dual(A, lda, W1, W2, ldw, C1, ldc1, C2, ldc2, M, N1, N2, K));
     if (M == 0) return LVX_OK;
-    return launch<128, 256, 2, 4>(A, lda, W1, ldw, C1, ldc, M, N, K, (int)LVX_EPI_STORE, nullptr, 0, nullptr, stream, W2, C2);
+    return launch<128, 256, 2, 4>(A, lda, W1, ldw, (bf16_t *)C1, ldc1, M, N1, K, c1_is_f32 ? (int)LVX_EPI_DUAL_F32_BF16 : (int)LVX_EPI_STORE, nullptr,
+                                  0, nullptr, stream, W2, C2, ldc2, N2);
+}
+
+extern "C" lvx_status_t lvx_linear_dual(const void *dev_a, int64_t lda, const void *dev_w1, const void *dev_w2, int64_t ldw, void *dev_c1,
+                                        int64_t ldc1, int32_t c1_is_f32, void *dev_c2, int64_t ldc2, int32_t M, int32_t N1, int32_t N2,
+                                        int32_t K, lvx_stream_t stream) {
+    return lvx_launch_linear_dual((const bf16_t *)dev_a, lda, (const bf16_t *)dev_w1, (const bf16_t *)dev_w2, ldw, dev_c1, ldc1, c1_is_f32,
+                                  (bf16_t *)dev_c2, ldc2, M, N1, N2, K, (hipStream_t)stream);
 }
 
 // Implicit-GEMM 3x3x3 convolution: rows = output pixels, K = 27 taps x C channels gathered from the padded volume P.
@@ -320,7 +357,7 @@ lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, con
                                   bf16_t *Y, int64_t ldy, int M, int N, hipStream_t stream) {
     const int K = 27 * cm.C;
     return launch<256, 128, 4, 2, true>(P, 0, Wt, ldw, Y, ldy, M, N, K, act ? (int)LVX_EPI_BIAS_SILU : (int)LVX_EPI_BIAS, nullptr, 0, bias, stream,
-                                        nullptr, nullptr, &cm);
+                                        nullptr, nullptr, 0, 0, &cm);
 }
 
 extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64_t ldw, void *dev_c, int64_t ldc, int32_t M,
@@ -335,7 +372,7 @@ extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *d
     LVX_REQUIRE(lda >= K && lda % 8 == 0 && ldw >= K && ldw % 8 == 0 && ldc >= N, LVX_ERR_SHAPE, "bad leading dimension");
     LVX_REQUIRE((uint64_t)M * (uint64_t)lda * 2 < (1ull << 32) && (uint64_t)N * (uint64_t)ldw * 2 < (1ull << 32), LVX_ERR_SHAPE,
                 "operand larger than 4 GiB (32-bit byte offsets inside the kernel)");
-    LVX_REQUIRE((int)epi >= (int)LVX_EPI_STORE && (int)epi <= (int)LVX_EPI_BIAS_SILU, LVX_ERR_INVALID_ARG, "unknown epilogue %d", (int)epi);
+    LVX_REQUIRE((int)epi >= (int)LVX_EPI_STORE && (int)epi <= (int)LVX_EPI_STORE_F32, LVX_ERR_INVALID_ARG, "unknown epilogue %d", (int)epi);
     if (epi == LVX_EPI_RESID_GATE || epi == LVX_EPI_RESID_GATE_F32) {
         LVX_REQUIRE(dev_resid != nullptr, LVX_ERR_INVALID_ARG, "residual epilogue needs a residual pointer");
         LVX_REQUIRE(ldr >= N, LVX_ERR_SHAPE, "bad residual leading dimension");

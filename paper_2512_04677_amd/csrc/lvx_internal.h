@@ -59,7 +59,7 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
 }
 // direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane
 __device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
 }
 
 // ---- cache handle (host) ----------------------------------------------------------------------
@@ -70,7 +70,7 @@ struct lvx_kvcache {
     bf16_t *k_base;                                    // [layer][head][cap_keys][D]
     bf16_t *vt_base;                                   // [layer][head][cap_keys/64][D][64]
     lvx_ring_state_t *state;                           // [n_layers]
-    bf16_t *sink_src;                                  // [layer][sink_keys][d] un-rotated sink keys, NULL until attached
+    float *sink_src;                                   // [layer][sink_keys][d] un-rotated sink keys in fp32, NULL until attached
     int32_t *sink_t;                                   // [n_layers] temporal index the sink keys are rotated to; < 0: see LVX_SINK_*
 };
 #define LVX_SINK_STATIC (-2)  /* keys were given already rotated (lvx_kvcache_set_sink) or there is no sink yet */
@@ -80,7 +80,7 @@ static inline const bf16_t *lvx_cache_k(const lvx_kvcache *c, int layer) { retur
 static inline const bf16_t *lvx_cache_vt(const lvx_kvcache *c, int layer) { return c->vt_base + (size_t)layer * c->layer_k_elems; }
 
 // ---- internal launchers (all enqueue on `stream`, arguments already validated) ----------------
-// Token-major K/V rows [n][ld] -> packed K [H][cap][D] rows key0.. and V^T tiles [H][cap/64][D][64].
+// Token-major K/V rows [n][ld] -> packed K [H][cap][D] rows key0.. and V^T tiles [H][cap/64][D][64] (k NULL: values only).
 lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, int n, int H, int D, int cap, int key0,
                                 bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream);
 // Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
@@ -96,11 +96,18 @@ lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, cons
 // Strided row copy [n_rows][row_elems] (row_elems % 8 == 0), bit-exact.
 lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst, int64_t ld_dst, int n_rows, int row_elems,
                                   hipStream_t stream);
-// RoPE of token-major rows written straight into packed K rows [H][cap][D] starting at key 0 (no norm), for n_layers
+// RoPE of token-major fp32 rows written straight into packed K rows [H][cap][D] starting at key 0 (no norm), for n_layers
 // consecutive layers in one launch (strides in elements between the layers' sources and between their packed K arrays).
-lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
+lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// y = x / sqrt(mean(x^2) + eps) * g on fp32 rows, fp32 out, no rounding (g NULL: plain copy): the sink warm-up's un-rotated keys.
+lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x, int64_t ld_in, const float *g, int n_tokens, float *y,
+                                    int64_t ld_out, hipStream_t stream);
+lvx_status_t lvx_launch_widen_rows(const bf16_t *src, int64_t ld_src, float *dst, int64_t ld_dst, int n_rows, int row_elems,
+                                   hipStream_t stream);
+// the layer's fp32 sink source is in place: install its values, mark its keys stale (they await the next rotation)
+lvx_status_t lvx_sink_install_values(lvx_kvcache *c, int layer, const bf16_t *v, int64_t ld, hipStream_t stream);
 // Row addressing of the GEMM's A operand for an implicit-GEMM 3x3x3 convolution over a zero-padded channels-last volume
 // P[frame][H+2][W+2][C]: output pixel m = (t, y, x) reads, for tap (dt, dy, dx), the C channels at P[t+dt][y+dy][x+dx].
 // K runs tap-major (27 taps x C channels); C % 64 == 0 so that a 64-wide K slab lies inside one tap.
@@ -113,9 +120,11 @@ struct lvx_conv_map_t {
 };
 lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, const bf16_t *Wt, int64_t ldw, const float *bias, int act,
                                   bf16_t *Y, int64_t ldy, int M, int N, hipStream_t stream);
-// C1 = A W1^T, C2 = A W2^T in one launch (bf16, plain store).
-lvx_status_t lvx_launch_linear_pair(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, bf16_t *C1, bf16_t *C2,
-                                    int64_t ldc, int M, int N, int K, hipStream_t stream);
+// C1[M][N1] = A W1^T (bf16, or fp32 if c1_is_f32), C2[M][N2] = A W2^T (bf16) in one launch, plain store.
+lvx_status_t lvx_launch_linear_dual(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, void *C1, int64_t ldc1,
+                                    int c1_is_f32, bf16_t *C2, int64_t ldc2, int M, int N1, int N2, int K, hipStream_t stream);
+// internal epilogue id of the GEMM kernel: first projection of a dual launch stored in fp32, second in bf16
+#define LVX_EPI_DUAL_F32_BF16 100
 // Per-tensor dynamic FP8 quantisation of a bf16 matrix.  The amax is collected in an array of LVX_AMAX_SLOTS fp32 bit patterns
 // (256 bytes, zero before the producers write): either by lvx_launch_fp8_amax, or by the kernel that produced x (attention,
 // the GELU epilogue of an FP8 linear), which saves the extra pass.  (The LayerNorm kernel does not: its one-row waves would

@@ -25,10 +25,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int ROWS_PER_WG = 4;
 
-// CPL = 16-byte chunks per lane (row length <= 64*8*CPL)
-template <int CPL>
+// CPL = 8-element chunks per lane (row length <= 64*8*CPL); F32IN: the input rows are fp32 (ld_in, batch_stride_in in fp32
+// elements), else bf16; F32OUT (norm-only form, needs F32IN): the result is stored in fp32, token-major, un-rounded
+template <int CPL, bool F32IN, bool F32OUT = false>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
-    lvx_rope_norm_kernel(const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in,
+    lvx_rope_norm_kernel(const void *q_in, const void *k_in, int64_t ld_in,
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
                          bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
                          float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out) {
@@ -61,23 +62,31 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
 
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
-        const bf16_t *in = which == 0 ? q_in : k_in;
+        const void *in = which == 0 ? q_in : k_in;
         bf16_t *outp = which == 0 ? q_out : k_out;
         const float *g = which == 0 ? g_q : g_k;
         if (in == nullptr) continue;
-        const u32x4_t *src = reinterpret_cast<const u32x4_t *>(in + (size_t)batch * batch_stride_in + (size_t)token * ld_in);
-        u32x4_t x[CPL];
+        const size_t row_off = (size_t)batch * batch_stride_in + (size_t)token * ld_in;
+        float x[CPL][8];
         float ss = 0.f;
 #pragma unroll
         for (int j = 0; j < CPL; ++j) {
             const int c = lane + 64 * j;
             if (c < n_chunks) {
-                x[j] = src[c];
+                if (F32IN) {
+                    const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(in) + row_off) + 2 * c;
+                    const float4 a = src[0], b = src[1];
+                    x[j][0] = a.x, x[j][1] = a.y, x[j][2] = a.z, x[j][3] = a.w, x[j][4] = b.x, x[j][5] = b.y, x[j][6] = b.z, x[j][7] = b.w;
+                } else {
+                    const u32x4_t v = reinterpret_cast<const u32x4_t *>(reinterpret_cast<const bf16_t *>(in) + row_off)[c];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float a = bf16_lo(x[j][e]), b = bf16_hi(x[j][e]);
-                    ss += a * a + b * b;
+                    for (int e = 0; e < 4; ++e) {
+                        x[j][2 * e] = bf16_lo(v[e]);
+                        x[j][2 * e + 1] = bf16_hi(v[e]);
+                    }
                 }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss += x[j][e] * x[j][e];
             }
         }
         float rinv = 1.f;
@@ -98,11 +107,17 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                     g1 = *reinterpret_cast<const float4 *>(g + c * 8 + 4);
                 }
                 const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                if (F32OUT) {  // normalised, un-rotated, un-rounded
+                    float4 *o = reinterpret_cast<float4 *>(reinterpret_cast<float *>(outp) + (size_t)token * ld_out) + 2 * c;
+                    o[0] = make_float4(x[j][0] * rinv * gg[0], x[j][1] * rinv * gg[1], x[j][2] * rinv * gg[2], x[j][3] * rinv * gg[3]);
+                    o[1] = make_float4(x[j][4] * rinv * gg[4], x[j][5] * rinv * gg[5], x[j][6] * rinv * gg[6], x[j][7] * rinv * gg[7]);
+                    continue;
+                }
                 u32x4_t y;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float a = bf16_lo(x[j][e]) * rinv * gg[2 * e];
-                    const float b = bf16_hi(x[j][e]) * rinv * gg[2 * e + 1];
+                    const float a = x[j][2 * e] * rinv * gg[2 * e];
+                    const float b = x[j][2 * e + 1] * rinv * gg[2 * e + 1];
                     y[e] = pack_bf16x2(a * c4[e] - b * s4[e], a * s4[e] + b * c4[e]);
                 }
                 *reinterpret_cast<u32x4_t *>(dst + (size_t)(c / cph) * ld_out_head + (c % cph) * 8) = y;
@@ -201,9 +216,10 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
     return LVX_OK;
 }
 
-static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
+static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, const void *k_in, int64_t ld_in, const float *g_q,
                                 const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
-                                hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0) {
+                                hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0,
+                                bool f32_in = false) {
     const int d = desc->n_heads * desc->head_dim;
     rope_table_t tab;
     for (int p = 0; p < 64; ++p) {
@@ -220,24 +236,33 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const bf16_t *q_in,
     }
     const dim3 grid((unsigned)(((int64_t)n_tokens * n_batch + ROWS_PER_WG - 1) / ROWS_PER_WG)), block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
-#define LVX_ROPE_LAUNCH(CPL)                                                                                                     \
-    hipLaunchKernelGGL(lvx_rope_norm_kernel<CPL>, grid, block, 0, stream, q_in, k_in, ld_in, g_q, g_k, n_tokens, t0, q_out, k_out, \
+#define LVX_ROPE_LAUNCH(CPL, F32)                                                                                                \
+    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, F32>), grid, block, 0, stream, q_in, k_in, ld_in, g_q, g_k, n_tokens, t0, q_out, k_out, \
                        ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab, n_batch,  \
                        batch_stride_in, batch_stride_out)
-    if (cpl <= 2)
-        LVX_ROPE_LAUNCH(2);
-    else if (cpl <= 10)
-        LVX_ROPE_LAUNCH(10);
-    else
-        LVX_ROPE_LAUNCH(16);
+    if (f32_in) {
+        if (cpl <= 2)
+            LVX_ROPE_LAUNCH(2, true);
+        else if (cpl <= 10)
+            LVX_ROPE_LAUNCH(10, true);
+        else
+            LVX_ROPE_LAUNCH(16, true);
+    } else {
+        if (cpl <= 2)
+            LVX_ROPE_LAUNCH(2, false);
+        else if (cpl <= 10)
+            LVX_ROPE_LAUNCH(10, false);
+        else
+            LVX_ROPE_LAUNCH(16, false);
+    }
 #undef LVX_ROPE_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
 
-extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
-                                   const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
-                                   void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
+static lvx_status_t rope3d_entry(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in, bool f32_in,
+                                 const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
+                                 void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     LVX_REQUIRE(dev_q_in != nullptr || dev_k_in != nullptr, LVX_ERR_INVALID_ARG, "both q and k are NULL");
@@ -252,18 +277,54 @@ extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_
     LVX_REQUIRE(n_tokens >= 0 && t0 >= 0, LVX_ERR_INVALID_ARG, "n_tokens and t0 must be non-negative");
     if (n_tokens == 0) return LVX_OK;
 
-    return launch_rope(desc, (const bf16_t *)dev_q_in, (const bf16_t *)dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out,
-                       (bf16_t *)dev_k_out, ld_out, desc->head_dim, (hipStream_t)stream);
+    return launch_rope(desc, dev_q_in, dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out, (bf16_t *)dev_k_out, ld_out,
+                       desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in);
 }
 
-lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const bf16_t *src, int64_t ld_src, int n_tokens, int t0,
+extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
+                                   const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
+                                   void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
+    return rope3d_entry(desc, dev_q_in, dev_k_in, ld_in, false, dev_g_q, dev_g_k, n_tokens, t0, dev_q_out, dev_k_out, ld_out, stream);
+}
+
+extern "C" lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc, const float *dev_q_in, const float *dev_k_in, int64_t ld_in,
+                                         const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
+                                         void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
+    return rope3d_entry(desc, dev_q_in, dev_k_in, ld_in, true, dev_g_q, dev_g_k, n_tokens, t0, dev_q_out, dev_k_out, ld_out, stream);
+}
+
+lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     if (n_tokens == 0 || n_layers == 0) return LVX_OK;
     return launch_rope(desc, nullptr, src, ld_src, nullptr, nullptr, n_tokens, t0, nullptr, k_packed, desc->head_dim,
-                       (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst);
+                       (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst, true);
+}
+
+lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x, int64_t ld_in, const float *g, int n_tokens, float *y,
+                                    int64_t ld_out, hipStream_t stream) {
+    lvx_status_t st = check_rope_desc(desc);
+    if (st != LVX_OK) return st;
+    if (n_tokens == 0) return LVX_OK;
+    const int d = desc->n_heads * desc->head_dim;
+    rope_table_t tab = {};
+    const dim3 grid((unsigned)((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG)), block(64 * ROWS_PER_WG);
+    const int cpl = (d / 8 + 63) / 64;
+#define LVX_NORM32_LAUNCH(CPL)                                                                                                     \
+    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, true, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, \
+                       (const float *)nullptr, g, n_tokens, 0, (bf16_t *)nullptr, (bf16_t *)y, ld_out, (int64_t)desc->head_dim, d,    \
+                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0)
+    if (cpl <= 2)
+        LVX_NORM32_LAUNCH(2);
+    else if (cpl <= 10)
+        LVX_NORM32_LAUNCH(10);
+    else
+        LVX_NORM32_LAUNCH(16);
+#undef LVX_NORM32_LAUNCH
+    LVX_CHECK_HIP(hipGetLastError());
+    return LVX_OK;
 }
 
 lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,

@@ -108,6 +108,12 @@ def test_error_paths_without_a_device():
     assert lib.lvx_linear(p, 128, p, 128, p, 64, 4, 64, 128, 2, None, 0, None, None) == 1      # residual missing
     assert lib.lvx_linear(C.c_void_p(4100), 128, p, 128, p, 64, 4, 64, 128, 0, None, 0, None, None) == 1
     assert lib.lvx_linear(None, 128, p, 128, p, 64, 4, 64, 128, 0, None, 0, None, None) == 1
+    # two projections in one launch
+    assert lib.lvx_linear_dual(p, 128, p, p, 128, p, 64, 1, p, 64, 4, 64, 64, 100, None) == 2    # K % 64
+    assert lib.lvx_linear_dual(p, 128, p, p, 128, p, 64, 1, p, 64, 4, 64, 60, 128, None) == 2    # N2 % 8
+    assert lib.lvx_linear_dual(p, 128, p, p, 128, p, 56, 0, p, 64, 4, 64, 64, 128, None) == 2    # ldc1 < N1
+    assert lib.lvx_linear_dual(p, 128, p, None, 128, p, 64, 0, p, 64, 4, 64, 64, 128, None) == 1
+    assert lib.lvx_linear_dual(p, 128, p, p, 128, C.c_void_p(4104), 64, 1, p, 64, 4, 64, 64, 128, None) == 1
     # rope descriptor checks
     r = lvx.rope_desc(40, 128, (44, 42, 40), 1e4, 30, 52)
     assert lib.lvx_rope3d(C.byref(r), p, p, 5120, None, None, 4, 0, p, p, 5120, None) == 2
@@ -115,6 +121,8 @@ def test_error_paths_without_a_device():
     assert lib.lvx_rope3d(C.byref(r), p, p, 5000, None, None, 4, 0, p, p, 5120, None) == 2       # ld < d
     assert lib.lvx_rope3d(C.byref(r), None, None, 5120, None, None, 4, 0, None, None, 5120, None) == 1
     assert lib.lvx_rope3d(C.byref(r), p, None, 5120, None, None, 4, 0, None, None, 5120, None) == 1
+    assert lib.lvx_rope3d_f32in(C.byref(r), p, p, 5000, None, None, 4, 0, p, p, 5120, None) == 2
+    assert lib.lvx_rope3d_f32in(C.byref(r), p, None, 10240, None, None, 4, 0, None, p, 5120, None) == 1
     assert lib.lvx_layernorm_modulate(p, 5120, None, None, 1e-6, 4, 5124, p, 5120, None) == 2
     # stage / workspace
     blocks = (lvx.BlockWeights * 1)()
@@ -133,7 +141,7 @@ def test_sink_management_host_checks():
     lib = lvx.load()
     d = desc14b()
     # un-rotated sink keys of all layers: 40 layers x 1560 tokens x 5120 channels x bf16 = 639 MB
-    assert lvx.load().lvx_sink_source_bytes(C.byref(d)) == 40 * 1560 * 5120 * 2
+    assert lvx.load().lvx_sink_source_bytes(C.byref(d)) == 40 * 1560 * 5120 * 4      # kept in fp32
     assert lvx.load().lvx_sink_source_bytes(C.byref(desc14b(head_dim=96))) == 0
     p = C.c_void_p(4096)
     r = lvx.rope_desc(40, 128, (44, 42, 42), 1e4, 30, 52)
@@ -171,7 +179,10 @@ def test_fp8_entry_points_host_checks():
     castb = C.cast(blocks, C.POINTER(lvx.BlockWeights))
     ok = lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 128, 13824 + 128)
     plain = lvx.Stage(1, 13824, 0, 0, r, castb)
-    assert lib.lvx_workspace_bytes(C.byref(ok), 4680, 544) >= lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) + 4680 * 13824
+    # a bf16 stage holds the fp32 q | k columns of its QKV projection (4680 x (2 x 5120 + 32) fp32), an FP8 stage holds the
+    # quantised input activation of the widest linear (4680 x 13824 bytes) and the quantised context instead
+    qk32 = 4680 * (2 * 5120 + 32) * 4
+    assert lib.lvx_workspace_bytes(C.byref(ok), 4680, 544) >= lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) - qk32 - 256 + 4680 * 13824
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824 + 64, 0, 0, r, castb, cast8, 0, 0)), 4680, 544) == 0
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 8, 0)), 4680, 544) == 0
 

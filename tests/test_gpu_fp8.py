@@ -78,22 +78,26 @@ def test_linear_fp8_epilogues(lvx, M, N, K):
 # step / sqrt(12): the flips alone are worth about 0.7 of the quantisation noise itself.  Measured on these configurations:
 # the FP8 oracle differs from the exact oracle by 4.4 % of the output RMS (that is the method's own quantisation noise), the
 # GPU differs from the FP8 oracle by 3.0 % (mean-abs 2.4 %), and from the exact oracle by 4.4 % again.
-# Gates: (1) the bf16 gates times FP8_CHAIN = 16 (mean-abs 3.2e-2, max-abs 0.32 of the output RMS); (2) the GPU is closer to
-# the FP8 oracle than 0.9 x the FP8 oracle is to the exact one, i.e. the discrepancy stays below the noise the method accepts;
-# (3) the GPU is no further from the exact oracle than 1.15 x the FP8 oracle is.  The weights get magnitudes that differ by
-# factors 2 .. 16 between tensors, so a scale or weight taken from the wrong tensor fails all three by a wide margin; the
-# codes themselves and every single linear are gated exactly / at x1 above.
-FP8_CHAIN = 16.0
-
-
+# Gates, all in units of e_q = rms(FP8 oracle - exact oracle), the quantisation noise the method itself accepts (no multiple of
+# the bf16 numbers is used: those are sized for bf16 roundings, which are 30 times smaller than an E4M3 step):
+# (1) rms(GPU - FP8 oracle) <= 0.9 e_q: the discrepancy stays below that noise (the flip model predicts 0.7; this also bounds
+#     the mean-abs error, which never exceeds the rms);
+# (2) rms(GPU - exact oracle) <= 1.15 e_q: the GPU is no further from the exact result than the FP8 oracle is;
+# (3) max-abs(GPU - FP8 oracle) <= 6 e_q: an output element sums thousands of independent flip errors, so 6 standard deviations
+#     bound the largest of ~1e5 elements (measured 3.5 .. 4.5).
+# The weights get magnitudes that differ by factors 2 .. 16 between tensors, so a scale or weight taken from the wrong tensor
+# fails all three by a wide margin; the codes themselves and every single linear are gated exactly / at the bf16 numbers above.
 def assert_fp8_close(gpu, ref8, refx, what):
-    assert_close(gpu, ref8, what, relative_to_rms=True, chain=FP8_CHAIN)
     g = S.to_f64(gpu).reshape(ref8.shape)
+    assert np.isfinite(g).all(), what
     rms = lambda a: math.sqrt(float((a ** 2).mean()))
     e_gpu, e_q, e_x = rms(g - ref8), rms(ref8 - refx), rms(g - refx)
-    print("%s: rms(gpu - fp8 oracle) %.3e, rms(fp8 oracle - exact) %.3e, rms(gpu - exact) %.3e" % (what, e_gpu, e_q, e_x), flush=True)
+    mx = float(np.abs(g - ref8).max())
+    print("%s: rms(gpu - fp8 oracle) %.3e, rms(fp8 oracle - exact) %.3e, rms(gpu - exact) %.3e, max-abs(gpu - fp8 oracle) %.2f e_q"
+          % (what, e_gpu, e_q, e_x, mx / e_q), flush=True)
     assert e_gpu <= 0.9 * e_q, (what, e_gpu, e_q)
     assert e_x <= 1.15 * e_q, (what, e_x, e_q)
+    assert mx <= 6.0 * e_q, (what, mx, e_q)
 
 
 def fp8_stage_setup(lvx, preset, n_layers, tag):

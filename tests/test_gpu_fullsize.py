@@ -14,7 +14,7 @@ import torch
 
 import lvx_synth as S
 from oracle import lvx_oracle as O
-from test_gpu_parity import CHAIN, DEV, assert_close, dims, make_cache
+from test_gpu_parity import BF16_OUT_LINK, DEV, assert_close, assert_same_bf16, dims, make_cache
 
 pytestmark = pytest.mark.gpu
 P = S.PRESETS["attn14b"]
@@ -123,16 +123,19 @@ def test_config3_streaming_loop_100_steps(lvx):
 def test_config4_dit_block_sampled_rows(lvx):
     """One full-size DiT block (weights N(0, 0.02)), cache pre-filled with 4 chunks: the block's output rows for sampled
     tokens against the oracle's row form, which is handed the keys the GPU cache holds; the cache rows the block wrote
-    for those tokens are checked against the oracle's own K-hat / V."""
+    for those tokens are checked against the oracle's own K-hat / V.  All at the stated numbers: K-hat absolutely (unit RMS),
+    V and the residual stream in units of their RMS (V = u W_v^T is not normalised, RMS 1.44).  The fp32-stream entry point
+    carries the gate; the bf16 one must return its exact narrowing."""
     d, sink_n, n = dims(P)
     H, D, W = P["n_heads"], P["head_dim"], P["window"]
     w = S.block_weights(d, P["ffn"], 0, "cfg4", std=0.02, device=DEV, on_device_draw=True, row_pad=64)   # padded rows, as bench.py
     rope = lvx.rope_desc(H, D, P["rope_axes"], 10000.0, P["frame_h"], P["frame_w"])
     stage = lvx.StageHandle([w], rope, P["ffn"], ldw_d=d + 64, ldw_ffn=P["ffn"] + 64)
-    cache = make_cache(lvx, P)
-    lvx.lvx_kvcache_set_sink(cache, 0, S.randn_bf16_device((sink_n, d), 2, 1.0, DEV), S.randn_bf16_device((sink_n, d), 3, 1.0, DEV))
-    for i in range(W):
-        lvx.lvx_chunk_append_evict(cache, 0, S.randn_bf16_device((n, d), 10 + i, 1.0, DEV), S.randn_bf16_device((n, d), 20 + i, 1.0, DEV), i)
+    cache, cache16 = make_cache(lvx, P), make_cache(lvx, P)
+    for c in (cache, cache16):
+        lvx.lvx_kvcache_set_sink(c, 0, S.randn_bf16_device((sink_n, d), 2, 1.0, DEV), S.randn_bf16_device((sink_n, d), 3, 1.0, DEV))
+        for i in range(W):
+            lvx.lvx_chunk_append_evict(c, 0, S.randn_bf16_device((n, d), 10 + i, 1.0, DEV), S.randn_bf16_device((n, d), 20 + i, 1.0, DEV), i)
     ws = torch.empty(lvx.lvx_workspace_bytes(stage, n, P["n_ctx"]), dtype=torch.uint8, device=DEV)
     x = S.randn_bf16_device((n, d), 31, 1.0, DEV)
     ctx = S.randn_bf16_device((P["n_ctx"], d), 32, 1.0, DEV)
@@ -143,9 +146,13 @@ def test_config4_dit_block_sampled_rows(lvx):
     rows_t = torch.as_tensor(rows, device=DEV)
     x_rows = S.to_f64(x[rows_t])
     t0 = 1 + 3 * W
-    lvx.lvx_dit_block(stage, 0, cache, x, ctx, mod6, W, t0, ws)
+    x32 = x.float()
+    lvx.lvx_dit_block_f32(stage, 0, cache, x32, ctx, mod6, W, t0, ws)
+    lvx.lvx_dit_block(stage, 0, cache16, x, ctx, mod6, W, t0, ws)
     torch.cuda.synchronize()
-    assert bool(torch.isfinite(x.float()).all())
+    assert bool(torch.isfinite(x32).all())
+    assert_same_bf16(x, x32.to(torch.bfloat16), "config 4: bf16 entry point = narrowing of the fp32 one")
+    assert torch.equal(cache.storage, cache16.storage)
     cap = sink_n + (W + 1) * n
     gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
     gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
@@ -156,20 +163,72 @@ def test_config4_dit_block_sampled_rows(lvx):
     ref, k_rows, v_rows = O.dit_block_rows(x_rows, pos, S.weights_to_f64(w), S.to_f64(gk).reshape(cap, H, D), S.to_f64(gv).reshape(cap, H, D),
                                            S.to_f64(ctx), S.to_f64(mod6), cfg)
     off = sink_n + (W % (W + 1)) * n
-    # K-hat went through three bf16-storing kernels (layernorm, QKV GEMM, rmsnorm+rope), V through two: chain gate
-    assert_close(gk[off + rows_t], k_rows.reshape(len(rows), d), "config 4 cached K-hat rows", chain=CHAIN)
-    assert_close(gv[off + rows_t], v_rows.reshape(len(rows), d), "config 4 cached V rows", chain=CHAIN)
-    assert_close(x[rows_t], ref, "config 4 block output rows", relative_to_rms=True, chain=CHAIN)
+    assert_close(gk[off + rows_t], k_rows.reshape(len(rows), d), "config 4 cached K-hat rows")
+    assert_close(gv[off + rows_t], v_rows.reshape(len(rows), d), "config 4 cached V rows", relative_to_rms=True)
+    assert_close(x32[rows_t], ref, "config 4 block output rows, fp32 stream", relative_to_rms=True)
+    assert_close(x[rows_t], ref, "config 4 block output rows, bf16 in/out", relative_to_rms=True, links=1.0 + BF16_OUT_LINK)
     cache.close()
+    cache16.close()
+
+
+@pytest.mark.parametrize("M,N,K,epi", [(4680, 15360, 5120, "store"), (4680, 13824, 5120, "gelu"), (4680, 5120, 5120, "resid_f32"),
+                                       (4680, 5120, 13824, "resid_f32"), (544, 5120, 5120, "dual")])
+def test_fullsize_linears_sampled_rows(lvx, M, N, K, epi):
+    """The stage's GEMM shapes with the padded row strides bench.py uses (activation and weight rows of in_features + 64
+    elements): QKV, FFN up (GELU), output / FFN down (fp32 gated residual), and the context's K | V pair."""
+    a = S.randn_bf16_device((M, K + 64), S.seed_of("fl_a", M, N, K), 1.0, DEV)[:, :K]
+    w = S.randn_bf16_device((N, K + 64), S.seed_of("fl_w", M, N, K), 0.02, DEV)[:, :K]
+    rows = sample_rows(M, 10, 13) if M >= 4680 else np.array([0, 1, 127, 128, 255, 256, 511, 512, 543])
+    rows_t = torch.as_tensor(rows, device=DEV)
+    ref = O.linear(S.to_f64(a[rows_t]), S.to_f64(w))
+    if epi == "store":
+        c = torch.empty((M, N + 64), dtype=torch.bfloat16, device=DEV)[:, :N]
+        lvx.lvx_linear(a, w, c, lvx.EPI_STORE)
+        torch.cuda.synchronize()
+        assert_close(c[rows_t], ref, "full-size linear %dx%dx%d" % (M, N, K), relative_to_rms=True)
+        # the same projection as the block runs it: q | k columns in fp32, v columns in bf16
+        d = N // 3
+        c32 = torch.empty((M, 2 * d + 32), dtype=torch.float32, device=DEV)[:, :2 * d]
+        cv = torch.empty((M, N + 64), dtype=torch.bfloat16, device=DEV)[:, 2 * d:N]
+        lvx.lvx_linear_dual(a, w[:2 * d], w[2 * d:], c32, cv)
+        torch.cuda.synchronize()
+        e = np.abs(S.to_f64(c32[rows_t]) - ref[:, :2 * d])
+        print("full-size QKV, fp32 q | k columns: max-abs %.3e" % e.max(), flush=True)
+        assert e.max() <= 1e-5 * math.sqrt(K)
+        assert torch.equal(cv, c[:, 2 * d:])
+    elif epi == "gelu":
+        c = torch.empty((M, N + 64), dtype=torch.bfloat16, device=DEV)[:, :N]
+        lvx.lvx_linear(a, w, c, lvx.EPI_GELU_TANH)
+        torch.cuda.synchronize()
+        assert_close(c[rows_t], O.gelu_tanh(ref), "full-size linear + GELU %dx%dx%d" % (M, N, K))
+    elif epi == "resid_f32":
+        r = torch.randn((M, N), dtype=torch.float32, device=DEV, generator=torch.Generator(device=DEV).manual_seed(5)) * 3.0
+        g = S.randn_f32((N,), 6, 0.2, 1.0, device=DEV)
+        want = S.to_f64(r[rows_t]) + S.to_f64(g) * ref
+        lvx.lvx_linear(a, w, r, lvx.EPI_RESID_GATE_F32, resid=r, gate=g)
+        torch.cuda.synchronize()
+        e = np.abs(S.to_f64(r[rows_t]) - want)
+        print("full-size linear + fp32 gated residual %dx%dx%d: max-abs %.3e" % (M, N, K, e.max()), flush=True)
+        assert e.max() <= 1e-5 * math.sqrt(K)
+    else:
+        w2 = S.randn_bf16_device((N, K + 64), S.seed_of("fl_w2", M, N, K), 0.02, DEV)[:, :K]       # same row stride as w
+        c = torch.empty((M, 2 * N + 64), dtype=torch.bfloat16, device=DEV)
+        lvx.lvx_linear_dual(a, w, w2, c[:, :N], c[:, N:2 * N])
+        torch.cuda.synchronize()
+        assert_close(c[rows_t][:, :N], ref, "context K projection (dual launch)", relative_to_rms=True)
+        assert_close(c[rows_t][:, N:2 * N], O.linear(S.to_f64(a[rows_t]), S.to_f64(w2)), "context V projection (dual launch)",
+                     relative_to_rms=True)
 
 
 def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
     """Full-size stage in the benchmark's launch configuration (40 blocks, 28 GB of weights with padded rows, sink installed
-    un-rotated and re-indexed before every forward), six chunks: warm-up key counts and, from chunk 4 on, the full ring of
-    24960 keys.  (a) lvx_denoise_stage must equal, bit for bit up to the last-place rounding of the Euler step, the chain
-    widen -> 40 x lvx_dit_block_f32 -> Euler run on a second cache; (b) in that chain, at chunks 0 and 5, layers 0, 20 and 39
-    are checked on sampled tokens against the oracle's row form, which is given the layer's fp32 input rows and the keys that
-    layer's cache holds; (c) both caches end bit-identical."""
+    un-rotated and re-indexed before every forward), twelve chunks: warm-up key counts, then the full ring of 24960 keys with
+    every slot overwritten twice (chunks 5..9 and 10, 11).  (a) lvx_denoise_stage must equal, bit for bit up to the last-place
+    rounding of the Euler step, the chain widen -> 40 x lvx_dit_block_f32 -> Euler run on a second cache; (b) in that chain, at
+    chunks 0, 5 and 11, layers 0, 20 and 39 are checked on sampled tokens against the oracle's row form, which is given the
+    layer's fp32 input rows and the keys that layer's cache holds (teacher-forced, links = 1); (c) at chunks 5 and 11 the oracle
+    also carries ITS OWN rows forward through layers 0..3 (only the visible keys are the GPU cache's): the drift of the chain,
+    gated with one link per layer; (d) both caches end bit-identical."""
     d, sink_n, n = dims(P)
     H, D, W = P["n_heads"], P["head_dim"], P["window"]
     L = 40
@@ -192,7 +251,8 @@ def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
     gk = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
     gv = torch.empty((cap, d), dtype=torch.bfloat16, device=DEV)
     dt = -0.25
-    for i in range(6):
+    DEPTH = 4
+    for i in range(12):
         x = S.randn_bf16_device((n, d), S.seed_of("cfg5_x", i), 1.0, DEV)
         ctx = S.randn_bf16_device((P["n_ctx"], d), S.seed_of("cfg5_ctx", i), 1.0, DEV)
         t0 = 1 + 3 * i
@@ -201,19 +261,27 @@ def test_config5_stage_40_layers_layerwise_and_bit_exact_chain(lvx):
         lvx.lvx_sink_rope_update(cache_b, rope, -1, t0 + 4)
         lvx.lvx_denoise_stage(stage, cache_a, xa, ctx, None, dt, i, t0, ws)
         h = x.float()
+        carry = S.to_f64(x[rows_t]) if i in (5, 11) else None          # the oracle's own rows, carried from layer to layer
+        pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
+        nk = sink_n + min(i + 1, W + 1) * n
         for l in range(L):
-            check = l in (0, 20, 39) and i in (0, 5)
-            h_in_rows = S.to_f64(h[rows_t]) if check else None
+            forced = l in (0, 20, 39) and i in (0, 5, 11)
+            drift = carry is not None and l < DEPTH
+            h_in_rows = S.to_f64(h[rows_t]) if forced else None
             lvx.lvx_dit_block_f32(stage, l, cache_b, h, ctx, None, i, t0, ws)
-            if not check:
+            if not (forced or drift):
                 continue
             lvx.lvx_kvcache_gather(cache_b, l, 0, cap, gk, gv)
             torch.cuda.synchronize()
-            nk = sink_n + min(i + 1, W + 1) * n
-            pos = tuple(p[rows] for p in O.token_positions(n, t0, P["frame_h"], P["frame_w"]))
-            ref, _, _ = O.dit_block_rows(h_in_rows, pos, S.weights_to_f64(layers[l]), S.to_f64(gk[:nk]).reshape(nk, H, D),
-                                         S.to_f64(gv[:nk]).reshape(nk, H, D), S.to_f64(ctx), None, cfg)
-            assert_close(h[rows_t], ref, "config 5 chunk %d layer %d output rows" % (i, l), relative_to_rms=True, chain=CHAIN)
+            w64 = S.weights_to_f64(layers[l])
+            k64, v64 = S.to_f64(gk[:nk]).reshape(nk, H, D), S.to_f64(gv[:nk]).reshape(nk, H, D)
+            if forced:
+                ref, _, _ = O.dit_block_rows(h_in_rows, pos, w64, k64, v64, S.to_f64(ctx), None, cfg)
+                assert_close(h[rows_t], ref, "config 5 chunk %d layer %d output rows" % (i, l), relative_to_rms=True)
+            if drift:
+                carry, _, _ = O.dit_block_rows(carry, pos, w64, k64, v64, S.to_f64(ctx), None, cfg)
+                assert_close(h[rows_t], carry, "config 5 chunk %d layers 0..%d, oracle rows carried forward" % (i, l), relative_to_rms=True,
+                             links=l + 1)
         torch.cuda.synchronize()
         want = (x.double() + dt * h.double()).to(torch.bfloat16)
         diff = (xa.view(torch.int16).int() - want.view(torch.int16).int()).abs()

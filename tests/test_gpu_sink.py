@@ -9,7 +9,7 @@ import torch
 
 import lvx_synth as S
 from oracle import lvx_oracle as O
-from test_gpu_parity import CHAIN, DEV, assert_close, dims, make_cache
+from test_gpu_parity import BF16_OUT_LINK, DEV, assert_close, assert_same_bf16, dims, make_cache
 
 pytestmark = pytest.mark.gpu
 
@@ -52,10 +52,10 @@ def test_reset_sink_and_rolling_update(lvx, preset):
     with pytest.raises(lvx.LvxError) as e:                 # stale sink keys are not attended to
         lvx.lvx_chunk_attention(cache, 1, q, 1 / math.sqrt(D), out)
     assert e.value.status == 3
-    back = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+    back = torch.empty((sink_n, d + 8), dtype=torch.float32, device=DEV)[:, :d]          # the source is kept in fp32
     lvx.lvx_kvcache_gather_sink_source(cache, 1, back)
     torch.cuda.synchronize()
-    assert torch.equal(back.view(torch.int16), k_src.contiguous().view(torch.int16))
+    assert torch.equal(back, k_src.float())
 
     model = O.RollingKVCache(W)
     model.set_sink_source(S.to_f64(k_src).reshape(sink_n, H, D), S.to_f64(v).reshape(sink_n, H, D))
@@ -129,15 +129,22 @@ def test_stage_with_sink_prefill_swap_and_rolling_index(lvx):
         lvx.lvx_sink_prefill(stage, cache, x_sink, ctx, mod6, t, ws, x_out)
         torch.cuda.synchronize()
         ref = O.sink_prefill(S.to_f64(x_sink), w64, models, S.to_f64(ctx), S.to_f64(mod6), t, cfg)
-        assert_close(x_out, ref, "prefill output", relative_to_rms=True, chain=CHAIN)
+        # The oracle is not re-seeded between the layers of this one call.  Layer 0's source, keys and values are gated at the
+        # stated numbers.  What lies deeper collects every block's own roundings plus, through the LayerNorm of each later
+        # block, each earlier block's error once more (this small stream's RMS stays near 1.5, so relative errors are not diluted
+        # as they are in the 14B stack): (l + 1)(l + 2) / 2 links for layer l's keys / values, L (L + 1) / 2 and the narrowing
+        # for the stack's bf16 output (a by-product the method does not use).  These deeper gates check the sequencing (the
+        # right weights, gains and modulation per layer), the accuracy itself is layer 0's.
+        deep = lambda l: (l + 1) * (l + 2) / 2 if l else 1
+        assert_close(x_out, ref, "prefill output", relative_to_rms=True, links=L * (L + 1) / 2 + BF16_OUT_LINK)
         for l in range(L):
             assert lvx.lvx_kvcache_get_sink_index(cache, l) == t
-            src = torch.empty((sink_n, d), dtype=torch.bfloat16, device=DEV)
+            src = torch.empty((sink_n, d), dtype=torch.float32, device=DEV)
             lvx.lvx_kvcache_gather_sink_source(cache, l, src)
             gk, gv = gather_sink(lvx, cache, l, sink_n, d)
-            assert_close(src, models[l].sink_source.reshape(sink_n, d), "prefill layer %d sink source" % l, chain=CHAIN)
-            assert_close(gk, models[l].sink[0].reshape(sink_n, d), "prefill layer %d sink keys" % l, chain=CHAIN)
-            assert_close(gv, models[l].sink[1].reshape(sink_n, d), "prefill layer %d sink values" % l, chain=CHAIN)
+            assert_close(src, models[l].sink_source.reshape(sink_n, d), "prefill layer %d sink source (fp32)" % l, links=deep(l))
+            assert_close(gk, models[l].sink[0].reshape(sink_n, d), "prefill layer %d sink keys" % l, links=deep(l))
+            assert_close(gv, models[l].sink[1].reshape(sink_n, d), "prefill layer %d sink values" % l, links=deep(l))
 
     ref_img = S.randn_bf16((sink_n, d), S.seed_of("sinkstage_ref"), device=DEV)
     ctx0 = S.randn_bf16((p["n_ctx"], d), S.seed_of("sinkstage_ctx", "p"), device=DEV)
@@ -151,7 +158,7 @@ def test_stage_with_sink_prefill_swap_and_rolling_index(lvx):
         ref = O.denoise_stage(S.to_f64(x), w64, models, S.to_f64(ctx), S.to_f64(mod6), -0.25, i, t0(i), cfg)
         lvx.lvx_denoise_stage(stage, cache, x, ctx, mod6, -0.25, i, t0(i), ws)
         torch.cuda.synchronize()
-        assert_close(x, ref, "stage chunk %d with rolling sink" % i, relative_to_rms=True, chain=CHAIN)
+        assert_close(x, ref, "stage chunk %d with rolling sink" % i, relative_to_rms=True)
         if i == 0:
             # sink swap: both sides continue from the GPU's own first generated frame (teacher forcing of the new sink's
             # input, so that the check of the second warm-up does not inherit block 0's rounding)
@@ -180,6 +187,7 @@ def test_sample_chunk_T_steps_with_per_timestep_caches(lvx):
     mod6[:, :, 2] += 1.0
     mod6[:, :, 5] += 1.0
     caches = [make_cache(lvx, p, L) for _ in range(T)]
+    caches_b = [make_cache(lvx, p, L) for _ in range(T)]      # the same loop written out with lvx_denoise_stage calls
     models = [[O.RollingKVCache(W) for _ in range(L)] for _ in range(T)]
     ref_img = S.randn_bf16((sink_n, d), S.seed_of("sampler_ref"), device=DEV)
     ctx0 = S.randn_bf16((p["n_ctx"], d), S.seed_of("sampler_ctx", "p"), device=DEV)
@@ -188,8 +196,9 @@ def test_sample_chunk_T_steps_with_per_timestep_caches(lvx):
         lvx.lvx_sample_chunk(stage, caches, x, ctx0, mod6, -1.0 / T, 0, 1, 4, ws)
     assert e.value.status == 3 and all(lvx.lvx_kvcache_get_state(c, 0).last_chunk == -1 for c in caches)
     for s in range(T):
-        caches[s].attach_sink_source()
-        lvx.lvx_sink_prefill(stage, caches[s], ref_img, ctx0, mod6[s], 4, ws)
+        for cs in (caches, caches_b):
+            cs[s].attach_sink_source()
+            lvx.lvx_sink_prefill(stage, cs[s], ref_img, ctx0, mod6[s], 4, ws)
         O.sink_prefill(S.to_f64(ref_img), w64, models[s], S.to_f64(ctx0), S.to_f64(mod6[s]), 4, cfg)
     with pytest.raises(lvx.LvxError):               # the same cache for two timesteps
         lvx.lvx_sample_chunk(stage, [caches[0], caches[1], caches[0]], x, ctx0, mod6, -1.0 / T, 0, 1, 4, ws)
@@ -199,12 +208,21 @@ def test_sample_chunk_T_steps_with_per_timestep_caches(lvx):
         t0 = 1 + p["chunk_frames"] * i
         t_sink = t0 + p["chunk_frames"] + 1
         ref = O.sample_chunk(S.to_f64(x), w64, models, S.to_f64(ctx), S.to_f64(mod6), -1.0 / T, i, t0, cfg, t_sink=t_sink)
+        xb = x.clone()
         lvx.lvx_sample_chunk(stage, caches, x, ctx, mod6, -1.0 / T, i, t0, t_sink, ws)
+        # the loop is T stage calls, each of which is gated at the stated numbers on its own (test_denoise_stage_streaming_small,
+        # stage chunks with rolling sink above): identical bits, and T links against the oracle, which keeps fp64 between steps
+        for s in range(T):
+            lvx.lvx_sink_rope_update(caches_b[s], rope, -1, t_sink)
+            lvx.lvx_denoise_stage(stage, caches_b[s], xb, ctx, mod6[s], -1.0 / T, i, t0, ws)
         torch.cuda.synchronize()
-        assert_close(x, ref, "sampler block %d after %d steps" % (i, T), relative_to_rms=True, chain=CHAIN)
+        assert_same_bf16(x, xb, "sampler block %d: lvx_sample_chunk = %d lvx_denoise_stage calls" % (i, T))
+        assert_close(x, ref, "sampler block %d after %d steps" % (i, T), relative_to_rms=True, links=T)
         for s in range(T):
             for l in range(L):
                 assert lvx.lvx_kvcache_get_state(caches[s], l).last_chunk == i
                 assert lvx.lvx_kvcache_get_sink_index(caches[s], l) == t_sink
-    for c in caches:
+    for s in range(T):
+        assert torch.equal(caches[s].storage, caches_b[s].storage)
+    for c in caches + caches_b:
         c.close()
