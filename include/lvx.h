@@ -234,6 +234,19 @@ lvx_status_t lvx_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_sc
                             const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K,
                             lvx_epilogue_t epi, const void *dev_resid, int64_t ldr, const float *dev_gate, lvx_stream_t stream);
 
+/* lvx_fp8_quantize for callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc -- and so have no scratch buffer to hand over: same inputs, outputs, arithmetic and result
+ * (bit for bit), but the amax slots live in a 256-byte array inside the library (one per GPU, held until the process ends)
+ * instead of dev_scratch256.  The call allocates and frees nothing and, like every other entry point, does not synchronise;
+ * the array is cleared by a kernel at the start of every call.  Tensors of more than LVX_FP8_QUANTIZE_STATIC_MAX_ELEMS elements
+ * are refused (LVX_ERR_SHAPE).  All calls on one GPU share that GPU's array: two calls whose work overlaps in time on one GPU
+ * (different streams, or two threads) race on it and give wrong scales -- serialise them, or use lvx_fp8_quantize with one
+ * scratch buffer per stream.  The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ * outside any stream capture. */
+#define LVX_FP8_QUANTIZE_STATIC_MAX_ELEMS (1ll << 31)
+lvx_status_t lvx_fp8_quantize_static(const void *dev_x, int64_t ld, int32_t rows, int32_t cols, void *dev_q, int64_t ldq,
+                                     float *dev_scale, lvx_stream_t stream);
+
 /* u = LayerNorm(x) * (1 + scale) + shift, no affine, biased variance, eps inside the root.  shift/scale fp32 [d]
  * or NULL (0).  x, u: [n][ld] bf16. */
 lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale,

@@ -85,6 +85,7 @@ SIGNATURES = {
     "lvx_linear": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_linear_dual": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32, _vp]),
     "lvx_fp8_quantize": (C.c_int, [_vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp]),
+    "lvx_fp8_quantize_static": (C.c_int, [_vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp]),
     "lvx_linear_fp8": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
     "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
@@ -294,6 +295,12 @@ def lvx_fp8_quantize(x, q=None, row_pad=0):
     scale = torch.empty(1, dtype=torch.float32, device=x.device)
     _check(load().lvx_fp8_quantize(_ptr(x), x.stride(0), rows, cols, _ptr(q), q.stride(0), _ptr(scratch), _ptr(scale), _stream()))
     return q, scale
+
+
+def lvx_fp8_quantize_static(x, q, scale):
+    """The allocation-free form: q (uint8 [rows][>= cols]) and scale (fp32 [1]) are the caller's; nothing is allocated here."""
+    rows, cols = x.shape
+    _check(load().lvx_fp8_quantize_static(_ptr(x), x.stride(0), rows, cols, _ptr(q), q.stride(0), _ptr(scale), _stream()))
 
 
 def lvx_linear_fp8(aq, scale_a, wq, scale_w, c, epi=EPI_STORE, resid=None, gate=None):

@@ -14,10 +14,38 @@
 // rate on this chip).  A fragment is 32 bytes per lane: row l%32, k = 32*(l/32) .. +31 of the 64-wide k-step.
 #include "lvx_internal.h"
 
+#include <mutex>
+
+// Scratch of lvx_fp8_quantize_static: the amax slot array that lvx_fp8_quantize takes from its caller, here owned by the
+// library.  One copy per GPU the library runs on, resident until the process ends.  In host code this name only stands for
+// the symbol: the device address is resolved per device with hipGetSymbolAddress (static_scratch() below) and only that
+// pointer is ever handed to a kernel.
+static __device__ __align__(256) uint32_t scratch[LVX_AMAX_SLOTS];
+
 namespace {
 
 constexpr int GROUP_M = 8;
 constexpr float E4M3_MAX = 448.0f;
+
+constexpr int MAX_DEVICES = 64;
+uint32_t *g_scratch_ptr[MAX_DEVICES];  // device address of `scratch` on each device, resolved on first use
+std::mutex g_scratch_mutex;
+
+// Device address of this device's copy of `scratch`.  No allocation: the array is part of the code object's data.
+lvx_status_t static_scratch(uint32_t **out) {
+    int dev = -1;
+    LVX_CHECK_HIP(hipGetDevice(&dev));
+    LVX_REQUIRE(dev >= 0 && dev < MAX_DEVICES, LVX_ERR_UNSUPPORTED, "device ordinal %d outside [0,%d)", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        LVX_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        LVX_REQUIRE(p != nullptr && (((uintptr_t)p) & 255u) == 0, LVX_ERR_HIP, "address of the static scratch array is NULL or misaligned");
+        g_scratch_ptr[dev] = (uint32_t *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return LVX_OK;
+}
 
 typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8_t;
 
@@ -331,6 +359,23 @@ extern "C" lvx_status_t lvx_fp8_quantize(const void *dev_x, int64_t ld, int32_t 
                 "row strides: ld a multiple of 8 and ldq a multiple of 16, both >= cols");
     return lvx_launch_fp8_quantize((const bf16_t *)dev_x, ld, rows, cols, (uint8_t *)dev_q, ldq, (uint32_t *)dev_scratch256, dev_scale,
                                    (hipStream_t)stream);
+}
+
+extern "C" lvx_status_t lvx_fp8_quantize_static(const void *dev_x, int64_t ld, int32_t rows, int32_t cols, void *dev_q, int64_t ldq,
+                                                float *dev_scale, lvx_stream_t stream) {
+    LVX_REQUIRE(dev_x != nullptr && dev_q != nullptr && dev_scale != nullptr, LVX_ERR_INVALID_ARG, "x, q or scale is NULL");
+    LVX_REQUIRE(lvx_aligned16(dev_x) && lvx_aligned16(dev_q) && (((uintptr_t)dev_scale) & 3u) == 0, LVX_ERR_INVALID_ARG,
+                "x and q must be 16-byte aligned, scale 4-byte aligned");
+    LVX_REQUIRE(rows >= 0 && cols > 0 && cols % 16 == 0, LVX_ERR_SHAPE, "rows %d, cols %d (cols must be a positive multiple of 16)", rows, cols);
+    LVX_REQUIRE(ld >= cols && ld % 8 == 0 && ldq >= cols && ldq % 16 == 0, LVX_ERR_SHAPE,
+                "row strides: ld a multiple of 8 and ldq a multiple of 16, both >= cols");
+    LVX_REQUIRE((uint64_t)rows * (uint64_t)cols <= (uint64_t)LVX_FP8_QUANTIZE_STATIC_MAX_ELEMS, LVX_ERR_SHAPE,
+                "tensor of %d x %d elements exceeds the %lld elements lvx_fp8_quantize_static accepts (use lvx_fp8_quantize)", rows, cols,
+                (long long)LVX_FP8_QUANTIZE_STATIC_MAX_ELEMS);
+    uint32_t *slots = nullptr;
+    LVX_TRY(static_scratch(&slots));
+    // the array keeps the previous call's maxima: lvx_launch_fp8_quantize clears it (by kernel) before collecting
+    return lvx_launch_fp8_quantize((const bf16_t *)dev_x, ld, rows, cols, (uint8_t *)dev_q, ldq, slots, dev_scale, (hipStream_t)stream);
 }
 
 lvx_status_t lvx_launch_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,

@@ -166,6 +166,11 @@ def test_fp8_entry_points_host_checks():
     assert lib.lvx_fp8_quantize(p, 64, 4, 64, p, 72, p, f, None) == 2            # ldq % 16
     assert lib.lvx_fp8_quantize(p, 32, 4, 64, p, 64, p, f, None) == 2            # ld < cols
     assert lib.lvx_fp8_quantize(p, 64, 4, 64, p, 64, C.c_void_p(4100), f, None) == 1
+    # the allocation-free form: same checks, plus its stated maximum, all before anything touches a device
+    assert lib.lvx_fp8_quantize_static(None, 64, 4, 64, p, 64, f, None) == 1
+    assert lib.lvx_fp8_quantize_static(p, 64, 4, 60, p, 64, f, None) == 2
+    assert lib.lvx_fp8_quantize_static(p, 1 << 20, 1 << 12, 1 << 20, p, 1 << 20, f, None) == 2          # 2^32 elements > 2^31
+    assert b"exceeds" in lib.lvx_last_error()
     assert lib.lvx_linear_fp8(p, 128, f, p, 128, f, p, 64, 4, 64, 192, 0, None, 0, None, None) == 2    # K % 128
     assert lib.lvx_linear_fp8(p, 128, f, p, 128, f, p, 64, 4, 60, 128, 0, None, 0, None, None) == 2    # N % 8
     assert lib.lvx_linear_fp8(p, 120, f, p, 128, f, p, 64, 4, 64, 128, 0, None, 0, None, None) == 2    # lda
