@@ -39,14 +39,16 @@ def block_flops(n, d, f, n_k, n_ctx, H, D):
 
 
 def cpu_baseline(p, sample_tokens, n_threads_hint):
-    """Oracle (as it stands) on one DiT block with `sample_tokens` of the chunk's tokens against a full-size cache
-    (sink + 4 past chunks); extrapolated linearly in tokens and layers to frames/s."""
+    """Oracle (as it stands: numpy fp64 on the BLAS threads of the host) on one DiT block for `sample_tokens` of the chunk's
+    tokens against the FULL visible key set (sink + 4 past chunks + the whole current chunk = 24960 keys), through the
+    oracle's row form; extrapolated linearly in tokens and layers to frames/s."""
     import numpy as np
     from oracle import lvx_oracle as O
     H, D = p["n_heads"], p["head_dim"]
     d = H * D
     fk = p["frame_h"] * p["frame_w"]
     chunk = fk * p["chunk_frames"]
+    n_k = fk * p["sink_frames"] + (p["window"] + 1) * chunk
     rng = np.random.default_rng(0)
     cfg = O.StageConfig(H, D, p["frame_h"], p["frame_w"], p["chunk_frames"], p["window"], p["sink_frames"], p["rope_axes"])
     w = {}
@@ -55,22 +57,89 @@ def cpu_baseline(p, sample_tokens, n_threads_hint):
         w[name] = rng.standard_normal(shape, dtype=np.float32).astype(np.float64) * 0.02
     for g in ("g_q", "g_k", "gc_q", "gc_k"):
         w[g] = np.ones(d)
-    cache = O.RollingKVCache(p["window"])
-    cache.set_sink(rng.standard_normal((fk, H, D)), rng.standard_normal((fk, H, D)))
-    for j in range(p["window"]):
-        cache.append(j, rng.standard_normal((chunk, H, D), dtype=np.float32).astype(np.float64),
-                     rng.standard_normal((chunk, H, D), dtype=np.float32).astype(np.float64))
+    k_vis = rng.standard_normal((n_k, H, D), dtype=np.float32).astype(np.float64)
+    v_vis = rng.standard_normal((n_k, H, D), dtype=np.float32).astype(np.float64)
     x = rng.standard_normal((sample_tokens, d))
     ctx = rng.standard_normal((p["n_ctx"], d))
+    pos = tuple(a[:sample_tokens] for a in O.token_positions(chunk, 1 + 3 * p["window"], p["frame_h"], p["frame_w"]))
     t0 = time.perf_counter()
-    O.dit_block(x, w, cache, ctx, None, p["window"], 1 + 3 * p["window"], cfg)
+    O.dit_block_rows(x, pos, w, k_vis, v_vis, ctx, None, cfg)
     dt = time.perf_counter() - t0
     try:
         from threadpoolctl import threadpool_info
         cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
         cores = n_threads_hint
-    return dt, cores
+    return dt, cores, n_k
+
+
+class PowerSampler:
+    """Polls the GPU's shader clock and socket power (amdsmi) from a host thread while the timed region runs."""
+
+    def __init__(self, period=0.1):
+        self.samples, self.cap_w, self.period, self._stop, self._t = [], None, period, False, None
+        try:
+            import amdsmi
+            self.A = amdsmi
+            amdsmi.amdsmi_init()
+            self.h = amdsmi.amdsmi_get_processor_handles()[0]
+            cap = amdsmi.amdsmi_get_power_info(self.h).get("power_limit")
+            self.cap_w = cap / 1e6 if isinstance(cap, (int, float)) else None
+        except Exception:
+            self.A = None
+
+    def _poll(self):
+        while not self._stop:
+            try:
+                m = self.A.amdsmi_get_gpu_metrics_info(self.h)
+                clk, pw = m.get("current_gfxclk"), m.get("current_socket_power")
+                if isinstance(clk, (int, float)) and isinstance(pw, (int, float)):
+                    self.samples.append((clk, pw))
+            except Exception:
+                pass
+            time.sleep(self.period)
+
+    def start(self):
+        if self.A is not None:
+            import threading
+            self._t = threading.Thread(target=self._poll, daemon=True)
+            self._t.start()
+
+    def stop(self):
+        self._stop = True
+        if self._t is not None:
+            self._t.join()
+        if not self.samples:
+            return None
+        clk = [c for c, _ in self.samples]
+        pw = [w for _, w in self.samples]
+        return {"samples": len(self.samples), "gfx_clk_mhz_avg": round(sum(clk) / len(clk)), "gfx_clk_mhz_min": min(clk), "gfx_clk_mhz_max": max(clk),
+                "socket_power_w_avg": round(sum(pw) / len(pw)), "socket_power_w_max": max(pw), "power_cap_w": self.cap_w,
+                "note": "amdsmi current_gfxclk / current_socket_power polled every %.1f s during the timed region; the published peaks assume 2400 MHz" % self.period}
+
+
+def kernel_classes(prof, steps, n, d, f, n_k, n_ctx, H, D, L, sink_n):
+    """Per kernel class: ms per step, launches per step, and the class's rate against the roofline that bounds it
+    (MFMA classes: algorithmic FLOPs against the dense bf16 peak; memory classes: algorithmic bytes against the HBM peak)."""
+    fl = {"attn_self": attention_flops(n, n_k, H, D), "gemm_qkv": 2.0 * n * d * 3 * d, "gemm_o": 2.0 * n * d * d, "gemm_cross": 2 * 2.0 * n * d * d,
+          "gemm_ffn1": 2.0 * n * d * f, "gemm_ffn2": 2.0 * n * d * f, "attn_cross": attention_flops(n, n_ctx, H, D), "ctx_kv": 2 * 2.0 * n_ctx * d * d}
+    # algorithmic bytes per layer: rope+norm reads q, k and writes q^, k^ (bf16 each; the fp32 hand-off moves 1.5 x that);
+    # append reads and writes k^, v; each LayerNorm reads the fp32 stream and writes bf16 (3 per layer)
+    by = {"rope_norm": 4.0 * n * d * 2, "append": 4.0 * n * d * 2, "layernorm": 3.0 * n * d * (4 + 2), "cross_qnorm": 2.0 * n * d * 2}
+    per_step = {"misc": n * d * (2 + 4) + n * d * (2 + 4 + 2), "sink_rope": L * sink_n * d * (4 + 2)}
+    out = {}
+    for k, (ms, cnt) in prof.items():
+        if not cnt:
+            continue
+        e = {"ms_per_step": round(ms / steps, 3), "launches_per_step": round(cnt / steps, 2)}
+        sec = ms / steps * 1e-3
+        if k in fl:
+            e.update(bound="mfma", achieved=round(L * fl[k] / sec / 1e12, 1), unit="TFLOP/s", frac=round(L * fl[k] / sec / 1e12 / PEAK_BF16_TFLOPS, 4))
+        elif k in by or k in per_step:
+            b = L * by[k] if k in by else per_step[k]
+            e.update(bound="hbm", achieved=round(b / sec / 1e9, 1), unit="GB/s", frac=round(b / sec / 1e9 / PEAK_HBM_GBS, 4))
+        out[k] = e
+    return out
 
 
 def main():
@@ -154,14 +223,21 @@ def main():
 
     lvx.lvx_profile_read()
     lvx.lvx_profile_set(args.profile_level)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # between steps, on the launch stream
+    sampler = PowerSampler()
     torch.cuda.synchronize()
+    sampler.start()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     seconds = time.perf_counter() - t0
+    clocks = sampler.stop()
     lvx.lvx_profile_set(0)
     prof = lvx.lvx_profile_read()
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     assert bool(torch.isfinite(x.float()).all()), "stage output is not finite"
 
     ms_per_step = seconds / args.steps * 1e3
@@ -181,6 +257,8 @@ def main():
                                "544 context tokens), chunk 3x1560=4680 tokens, rolling cache full: sink 1560 + 4 past chunks + self "
                                "= 24960 keys per layer (the attention inside is configs[1])" % L,
                    "n_layers": L, "chunk_tokens": n, "keys": n_k, "ms_per_chunk": round(ms_per_step, 3),
+                   "ms_per_chunk_median": round(step_ms[len(step_ms) // 2], 3), "ms_per_chunk_min": round(step_ms[0], 3),
+                   "ms_per_chunk_max": round(step_ms[-1], 3),
                    "stage_tflops": round(stage_fl / (seconds / args.steps) / 1e12, 2),
                    "stage_frac_of_bf16_peak": round(stage_fl / (seconds / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)},
         "roofline": {"kernel": "lvx_attention_kernel<128,8> (chunk-to-cache self-attention, configs[1] shape)", "bound": "mfma",
@@ -192,17 +270,30 @@ def main():
                                   "cores busy in 64 % of the cycles (its softmax VALU phase and its MFMA phase do not overlap on a SIMD); "
                                   "with the softmax removed the same kernel reaches 89 % of this peak"},
     }
+    out["clocks"] = clocks
+    bd_prof, bd_steps, bd_ms = None, 0, ms_per_step
     if args.profile_level >= 2:
-        out["kernel_ms_per_step"] = {k: round(v[0] / args.steps, 3) for k, v in prof.items() if v[1]}
+        bd_prof, bd_steps = prof, args.steps
     elif args.breakdown_steps > 0:
         # per-class kernel times from a separate, untimed pass (the events around every launch slow the step a little)
         lvx.lvx_profile_set(2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for _ in range(args.breakdown_steps):
             step()
+        e1.record()
         torch.cuda.synchronize()
         lvx.lvx_profile_set(0)
-        prof2 = lvx.lvx_profile_read()
-        out["kernel_ms_per_step"] = {k: round(v[0] / args.breakdown_steps, 3) for k, v in prof2.items() if v[1]}
+        bd_prof, bd_steps, bd_ms = lvx.lvx_profile_read(), args.breakdown_steps, e0.elapsed_time(e1) / args.breakdown_steps
+    if bd_prof is not None:
+        # every launch of a step belongs to one class; what is left of the step is the idle time between launches (and the
+        # events themselves).  fp8_quant (FP8 stages) is also contained in its linear's class, so it is not added again.
+        out["kernel_ms_per_step"] = {k: round(v[0] / bd_steps, 3) for k, v in bd_prof.items() if v[1]}
+        out["kernel_classes"] = kernel_classes(bd_prof, bd_steps, n, d, p["ffn"], n_k, p["n_ctx"], H, D, L, sink_n)
+        in_kernels = sum(v[0] for k, v in bd_prof.items() if k != "fp8_quant") / bd_steps
+        out["kernel_ms_per_step_sum"] = round(in_kernels, 3)
+        out["between_launches_ms_per_step"] = round(bd_ms - in_kernels, 3)
+        out["breakdown_ms_per_step"] = round(bd_ms, 3)
     if not args.fp8 and not args.no_fp8_extra:
         # second, separately reported configuration: the same stage with every linear in FP8 E4M3 (Appendix C, the paper's own
         # default); same weights (quantised per tensor here), same cache, continuing the same chunk sequence
@@ -243,13 +334,14 @@ def main():
             "qkv_gemm_tflops": round(2.0 * n * 3 * d * d / (qkv_ms * 1e-3) / 1e12, 1), "fp8_mfma_peak_tflops": 5000.0,
             "kernel_ms_per_step": {k: round(v[0] / bd8, 3) for k, v in prof8.items() if v[1]}}
     if not args.no_cpu_baseline:
-        t_cpu, cores = cpu_baseline(p, args.cpu_sample_tokens, os.cpu_count())
+        t_cpu, cores, keys_cpu = cpu_baseline(p, args.cpu_sample_tokens, os.cpu_count())
         est_chunk_s = t_cpu * (n / args.cpu_sample_tokens) * L
         out["cpu_baseline"] = {"value": round(p["chunk_frames"] / est_chunk_s, 6), "unit": "latent frames/s", "cores": cores,
                                "kind": "oracle",
-                               "sample": "fp64 numpy oracle, ONE DiT block on %d of the chunk's 4680 tokens against a full cache "
-                                         "(sink + 4 chunks + self): %.2f s measured; extrapolated x%.0f tokens x%d layers"
-                                         % (args.cpu_sample_tokens, t_cpu, n / args.cpu_sample_tokens, L)}
+                               "sample": "the fp64 numpy oracle (BLAS threads of the host, not a compiled C oracle), ONE DiT block in row form on "
+                                         "%d of the chunk's %d tokens against all %d visible keys (sink + 4 chunks + the whole current chunk): "
+                                         "%.2f s measured; extrapolated x%.0f tokens x%d layers"
+                                         % (args.cpu_sample_tokens, n, keys_cpu, t_cpu, n / args.cpu_sample_tokens, L)}
     print(json.dumps(out), flush=True)
     cache.close()
 

@@ -297,6 +297,14 @@ typedef struct {
 
 size_t lvx_workspace_bytes(const lvx_stage_t *stage /* host */, int32_t n_tokens, int32_t n_ctx);
 
+/* The cross-attention keys and values of layers [layer0, layer0 + n_layers) for one context, exactly as the blocks compute and
+ * read them (the conditions C_i of Alg. 3 / Alg. 4 are one set per forward, so a stage prepares them for a group of layers in
+ * one GEMM launch): K = RMSNorm(ctx Wc_k^T) * gc_k, V = ctx Wc_v^T, read back token-major as [n_layers][n_ctx][ld] bf16 each.
+ * Exported for parity checks of that path; the blocks keep these tensors in the attention kernel's packed layout inside the
+ * workspace.  n_layers <= 8; bf16 stages only; workspace >= lvx_workspace_bytes(stage, 1, n_ctx). */
+lvx_status_t lvx_context_kv(const lvx_stage_t *stage /* host */, int32_t layer0, int32_t n_layers, const void *dev_ctx, int32_t n_ctx,
+                            void *dev_k_out, void *dev_v_out, int64_t ld, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
+
 /* One block on the current chunk.  x_inout [n_tokens][d] bf16 (ld = d); ctx [n_ctx][d] bf16; t0 = temporal rotary
  * index of the chunk's first frame; n_tokens must equal the cache's chunk size.  workspace: device scratch of
  * lvx_workspace_bytes, 256-byte aligned. */
@@ -368,7 +376,7 @@ lvx_status_t lvx_causal_conv_step(lvx_causal_conv_t *conv, const void *dev_x, in
 /* ------------------------------------------------------------------------------------------------
  * Optional timing of the kernel classes inside lvx_dit_block / lvx_denoise_stage with HIP events recorded on the
  * caller's stream (the benchmark's roofline figures come from here).  Not thread-safe; level 0 = off (default),
- * 1 = the chunk-to-cache attention launches only, 2 = every class below.  lvx_profile_read waits for the recorded
+ * 1 = the chunk-to-cache attention launches only, 2 = every class below (together they cover every launch of a stage call).  lvx_profile_read waits for the recorded
  * events (it synchronises on them), writes per-class totals into host arrays of LVX_PROF_KINDS entries and resets.
  * ------------------------------------------------------------------------------------------------ */
 enum {
@@ -376,7 +384,11 @@ enum {
     LVX_PROF_GEMM_FFN2 = 5, LVX_PROF_ATTN_CROSS = 6, LVX_PROF_ROPE_NORM = 7, LVX_PROF_APPEND = 8, LVX_PROF_LAYERNORM = 9,
     LVX_PROF_FP8_QUANT = 10, /* per-tensor quantisation of the linears' input activations (FP8 stages only); this time is also
                                 contained in the class of the linear it precedes */
-    LVX_PROF_KINDS = 11
+    LVX_PROF_CTX_KV = 11,      /* the context's K / V projections (a group of layers per launch), their RMSNorm and pack */
+    LVX_PROF_CROSS_QNORM = 12, /* RMSNorm of the cross-attention queries */
+    LVX_PROF_MISC = 13,        /* widening of the input, Euler step / narrowing, zero fills at the start of a call */
+    LVX_PROF_SINK_ROPE = 14,   /* lvx_sink_rope_update */
+    LVX_PROF_KINDS = 15
 };
 lvx_status_t lvx_profile_set(int32_t level);
 lvx_status_t lvx_profile_read(double *ms_total /* host [LVX_PROF_KINDS] */, int64_t *launches /* host [LVX_PROF_KINDS] */);

@@ -89,6 +89,7 @@ SIGNATURES = {
     "lvx_linear_fp8": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_layernorm_modulate": (C.c_int, [_vp, _i64, _vp, _vp, _f32, _i32, _i32, _vp, _i64, _vp]),
     "lvx_workspace_bytes": (_sz, [C.POINTER(Stage), _i32, _i32]),
+    "lvx_context_kv": (C.c_int, [C.POINTER(Stage), _i32, _i32, _vp, _i32, _vp, _vp, _i64, _vp, _sz, _vp]),
     "lvx_dit_block": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_dit_block_f32": (C.c_int, [C.POINTER(Stage), _i32, _vp, _vp, _i32, _vp, _i32, _vp, _i64, _i32, _vp, _sz, _vp]),
     "lvx_denoise_stage": (C.c_int, [C.POINTER(Stage), _vp, _vp, _i32, _vp, _i32, _vp, _f32, _i64, _i32, _vp, _sz, _vp]),
@@ -111,7 +112,7 @@ SIGNATURES = {
     "lvx_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 PROF_KINDS = ["attn_self", "gemm_qkv", "gemm_o", "gemm_cross", "gemm_ffn1", "gemm_ffn2", "attn_cross", "rope_norm", "append",
-              "layernorm", "fp8_quant"]
+              "layernorm", "fp8_quant", "ctx_kv", "cross_qnorm", "misc", "sink_rope"]
 
 
 def load():
@@ -356,6 +357,12 @@ class StageHandle:
 
 def lvx_workspace_bytes(stage, n_tokens, n_ctx):
     return load().lvx_workspace_bytes(C.byref(stage.c), n_tokens, n_ctx)
+
+
+def lvx_context_kv(stage, layer0, n_layers, ctx, k_out, v_out, workspace):
+    """k_out, v_out: bf16 [n_layers][n_ctx][d] (contiguous in the first two dims, row stride k_out.stride(1))."""
+    _check(load().lvx_context_kv(C.byref(stage.c), layer0, n_layers, _ptr(ctx), ctx.shape[0], _ptr(k_out), _ptr(v_out), k_out.stride(1),
+                                 _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
 def lvx_dit_block(stage, layer, cache, x, ctx, mod6, chunk_index, t0, workspace):

@@ -18,33 +18,39 @@ int g_prof_level = 0;
 std::vector<prof_pair_t> g_prof_pool;
 size_t g_prof_used = 0;
 
-struct prof_scope_t {
-    hipStream_t st;
-    prof_pair_t *p = nullptr;
-    prof_scope_t(int kind, hipStream_t stream) : st(stream) {
-        if (g_prof_level == 0 || (g_prof_level == 1 && kind != LVX_PROF_ATTN_SELF)) return;
-        if (g_prof_used == g_prof_pool.size()) {
-            prof_pair_t n;
-            if (hipEventCreate(&n.a) != hipSuccess) return;
-            if (hipEventCreate(&n.b) != hipSuccess) {
-                (void)hipEventDestroy(n.a);
-                return;
-            }
-            g_prof_pool.push_back(n);
+}  // namespace
+
+lvx_prof_scope_t::lvx_prof_scope_t(int kind, hipStream_t stream) : st(stream), pair(nullptr) {
+    if (g_prof_level == 0 || (g_prof_level == 1 && kind != LVX_PROF_ATTN_SELF)) return;
+    if (g_prof_used == g_prof_pool.size()) {
+        prof_pair_t n;
+        if (hipEventCreate(&n.a) != hipSuccess) return;
+        if (hipEventCreate(&n.b) != hipSuccess) {
+            (void)hipEventDestroy(n.a);
+            return;
         }
-        p = &g_prof_pool[g_prof_used++];
-        p->kind = kind;
-        (void)hipEventRecord(p->a, st);
+        g_prof_pool.push_back(n);
     }
-    ~prof_scope_t() {
-        if (p) (void)hipEventRecord(p->b, st);
-    }
-};
+    const size_t idx = g_prof_used++;  // the pool may grow while this scope lives: keep the index, not a pointer
+    g_prof_pool[idx].kind = kind;
+    (void)hipEventRecord(g_prof_pool[idx].a, st);
+    pair = (void *)(idx + 1);
+}
+
+lvx_prof_scope_t::~lvx_prof_scope_t() {
+    if (pair != nullptr) (void)hipEventRecord(g_prof_pool[(size_t)pair - 1].b, st);
+}
+
+namespace {
+typedef lvx_prof_scope_t prof_scope_t;
+
+// Layers whose context K / V projections, norm and pack are done together (one GEMM launch of 2 x group segments).
+constexpr int CTX_GROUP = LVX_GEMM_MAX_SEGS / 2;
 
 struct ws_layout_t {
-    size_t u, big, qk32, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
+    size_t u, big, qk32, ctx_k32, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
     int64_t ld_q8, ld_q8c;                            // row strides (bytes) of the FP8 activation buffers
-    int cap_ctx;
+    int cap_ctx, ctx_group;
     int64_t ld_u, ld_qkv, ld_cq, ld_ffn, ld_ckv;      // padded row strides (elements) of the bf16 workspace matrices
     int64_t ld_qk32;                                  // row stride (fp32 elements) of the un-rounded q | k columns
 };
@@ -71,9 +77,13 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.big = off;     off += round256((size_t)n_tokens * (wide + WS_PAD) * 2);
     w.qk32 = off;    // fp32 q | k columns of the QKV projection (bf16 stages only; an FP8 stage stores them in bf16)
     if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * w.ld_qk32 * 4);
-    w.ctx_kv = off;  off += round256((size_t)n_ctx * w.ld_ckv * 2);
-    w.pack_k = off;  off += round256((size_t)w.cap_ctx * d * 2);
-    w.pack_v = off;  off += round256((size_t)w.cap_ctx * d * 2);
+    // context K | V rows and their packed forms for a group of layers at once (bf16 stages; an FP8 stage uses one slot)
+    w.ctx_group = s->blocks_fp8 != nullptr ? 1 : (s->n_layers < CTX_GROUP ? s->n_layers : CTX_GROUP);
+    w.ctx_kv = off;  off += round256((size_t)w.ctx_group * n_ctx * w.ld_ckv * 2);
+    w.ctx_k32 = off;  // un-rounded context keys before their RMSNorm (bf16 stages), row stride ld_u fp32 elements
+    if (s->blocks_fp8 == nullptr) off += round256((size_t)w.ctx_group * n_ctx * w.ld_u * 4);
+    w.pack_k = off;  off += round256((size_t)w.ctx_group * w.cap_ctx * d * 2);
+    w.pack_v = off;  off += round256((size_t)w.ctx_group * w.cap_ctx * d * 2);
     w.h = off;       off += round256((size_t)n_tokens * d * 4);  // fp32 residual stream
     w.q8 = w.q8_ctx = w.q8_misc = off;
     const size_t wide_in = d > (size_t)s->d_ffn ? d : (size_t)s->d_ffn;
@@ -124,9 +134,36 @@ lvx_status_t check_stage(const lvx_stage_t *s, const lvx_kvcache *c, int n_token
 //   attend to the sink segment only; the ring is not touched.
 // amax_cur (FP8 stages): which of the two amax slot arrays the next producer writes and the next quantisation reads; both arrays
 //   are zero when the entry point starts (call_begin), every quantisation clears the other one.
+// Context K / V of layers [l0, l1) (at most CTX_GROUP; bf16 stages): the context is the same for every layer of a forward
+// (Alg. 4 hands one condition set C_i to the whole stack), so their 2 (l1 - l0) projections run as ONE GEMM launch (a single
+// layer's pair is 200 tiles on 256 compute units), followed by one launch that normalises the K rows straight into the
+// packed layout the attention kernel reads and one that transposes the V rows into it.  Slot j of the group holds layer l0 + j.
+lvx_status_t precompute_ctx(const lvx_stage_t *s, int l0, int l1, const bf16_t *ctx, int n_ctx, char *ws, const ws_layout_t &L, hipStream_t st) {
+    const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D;
+    const int64_t ldw = s->ldw_d > 0 ? s->ldw_d : d, ldk = L.ld_ckv;
+    bf16_t *ctx_kv = (bf16_t *)(ws + L.ctx_kv), *pack_k = (bf16_t *)(ws + L.pack_k), *pack_v = (bf16_t *)(ws + L.pack_v);
+    float *ctx_k32 = (float *)(ws + L.ctx_k32);
+    const int g = l1 - l0;
+    const int64_t slot_rows = (int64_t)n_ctx * ldk, slot_packed = (int64_t)L.cap_ctx * d, ld32 = L.ld_u, slot_rows32 = (int64_t)n_ctx * ld32;
+    lvx_gemm_segs_t segs;
+    segs.n = 2 * g;
+    const float *gains[CTX_GROUP];
+    for (int j = 0; j < g; ++j) {
+        const lvx_block_weights_t &w = s->blocks[l0 + j];
+        segs.s[2 * j] = {(const bf16_t *)w.Wc_k, ctx_k32 + j * slot_rows32, ld32, d, 0, 1, 0};  // keys in fp32: rounded once, after the norm
+        segs.s[2 * j + 1] = {(const bf16_t *)w.Wc_v, ctx_kv + j * slot_rows + d, ldk, d, 0, 0, 0};
+        gains[j] = w.gc_k;
+    }
+    prof_scope_t ps(LVX_PROF_CTX_KV, st);
+    LVX_TRY(lvx_launch_linear_segments(ctx, d, ldw, segs, n_ctx, d, st));
+    LVX_TRY(lvx_launch_norm_to_packed_k(&s->rope, ctx_k32, 1, ld32, n_ctx, gains, pack_k, L.cap_ctx, g, slot_rows32, slot_packed, st));
+    return lvx_launch_pack_kv(nullptr, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st, g, slot_rows, slot_packed);
+}
+
+// ctx_slot: slot of the context group that holds this layer's packed context K / V (bf16 stages, see precompute_ctx).
 lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
                        const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st, int *amax_cur,
-                       bool sink_prefill = false) {
+                       int ctx_slot, bool sink_prefill = false) {
     const lvx_block_weights_t &w = s->blocks[layer];
     const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
     const float eps = s->rope.eps;
@@ -134,8 +171,8 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     bf16_t *u = (bf16_t *)(ws + L.u);
     bf16_t *big = (bf16_t *)(ws + L.big);
     bf16_t *ctx_kv = (bf16_t *)(ws + L.ctx_kv);
-    bf16_t *pack_k = (bf16_t *)(ws + L.pack_k);
-    bf16_t *pack_v = (bf16_t *)(ws + L.pack_v);
+    bf16_t *pack_k = (bf16_t *)(ws + L.pack_k) + (size_t)ctx_slot * L.cap_ctx * (s->rope.n_heads * s->rope.head_dim);
+    bf16_t *pack_v = (bf16_t *)(ws + L.pack_v) + (size_t)ctx_slot * L.cap_ctx * (s->rope.n_heads * s->rope.head_dim);
     const float *shift1 = mod6 ? mod6 : nullptr, *scale1 = mod6 ? mod6 + d : nullptr, *gate1 = mod6 ? mod6 + 2 * d : nullptr;
     const float *shift2 = mod6 ? mod6 + 3 * d : nullptr, *scale2 = mod6 ? mod6 + 4 * d : nullptr, *gate2 = mod6 ? mod6 + 5 * d : nullptr;
 
@@ -222,21 +259,18 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
 
     // cross-attention to the audio + text context
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st)); }
-    {
-        prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
-        LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
-        if (w8 == nullptr) {  // the context's K and V projections share one launch
-            LVX_TRY(lvx_launch_linear_dual(ctx, d, (const bf16_t *)w.Wc_k, (const bf16_t *)w.Wc_v, ldw, ctx_kv, ldk, 0, ctx_kv + d, ldk, n_ctx, d, d, d, st));
-        } else {
-            LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false, false, false));
-            LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true, false, false));
-        }
-    }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false)); }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
-    if (w.gc_q) LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st));
-    if (w.gc_k) LVX_TRY(lvx_rope3d(&norm_only, nullptr, ctx_kv, ldk, nullptr, w.gc_k, n_ctx, 0, nullptr, ctx_kv, ldk, st));
-    LVX_TRY(lvx_launch_pack_kv(ctx_kv, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
+    if (w.gc_q) { prof_scope_t ps(LVX_PROF_CROSS_QNORM, st); LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st)); }
+    if (w8 != nullptr) {  // FP8 stage: this layer's context projections, norm and pack, into slot 0 (the context is quantised once)
+        prof_scope_t ps(LVX_PROF_CTX_KV, st);
+        LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false, false, false));
+        LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true, false, false));
+        const float *gains[1] = {w.gc_k};
+        LVX_TRY(lvx_launch_norm_to_packed_k(&s->rope, ctx_kv, 0, ldk, n_ctx, gains, pack_k, L.cap_ctx, 1, 0, 0, st));
+        LVX_TRY(lvx_launch_pack_kv(nullptr, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
+    }
     { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st, amax_out())); }
     { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false, true, false)); }
 
@@ -251,9 +285,37 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
 // tile (the keys past n_ctx are masked in the attention but must be finite; the per-layer pack only writes keys below n_ctx),
 // and an FP8 stage clears both amax slot arrays.
 lvx_status_t call_begin(const lvx_stage_t *s, char *ws, const ws_layout_t &L, hipStream_t st, int n_ctx) {
+    prof_scope_t ps(LVX_PROF_MISC, st);
     if (L.cap_ctx != n_ctx) LVX_TRY(lvx_launch_fill_zero(ws + L.pack_k, L.h - L.pack_k, st));
     if (s->blocks_fp8 == nullptr) return LVX_OK;
     return lvx_launch_fill_zero(ws + L.q8_misc, 2 * LVX_AMAX_SLOTS * sizeof(uint32_t), st);
+}
+
+// Blocks l0 .. l1-1 on the fp32 stream h.  mod6: modulation of layer l0 (NULL = none), the following layers' mod6_stride
+// floats apart.  In a bf16 stage the context K / V of up to CTX_GROUP layers are prepared together, ahead of the first of them.
+lvx_status_t run_layers(const lvx_stage_t *s, int l0, int l1, lvx_kvcache *c, float *h, int n, const bf16_t *ctx, int n_ctx, const float *mod6,
+                        size_t mod6_stride, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st, int *amax_cur,
+                        bool sink_prefill) {
+    for (int l = l0; l < l1; ++l) {
+        int slot = 0;
+        if (s->blocks_fp8 == nullptr) {
+            slot = (l - l0) % L.ctx_group;
+            if (slot == 0) LVX_TRY(precompute_ctx(s, l, l + L.ctx_group < l1 ? l + L.ctx_group : l1, ctx, n_ctx, ws, L, st));
+        }
+        const float *m6 = mod6 ? mod6 + (size_t)(l - l0) * mod6_stride : nullptr;
+        LVX_TRY(run_block(s, l, c, h, n, ctx, n_ctx, m6, chunk_index, t0, ws, L, st, amax_cur, slot, sink_prefill));
+    }
+    return LVX_OK;
+}
+
+lvx_status_t widen_in(const bf16_t *x, float *h, size_t n_elems, hipStream_t st) {
+    prof_scope_t ps(LVX_PROF_MISC, st);
+    return lvx_launch_widen(x, h, n_elems, st);
+}
+
+lvx_status_t euler_out(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t st) {
+    prof_scope_t ps(LVX_PROF_MISC, st);
+    return lvx_launch_euler(x, h, dt, out, n_elems, st);
 }
 
 lvx_status_t check_common(const lvx_stage_t *s, lvx_kvcache *c, void *x, int n, const void *ctx, int n_ctx, void *ws, size_t ws_bytes,
@@ -314,6 +376,33 @@ extern "C" size_t lvx_workspace_bytes(const lvx_stage_t *stage, int32_t n_tokens
     return ws_layout(stage, n_tokens, n_ctx).total;
 }
 
+extern "C" lvx_status_t lvx_context_kv(const lvx_stage_t *stage, int32_t layer0, int32_t n_layers, const void *dev_ctx, int32_t n_ctx,
+                                       void *dev_k_out, void *dev_v_out, int64_t ld, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
+    LVX_TRY(check_stage(stage, nullptr, 1, n_ctx));
+    LVX_REQUIRE(stage->blocks_fp8 == nullptr, LVX_ERR_UNSUPPORTED, "lvx_context_kv serves bf16 stages (an FP8 stage projects the context layer by layer)");
+    LVX_REQUIRE(layer0 >= 0 && n_layers >= 1 && layer0 + n_layers <= stage->n_layers, LVX_ERR_INVALID_ARG, "layers [%d,%d) outside the stage's %d",
+                layer0, layer0 + n_layers, stage->n_layers);
+    LVX_REQUIRE(dev_ctx != nullptr && dev_k_out != nullptr && dev_v_out != nullptr && dev_workspace != nullptr, LVX_ERR_INVALID_ARG,
+                "ctx, an output or the workspace is NULL");
+    LVX_REQUIRE(lvx_aligned16(dev_ctx) && lvx_aligned16(dev_k_out) && lvx_aligned16(dev_v_out) && (((uintptr_t)dev_workspace) & 255u) == 0,
+                LVX_ERR_INVALID_ARG, "ctx / outputs must be 16-byte and workspace 256-byte aligned");
+    const int H = stage->rope.n_heads, D = stage->rope.head_dim, d = H * D;
+    LVX_REQUIRE(ld >= d && ld % 8 == 0, LVX_ERR_SHAPE, "row stride %lld must be a multiple of 8 and >= d_model", (long long)ld);
+    const ws_layout_t L = ws_layout(stage, 1, n_ctx);
+    LVX_REQUIRE(n_layers <= L.ctx_group, LVX_ERR_SHAPE, "at most %d layers per call", L.ctx_group);
+    LVX_REQUIRE(ws_bytes >= L.total, LVX_ERR_SHAPE, "workspace too small: %zu bytes given, %zu needed (lvx_workspace_bytes(stage, 1, n_ctx))", ws_bytes,
+                L.total);
+    char *ws = (char *)dev_workspace;
+    hipStream_t st = (hipStream_t)stream;
+    LVX_TRY(call_begin(stage, ws, L, st, n_ctx));
+    LVX_TRY(precompute_ctx(stage, layer0, layer0 + n_layers, (const bf16_t *)dev_ctx, n_ctx, ws, L, st));
+    for (int j = 0; j < n_layers; ++j)
+        LVX_TRY(lvx_launch_gather_kv((const bf16_t *)(ws + L.pack_k) + (size_t)j * L.cap_ctx * d, (const bf16_t *)(ws + L.pack_v) + (size_t)j * L.cap_ctx * d,
+                                     L.cap_ctx, H, D, 0, n_ctx, (bf16_t *)dev_k_out + (size_t)j * n_ctx * ld, (bf16_t *)dev_v_out + (size_t)j * n_ctx * ld, ld,
+                                     st));
+    return LVX_OK;
+}
+
 extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
                                       const void *dev_ctx, int32_t n_ctx, const float *dev_mod6, int64_t chunk_index, int32_t t0,
                                       void *dev_workspace, size_t ws_bytes, lvx_stream_t stream) {
@@ -323,12 +412,12 @@ extern "C" lvx_status_t lvx_dit_block(const lvx_stage_t *stage, int32_t layer, l
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     const size_t n_elems = (size_t)n_tokens * stage->rope.n_heads * stage->rope.head_dim;
     float *h = (float *)((char *)dev_workspace + L.h);
-    LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_inout, h, n_elems, (hipStream_t)stream));
+    LVX_TRY(widen_in((const bf16_t *)dev_x_inout, h, n_elems, (hipStream_t)stream));
     int amax_cur = 0;
     LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
-    LVX_TRY(run_block(stage, layer, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0, (char *)dev_workspace, L,
-                      (hipStream_t)stream, &amax_cur));
-    return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
+    LVX_TRY(run_layers(stage, layer, layer + 1, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, 0, chunk_index, t0,
+                       (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur, false));
+    return euler_out(nullptr, h, 1.0f, (bf16_t *)dev_x_inout, n_elems, (hipStream_t)stream);
 }
 
 extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t layer, lvx_kvcache_t *cache, float *dev_x_inout, int32_t n_tokens,
@@ -340,8 +429,8 @@ extern "C" lvx_status_t lvx_dit_block_f32(const lvx_stage_t *stage, int32_t laye
     const ws_layout_t L = ws_layout(stage, n_tokens, n_ctx);
     int amax_cur = 0;
     LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
-    return run_block(stage, layer, cache, dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, chunk_index, t0,
-                     (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur);
+    return run_layers(stage, layer, layer + 1, cache, dev_x_inout, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6, 0, chunk_index, t0,
+                      (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur, false);
 }
 
 extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_t *cache, void *dev_x_inout, int32_t n_tokens,
@@ -354,16 +443,13 @@ extern "C" lvx_status_t lvx_denoise_stage(const lvx_stage_t *stage, lvx_kvcache_
     bf16_t *x = (bf16_t *)dev_x_inout;
     float *h = (float *)((char *)dev_workspace + L.h);
     const size_t n_elems = (size_t)n_tokens * d;
-    LVX_TRY(lvx_launch_widen(x, h, n_elems, (hipStream_t)stream));
+    LVX_TRY(widen_in(x, h, n_elems, (hipStream_t)stream));
     int amax_cur = 0;
     LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
-    for (int l = 0; l < stage->n_layers; ++l) {
-        const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
-        LVX_TRY(run_block(stage, l, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, m6, chunk_index, t0, (char *)dev_workspace, L,
-                          (hipStream_t)stream, &amax_cur));
-    }
+    LVX_TRY(run_layers(stage, 0, stage->n_layers, cache, h, n_tokens, (const bf16_t *)dev_ctx, n_ctx, dev_mod6_per_layer, (size_t)6 * d, chunk_index,
+                       t0, (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur, false));
     // Euler step of Alg. 3 / Alg. 4:  x <- x + v dt, the stack output standing in for the velocity
-    return lvx_launch_euler(x, h, dt, x, n_elems, (hipStream_t)stream);
+    return euler_out(x, h, dt, x, n_elems, (hipStream_t)stream);
 }
 
 // Warm-up of a (new) sink frame, Appendix D: after the first block the model's own output replaces the reference image as
@@ -380,23 +466,18 @@ extern "C" lvx_status_t lvx_sink_prefill(const lvx_stage_t *stage, lvx_kvcache_t
     LVX_REQUIRE(lvx_aligned16(dev_x_sink) && lvx_aligned16(dev_ctx) && (((uintptr_t)dev_workspace) & 255u) == 0, LVX_ERR_INVALID_ARG,
                 "x_sink / ctx must be 16-byte and workspace 256-byte aligned");
     LVX_REQUIRE(t_sink >= 0, LVX_ERR_INVALID_ARG, "t_sink must be non-negative");
+    LVX_REQUIRE(lvx_aligned16(dev_x_out), LVX_ERR_INVALID_ARG, "x_out must be 16-byte aligned");
     const size_t need = lvx_workspace_bytes(stage, n, n_ctx);
     LVX_REQUIRE(ws_bytes >= need, LVX_ERR_SHAPE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
     const ws_layout_t L = ws_layout(stage, n, n_ctx);
     const int d = stage->rope.n_heads * stage->rope.head_dim;
     float *h = (float *)((char *)dev_workspace + L.h);
-    LVX_TRY(lvx_launch_widen((const bf16_t *)dev_x_sink, h, (size_t)n * d, (hipStream_t)stream));
+    LVX_TRY(widen_in((const bf16_t *)dev_x_sink, h, (size_t)n * d, (hipStream_t)stream));
     int amax_cur = 0;
     LVX_TRY(call_begin(stage, (char *)dev_workspace, L, (hipStream_t)stream, n_ctx));
-    for (int l = 0; l < stage->n_layers; ++l) {
-        const float *m6 = dev_mod6_per_layer ? dev_mod6_per_layer + (size_t)l * 6 * d : nullptr;
-        LVX_TRY(run_block(stage, l, cache, h, n, (const bf16_t *)dev_ctx, n_ctx, m6, 0, t_sink, (char *)dev_workspace, L, (hipStream_t)stream,
-                          &amax_cur, true));
-    }
-    if (dev_x_out != nullptr) {
-        LVX_REQUIRE(lvx_aligned16(dev_x_out), LVX_ERR_INVALID_ARG, "x_out must be 16-byte aligned");
-        return lvx_launch_euler(nullptr, h, 1.0f, (bf16_t *)dev_x_out, (size_t)n * d, (hipStream_t)stream);
-    }
+    LVX_TRY(run_layers(stage, 0, stage->n_layers, cache, h, n, (const bf16_t *)dev_ctx, n_ctx, dev_mod6_per_layer, (size_t)6 * d, 0, t_sink,
+                       (char *)dev_workspace, L, (hipStream_t)stream, &amax_cur, true));
+    if (dev_x_out != nullptr) return euler_out(nullptr, h, 1.0f, (bf16_t *)dev_x_out, (size_t)n * d, (hipStream_t)stream);
     return LVX_OK;
 }
 

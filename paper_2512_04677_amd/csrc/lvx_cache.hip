@@ -43,7 +43,12 @@ __global__ void __launch_bounds__(256) lvx_fill_zero_kernel(uint4 *p, size_t n16
 template <int D>
 __global__ void __launch_bounds__(256) lvx_pack_kv_kernel(const bf16_t *__restrict__ k, const bf16_t *__restrict__ v, int64_t ld,
                                                           int n, int cap, int key0, int tile0, bf16_t *__restrict__ kp,
-                                                          bf16_t *__restrict__ vtp) {
+                                                          bf16_t *__restrict__ vtp, int64_t batch_stride_src, int64_t batch_stride_dst) {
+    // blockIdx.z: independent row set / packed array (the context values of several layers in one launch)
+    if (k != nullptr) k += (size_t)blockIdx.z * batch_stride_src;
+    v += (size_t)blockIdx.z * batch_stride_src;
+    kp += (size_t)blockIdx.z * batch_stride_dst;
+    vtp += (size_t)blockIdx.z * batch_stride_dst;
     constexpr int KT = LVX_KEY_TILE;
     constexpr int CPR = D / 8;        // 16-byte chunks per row
     constexpr int LDS_LD = D + 8;     // padded row, keeps 16-byte alignment
@@ -207,15 +212,18 @@ lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream) {
 }
 
 lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, int n, int H, int D, int cap, int key0,
-                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream) {
-    if (n <= 0) return LVX_OK;
+                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream, int n_batch, int64_t batch_stride_src,
+                                int64_t batch_stride_dst) {
+    if (n <= 0 || n_batch <= 0) return LVX_OK;
     const int tile0 = key0 / LVX_KEY_TILE;
     const int tile1 = (key0 + n - 1) / LVX_KEY_TILE;
-    dim3 grid(tile1 - tile0 + 1, H);
+    dim3 grid(tile1 - tile0 + 1, H, n_batch);
     if (D == 128)
-        hipLaunchKernelGGL(lvx_pack_kv_kernel<128>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed);
+        hipLaunchKernelGGL(lvx_pack_kv_kernel<128>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed,
+                           batch_stride_src, batch_stride_dst);
     else if (D == 64)
-        hipLaunchKernelGGL(lvx_pack_kv_kernel<64>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed);
+        hipLaunchKernelGGL(lvx_pack_kv_kernel<64>, grid, dim3(256), 0, stream, k, v, ld, n, cap, key0, tile0, k_packed, vt_packed,
+                           batch_stride_src, batch_stride_dst);
     else
         return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
     LVX_CHECK_HIP(hipGetLastError());
@@ -405,9 +413,13 @@ extern "C" lvx_status_t lvx_sink_rope_update(lvx_kvcache_t *c, const lvx_rope_de
     for (int l = l0; l < l1; ++l)
         LVX_REQUIRE(c->sink_t[l] != LVX_SINK_STATIC, LVX_ERR_STATE, "layer %d has no sink source (lvx_kvcache_reset_sink / lvx_sink_prefill)", l);
     const int d = c->desc.n_heads * c->desc.head_dim;
-    lvx_status_t st = lvx_launch_rope_to_packed_k(rope, c->sink_src + (size_t)l0 * c->sink_keys * d, d, c->sink_keys, t_sink,
-                                                  (bf16_t *)lvx_cache_k(c, l0), c->cap_keys, l1 - l0, (int64_t)c->sink_keys * d,
-                                                  (int64_t)c->layer_k_elems, (hipStream_t)stream);
+    lvx_status_t st;
+    {
+        lvx_prof_scope_t ps(LVX_PROF_SINK_ROPE, (hipStream_t)stream);
+        st = lvx_launch_rope_to_packed_k(rope, c->sink_src + (size_t)l0 * c->sink_keys * d, d, c->sink_keys, t_sink,
+                                         (bf16_t *)lvx_cache_k(c, l0), c->cap_keys, l1 - l0, (int64_t)c->sink_keys * d,
+                                         (int64_t)c->layer_k_elems, (hipStream_t)stream);
+    }
     if (st != LVX_OK) return st;
     for (int l = l0; l < l1; ++l) c->sink_t[l] = t_sink;
     return LVX_OK;
@@ -498,16 +510,22 @@ extern "C" lvx_status_t lvx_kvcache_gather(const lvx_kvcache_t *c, int32_t layer
     if (st != LVX_OK) return st;
     LVX_REQUIRE(first_key >= 0 && n_keys >= 0 && (int64_t)first_key + n_keys <= c->cap_keys, LVX_ERR_SHAPE,
                 "key range [%d,%d) outside the cache (%d keys)", first_key, first_key + n_keys, c->cap_keys);
+    return lvx_launch_gather_kv(lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->desc.n_heads, c->desc.head_dim, first_key, n_keys,
+                                (bf16_t *)dev_k_out, (bf16_t *)dev_v_out, ld, (hipStream_t)stream);
+}
+
+lvx_status_t lvx_launch_gather_kv(const bf16_t *k_packed, const bf16_t *vt_packed, int cap, int H, int D, int first_key, int n_keys,
+                                  bf16_t *k_out, bf16_t *v_out, int64_t ld, hipStream_t stream) {
     if (n_keys == 0) return LVX_OK;
-    const size_t total = (size_t)n_keys * c->desc.n_heads * (c->desc.head_dim / 8);
-    if (c->desc.head_dim == 128)
-        hipLaunchKernelGGL(lvx_gather_kv_kernel<128>, dim3(grid_for(total)), dim3(256), 0, (hipStream_t)stream, lvx_cache_k(c, layer),
-                           lvx_cache_vt(c, layer), c->cap_keys, c->desc.n_heads, first_key, n_keys, (bf16_t *)dev_k_out,
-                           (bf16_t *)dev_v_out, ld);
+    const size_t total = (size_t)n_keys * H * (D / 8);
+    if (D == 128)
+        hipLaunchKernelGGL(lvx_gather_kv_kernel<128>, dim3(grid_for(total)), dim3(256), 0, stream, k_packed, vt_packed, cap, H, first_key, n_keys,
+                           k_out, v_out, ld);
+    else if (D == 64)
+        hipLaunchKernelGGL(lvx_gather_kv_kernel<64>, dim3(grid_for(total)), dim3(256), 0, stream, k_packed, vt_packed, cap, H, first_key, n_keys,
+                           k_out, v_out, ld);
     else
-        hipLaunchKernelGGL(lvx_gather_kv_kernel<64>, dim3(grid_for(total)), dim3(256), 0, (hipStream_t)stream, lvx_cache_k(c, layer),
-                           lvx_cache_vt(c, layer), c->cap_keys, c->desc.n_heads, first_key, n_keys, (bf16_t *)dev_k_out,
-                           (bf16_t *)dev_v_out, ld);
+        return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }

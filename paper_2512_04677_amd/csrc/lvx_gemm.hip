@@ -78,7 +78,7 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, bool CONV>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     lvx_gemm_dma_kernel(const bf16_t *__restrict__ A, int64_t lda, const bf16_t *__restrict__ W, int64_t ldw, bf16_t *C, int64_t ldc,
                         int M, int N, int K, const bf16_t *R, int64_t ldr, const float *__restrict__ gate, int tiles_m, int tiles_n,
-                        int per_xcd, const bf16_t *__restrict__ W2, bf16_t *C2, int64_t ldc2, int N2, int split_tn, lvx_conv_map_t cm) {
+                        int per_xcd, lvx_gemm_segs_t segs, lvx_conv_map_t cm) {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int FM = WTM / 16, FN = WTN / 16;  // 16 x 16 accumulator blocks per wave
@@ -103,15 +103,19 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     const int in_band = widx - band * GROUP_M * tiles_n;
     const int tm = first_m + in_band % band_m;
     int tn = in_band / band_m;
-    // two projections of the same activations in one launch (tiles_n counts both): column tiles past split_tn belong to the
-    // second weight matrix and its own output (its own width and row stride)
-    const bool second = tn >= split_tn;
-    if (second) {
-        tn -= split_tn;
-        W = W2;
-        C = C2;
-        ldc = ldc2;
-        N = N2;
+    // several projections of the same activations in one launch (tiles_n counts all of them): the column tile's segment gives
+    // the weight matrix, the output, its width, its row stride and whether it is stored in fp32 (workgroup-uniform)
+    bool seg_f32 = false;
+    if (EPI == LVX_EPI_SEGMENTS) {
+        int sg = 0;
+        for (int i = 1; i < segs.n; ++i)
+            if (tn >= segs.s[i].tn_begin) sg = i;
+        tn -= segs.s[sg].tn_begin;
+        W = segs.s[sg].W;
+        C = reinterpret_cast<bf16_t *>(segs.s[sg].C);
+        ldc = segs.s[sg].ldc;
+        N = segs.s[sg].N;
+        seg_f32 = segs.s[sg].f32 != 0;
     }
 
     const int tid = threadIdx.x;
@@ -270,11 +274,11 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     // no DMA may still be in flight when the workgroup releases its LDS
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    if (EPI == LVX_EPI_DUAL_F32_BF16) {  // first projection stored in fp32, second in bf16 (workgroup-uniform branch)
-        if (second)
-            lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
-        else
+    if (EPI == LVX_EPI_SEGMENTS) {
+        if (seg_f32)
             lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE_F32>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+        else
+            lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
     } else {
         lvx_gemm_epilogue<FM, FN, EPI>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
     }
@@ -282,18 +286,28 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool CONV = false>
 lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, bf16_t *C, int64_t ldc, int M, int N, int K, int epi,
-                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const bf16_t *W2 = nullptr, bf16_t *C2 = nullptr,
-                    int64_t ldc2 = 0, int N2 = 0, const lvx_conv_map_t *conv = nullptr) {
+                    const bf16_t *R, int64_t ldr, const float *gate, hipStream_t stream, const lvx_gemm_segs_t *seg_table = nullptr,
+                    const lvx_conv_map_t *conv = nullptr) {
     lvx_conv_map_t cm = {};
     if (conv != nullptr) cm = *conv;
-    const int split_tn = W2 != nullptr ? (N + BN - 1) / BN : 0x7fffffff;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN + (W2 != nullptr ? (N2 + BN - 1) / BN : 0);
+    lvx_gemm_segs_t segs;
+    segs.n = 0;
+    int tiles_n = (N + BN - 1) / BN;
+    if (seg_table != nullptr) {  // column tiles of all segments, one after the other
+        segs = *seg_table;
+        tiles_n = 0;
+        for (int i = 0; i < segs.n; ++i) {
+            segs.s[i].tn_begin = tiles_n;
+            tiles_n += (segs.s[i].N + BN - 1) / BN;
+        }
+    }
+    const int tiles_m = (M + BM - 1) / BM;
     const int total = tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
     hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_, CONV>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \
-                       R, ldr, gate, tiles_m, tiles_n, per_xcd, W2, C2, ldc2, N2, split_tn, cm)
+                       R, ldr, gate, tiles_m, tiles_n, per_xcd, segs, cm)
     if (epi == LVX_EPI_STORE) {
         LVX_GEMM_LAUNCH(LVX_EPI_STORE);
     } else if (epi == LVX_EPI_GELU_TANH) {
@@ -306,8 +320,8 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
         LVX_GEMM_LAUNCH(LVX_EPI_BIAS);
     } else if (epi == LVX_EPI_STORE_F32) {
         LVX_GEMM_LAUNCH(LVX_EPI_STORE_F32);
-    } else if (epi == LVX_EPI_DUAL_F32_BF16) {
-        LVX_GEMM_LAUNCH(LVX_EPI_DUAL_F32_BF16);
+    } else if (epi == LVX_EPI_SEGMENTS) {
+        LVX_GEMM_LAUNCH(LVX_EPI_SEGMENTS);
     } else {
         LVX_GEMM_LAUNCH(LVX_EPI_BIAS_SILU);
     }
@@ -340,8 +354,22 @@ lvx_status_t lvx_launch_linear_dual(const bf16_t *A, int64_t lda, const bf16_t *
                                     int c1_is_f32, bf16_t *C2, int64_t ldc2, int M, int N1, int N2, int K, hipStream_t stream) {
     LVX_TRY(check_dual(A, lda, W1, W2, ldw, C1, ldc1, C2, ldc2, M, N1, N2, K));
     if (M == 0) return LVX_OK;
-    return launch<128, 256, 2, 4>(A, lda, W1, ldw, (bf16_t *)C1, ldc1, M, N1, K, c1_is_f32 ? (int)LVX_EPI_DUAL_F32_BF16 : (int)LVX_EPI_STORE, nullptr,
-                                  0, nullptr, stream, W2, C2, ldc2, N2);
+    lvx_gemm_segs_t segs;
+    segs.n = 2;
+    segs.s[0] = {W1, C1, ldc1, N1, 0, c1_is_f32 ? 1 : 0, 0};
+    segs.s[1] = {W2, C2, ldc2, N2, 0, 0, 0};
+    return launch<128, 256, 2, 4>(A, lda, W1, ldw, (bf16_t *)C1, ldc1, M, N1, K, (int)LVX_EPI_SEGMENTS, nullptr, 0, nullptr, stream, &segs);
+}
+
+// Up to LVX_GEMM_MAX_SEGS projections of the same activations in one launch (same K, same weight row stride; each with its own
+// weight matrix, output, width and row stride; bf16 or fp32 plain store): the context's K and V projections of several layers.
+lvx_status_t lvx_launch_linear_segments(const bf16_t *A, int64_t lda, int64_t ldw, const lvx_gemm_segs_t &segs, int M, int K, hipStream_t stream) {
+    LVX_REQUIRE(segs.n >= 1 && segs.n <= LVX_GEMM_MAX_SEGS, LVX_ERR_INVALID_ARG, "linear segments: %d segments (1..%d)", segs.n, LVX_GEMM_MAX_SEGS);
+    for (int i = 0; i < segs.n; ++i)
+        LVX_TRY(check_dual(A, lda, segs.s[i].W, segs.s[i].W, ldw, segs.s[i].C, segs.s[i].ldc, segs.s[i].C, segs.s[i].ldc, M, segs.s[i].N, segs.s[i].N, K));
+    if (M == 0) return LVX_OK;
+    return launch<128, 256, 2, 4>(A, lda, segs.s[0].W, ldw, (bf16_t *)segs.s[0].C, segs.s[0].ldc, M, segs.s[0].N, K, (int)LVX_EPI_SEGMENTS, nullptr, 0,
+                                  nullptr, stream, &segs);
 }
 
 extern "C" lvx_status_t lvx_linear_dual(const void *dev_a, int64_t lda, const void *dev_w1, const void *dev_w2, int64_t ldw, void *dev_c1,
@@ -357,7 +385,7 @@ lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, con
                                   bf16_t *Y, int64_t ldy, int M, int N, hipStream_t stream) {
     const int K = 27 * cm.C;
     return launch<256, 128, 4, 2, true>(P, 0, Wt, ldw, Y, ldy, M, N, K, act ? (int)LVX_EPI_BIAS_SILU : (int)LVX_EPI_BIAS, nullptr, 0, bias, stream,
-                                        nullptr, nullptr, 0, 0, &cm);
+                                        nullptr, &cm);
 }
 
 extern "C" lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64_t ldw, void *dev_c, int64_t ldc, int32_t M,

@@ -57,10 +57,15 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
     const float e = __builtin_amdgcn_exp2f(-2.0f * 1.4426950408889634f * u);
     return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
-// direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane
+// direct-to-LDS load of 16 bytes per lane: LDS byte address = lds_addr (wave-uniform, goes to M0) + 16 * lane.
+// The statement writes M0 and says so in its clobber list, so the compiler never assumes a value of its own survives in M0
+// across it (clang notes that M0 is a reserved register it cannot save and restore around the statement: nothing here asks it to).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(gbase), "s"(lds_addr) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // ---- cache handle (host) ----------------------------------------------------------------------
 struct lvx_kvcache {
@@ -81,8 +86,10 @@ static inline const bf16_t *lvx_cache_vt(const lvx_kvcache *c, int layer) { retu
 
 // ---- internal launchers (all enqueue on `stream`, arguments already validated) ----------------
 // Token-major K/V rows [n][ld] -> packed K [H][cap][D] rows key0.. and V^T tiles [H][cap/64][D][64] (k NULL: values only).
+// n_batch > 1: that many independent row sets / packed arrays, batch_stride_src / batch_stride_dst elements apart.
 lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, int n, int H, int D, int cap, int key0,
-                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream);
+                                bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream, int n_batch = 1, int64_t batch_stride_src = 0,
+                                int64_t batch_stride_dst = 0);
 // Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
@@ -101,6 +108,11 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// RMSNorm (no rotation) of n_batch sets of token-major rows (bf16, or fp32 with strides in fp32 elements), written straight into n_batch packed K arrays [H][cap][D]
+// from key 0 on; gains[b] is batch b's gain vector (NULL: that batch is copied un-normalised).  n_batch <= LVX_GEMM_MAX_SEGS.
+lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,
+                                         const float *const *gains, bf16_t *k_packed, int cap, int n_batch, int64_t batch_stride_src,
+                                         int64_t batch_stride_dst, hipStream_t stream);
 // y = x / sqrt(mean(x^2) + eps) * g on fp32 rows, fp32 out, no rounding (g NULL: plain copy): the sink warm-up's un-rotated keys.
 lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x, int64_t ld_in, const float *g, int n_tokens, float *y,
                                     int64_t ld_out, hipStream_t stream);
@@ -123,8 +135,22 @@ lvx_status_t lvx_launch_conv_gemm(const bf16_t *P, const lvx_conv_map_t &cm, con
 // C1[M][N1] = A W1^T (bf16, or fp32 if c1_is_f32), C2[M][N2] = A W2^T (bf16) in one launch, plain store.
 lvx_status_t lvx_launch_linear_dual(const bf16_t *A, int64_t lda, const bf16_t *W1, const bf16_t *W2, int64_t ldw, void *C1, int64_t ldc1,
                                     int c1_is_f32, bf16_t *C2, int64_t ldc2, int M, int N1, int N2, int K, hipStream_t stream);
-// internal epilogue id of the GEMM kernel: first projection of a dual launch stored in fp32, second in bf16
-#define LVX_EPI_DUAL_F32_BF16 100
+// Several projections of the same activations in one GEMM launch: segment i owns the column tiles from tn_begin on (filled in
+// by the launcher) and has its own weight matrix [N][ldw], output (bf16, or fp32 if f32), output row stride and width.
+#define LVX_GEMM_MAX_SEGS 16
+struct lvx_gemm_seg_t {
+    const bf16_t *W;
+    void *C;
+    int64_t ldc;
+    int32_t N, tn_begin, f32, pad;
+};
+struct lvx_gemm_segs_t {
+    int32_t n, pad;
+    lvx_gemm_seg_t s[LVX_GEMM_MAX_SEGS];
+};
+lvx_status_t lvx_launch_linear_segments(const bf16_t *A, int64_t lda, int64_t ldw, const lvx_gemm_segs_t &segs, int M, int K, hipStream_t stream);
+// internal epilogue id of the GEMM kernel: plain store per segment (bf16 or fp32)
+#define LVX_EPI_SEGMENTS 100
 // Per-tensor dynamic FP8 quantisation of a bf16 matrix.  The amax is collected in an array of LVX_AMAX_SLOTS fp32 bit patterns
 // (256 bytes, zero before the producers write): either by lvx_launch_fp8_amax, or by the kernel that produced x (attention,
 // the GELU epilogue of an FP8 linear), which saves the extra pass.  (The LayerNorm kernel does not: its one-row waves would
@@ -140,5 +166,16 @@ lvx_status_t lvx_launch_fp8_quantize(const bf16_t *x, int64_t ld, int rows, int 
 lvx_status_t lvx_launch_linear_fp8(const void *dev_aq, int64_t lda, const float *dev_scale_a, const void *dev_wq, int64_t ldw,
                                    const float *dev_scale_w, void *dev_c, int64_t ldc, int32_t M, int32_t N, int32_t K, lvx_epilogue_t epi,
                                    const void *dev_resid, int64_t ldr, const float *dev_gate, uint32_t *amax_slots, hipStream_t stream);
+// Optional HIP-event timing of a kernel class on the caller's stream (lvx_profile_set / lvx_profile_read): the events are
+// recorded around the launches made while the object lives.
+struct lvx_prof_scope_t {
+    hipStream_t st;
+    void *pair;
+    lvx_prof_scope_t(int kind, hipStream_t stream);
+    ~lvx_prof_scope_t();
+};
+// Packed K [H][cap][D] / V^T tiles -> token-major rows [n_keys][ld] from key first_key on (bit-exact).
+lvx_status_t lvx_launch_gather_kv(const bf16_t *k_packed, const bf16_t *vt_packed, int cap, int H, int D, int first_key, int n_keys,
+                                  bf16_t *k_out, bf16_t *v_out, int64_t ld, hipStream_t stream);
 // Zero fill by kernel (not a memset node, so callers may capture it in a HIP graph); bytes % 16 == 0.
 lvx_status_t lvx_launch_fill_zero(void *dst, size_t bytes, hipStream_t stream);

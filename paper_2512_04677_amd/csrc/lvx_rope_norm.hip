@@ -12,6 +12,11 @@
 
 namespace {
 
+struct gain_table_t {  // per-batch gain vectors of the k input (n = 0: g_k serves every batch)
+    int32_t n, pad;
+    const float *g[LVX_GEMM_MAX_SEGS];
+};
+
 struct rope_table_t {
     double inv_freq[64];  // theta^(-2k/d_a) of pair p (p = global pair index inside the head)
     int32_t axis[64];     // 0 = t, 1 = y, 2 = x
@@ -32,7 +37,8 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     lvx_rope_norm_kernel(const void *q_in, const void *k_in, int64_t ld_in,
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
                          bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
-                         float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out) {
+                         float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out,
+                         gain_table_t gtab) {
     // n_batch independent row sets of n_tokens rows each (the sink keys of several layers in one launch); positions and t0
     // are those of the row inside its set
     const int lane = threadIdx.x & 63;
@@ -64,7 +70,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     for (int which = 0; which < 2; ++which) {
         const void *in = which == 0 ? q_in : k_in;
         bf16_t *outp = which == 0 ? q_out : k_out;
-        const float *g = which == 0 ? g_q : g_k;
+        const float *g = which == 0 ? g_q : (gtab.n > 0 ? gtab.g[batch] : g_k);
         if (in == nullptr) continue;
         const size_t row_off = (size_t)batch * batch_stride_in + (size_t)token * ld_in;
         float x[CPL][8];
@@ -219,7 +225,9 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
 static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, const void *k_in, int64_t ld_in, const float *g_q,
                                 const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
                                 hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0,
-                                bool f32_in = false) {
+                                bool f32_in = false, const gain_table_t *gains = nullptr) {
+    gain_table_t gtab = {};
+    if (gains != nullptr) gtab = *gains;
     const int d = desc->n_heads * desc->head_dim;
     rope_table_t tab;
     for (int p = 0; p < 64; ++p) {
@@ -239,7 +247,7 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, c
 #define LVX_ROPE_LAUNCH(CPL, F32)                                                                                                \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, F32>), grid, block, 0, stream, q_in, k_in, ld_in, g_q, g_k, n_tokens, t0, q_out, k_out, \
                        ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab, n_batch,  \
-                       batch_stride_in, batch_stride_out)
+                       batch_stride_in, batch_stride_out, gtab)
     if (f32_in) {
         if (cpl <= 2)
             LVX_ROPE_LAUNCH(2, true);
@@ -303,6 +311,22 @@ lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const floa
                        (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst, true);
 }
 
+lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,
+                                         const float *const *gains, bf16_t *k_packed, int cap, int n_batch, int64_t batch_stride_src,
+                                         int64_t batch_stride_dst, hipStream_t stream) {
+    lvx_status_t st = check_rope_desc(desc);
+    if (st != LVX_OK) return st;
+    LVX_REQUIRE(n_batch >= 0 && n_batch <= LVX_GEMM_MAX_SEGS, LVX_ERR_INVALID_ARG, "norm to packed K: %d batches (0..%d)", n_batch, LVX_GEMM_MAX_SEGS);
+    if (n_tokens == 0 || n_batch == 0) return LVX_OK;
+    lvx_rope_desc_t norm_only = *desc;
+    norm_only.apply_rope = 0;
+    gain_table_t gt = {};
+    gt.n = n_batch;
+    for (int b = 0; b < n_batch; ++b) gt.g[b] = gains[b];
+    return launch_rope(&norm_only, nullptr, src, ld_src, nullptr, nullptr, n_tokens, 0, nullptr, k_packed, desc->head_dim,
+                       (int64_t)cap * desc->head_dim, stream, n_batch, batch_stride_src, batch_stride_dst, src_is_f32 != 0, &gt);
+}
+
 lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x, int64_t ld_in, const float *g, int n_tokens, float *y,
                                     int64_t ld_out, hipStream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
@@ -315,7 +339,7 @@ lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x,
 #define LVX_NORM32_LAUNCH(CPL)                                                                                                     \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, true, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, \
                        (const float *)nullptr, g, n_tokens, 0, (bf16_t *)nullptr, (bf16_t *)y, ld_out, (int64_t)desc->head_dim, d,    \
-                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0)
+                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{})
     if (cpl <= 2)
         LVX_NORM32_LAUNCH(2);
     else if (cpl <= 10)

@@ -403,6 +403,38 @@ def test_linear_dual_and_fp32_store(lvx, M, N1, N2, K):
     assert torch.equal(c32b, c32[:, :N1])                                    # same kernel, same accumulation order
 
 
+@pytest.mark.parametrize("preset,n_layers", [("tiny", 3), ("small", 8)])
+def test_context_kv_group_projection_norm_and_pack(lvx, preset, n_layers):
+    """The cross-attention keys / values of a group of layers from one GEMM launch (2 x n_layers projections of the same context),
+    the batched RMSNorm into the packed layout and the batched V transpose: every layer against the oracle, with per-layer
+    gains (one layer without a gain vector: no norm), a context length that does not fill its last 64-key tile."""
+    p = S.PRESETS[preset]
+    d, _, chunk_n = dims(p)
+    H, D = p["n_heads"], p["head_dim"]
+    layers = [S.block_weights(d, p["ffn"], l, "ctxkv_" + preset, std=1.0 / math.sqrt(d), device=DEV) for l in range(n_layers)]
+    for l, w in enumerate(layers):
+        w["gc_k"] = None if l == 1 else (1.0 + S.randn_f32((d,), S.seed_of("ctxkv_g", l), 0.2)).to(DEV)
+    rope = lvx.rope_desc(H, D, p["rope_axes"], 10000.0, p["frame_h"], p["frame_w"])
+    stage = lvx.StageHandle(layers, rope, p["ffn"])
+    n_ctx = p["n_ctx"] + 3
+    ctx = S.randn_bf16((n_ctx, d), S.seed_of("ctxkv_ctx", preset), device=DEV)
+    ws = torch.empty(lvx.lvx_workspace_bytes(stage, 1, n_ctx), dtype=torch.uint8, device=DEV)
+    for l0, g in ((0, n_layers), (1, 2)):
+        k = torch.empty((g, n_ctx, d), dtype=torch.bfloat16, device=DEV)
+        v = torch.empty_like(k)
+        lvx.lvx_context_kv(stage, l0, g, ctx, k, v, ws)
+        torch.cuda.synchronize()
+        for j in range(g):
+            w = S.weights_to_f64({n: t for n, t in layers[l0 + j].items() if t is not None})
+            k_ref = O.linear(S.to_f64(ctx), w["Wc_k"])
+            if layers[l0 + j]["gc_k"] is not None:
+                k_ref = O.rmsnorm(k_ref, w["gc_k"], 1e-6)
+            assert_close(k[j], k_ref, "%s context keys, layer %d" % (preset, l0 + j), relative_to_rms=True)
+            assert_close(v[j], O.linear(S.to_f64(ctx), w["Wc_v"]), "%s context values, layer %d" % (preset, l0 + j), relative_to_rms=True)
+    with pytest.raises(lvx.LvxError):
+        lvx.lvx_context_kv(stage, n_layers - 1, 2, ctx, k, v, ws)
+
+
 # ------------------------------------------------------------------------------------------------ block / stage
 def stage_setup(lvx, preset, n_layers, tag, n_caches=1):
     p = S.PRESETS[preset]
