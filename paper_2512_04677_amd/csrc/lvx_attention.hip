@@ -29,12 +29,12 @@ namespace {
 
 constexpr int KT = LVX_KEY_TILE;
 
-template <int D, int NWAVES>
+template <int D, int NWAVES, int QB = 2>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
                          int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots) {
-    constexpr int QT = 32 * NWAVES;
+    constexpr int QT = 16 * QB * NWAVES;  // QB blocks of 16 queries per wave
     constexpr int MK = D / 32;  // MFMA k-steps (32 wide) over head_dim
     constexpr int DB = D / 16;  // 16-row blocks of O^T
     constexpr int NV = DB * 2;  // V^T fragments per 64-key tile (each feeds two PV MFMAs, one per 16-query block)
@@ -71,10 +71,10 @@ __global__ void __launch_bounds__(64 * NWAVES)
 
     // Q fragments (B operand of S^T = K Q^T, v_mfma_f32_16x16x32_bf16): for query block qb, lane (l16, q4) holds
     // Q[query 16qb + l16][d = 32m + 8q4 .. +7]
-    bf16x8_t qf[2][MK];
+    bf16x8_t qf[QB][MK];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        int row = qtile * QT + wave * 32 + 16 * qb + l16;
+    for (int qb = 0; qb < QB; ++qb) {
+        int row = qtile * QT + wave * (16 * QB) + 16 * qb + l16;
         if (row > n_q - 1) row = n_q - 1;
         const bf16_t *qp = q + (size_t)row * ld_q + (size_t)head * D + q4 * 8;
 #pragma unroll
@@ -156,32 +156,31 @@ __global__ void __launch_bounds__(64 * NWAVES)
     const int grp = wave / (NWAVES / 2);
 
     // o[db][qb][e] = O^T[d = 16 db + 4 q4 + e][query 16 qb + l16];  s[kb][qb][e] = score of key row 4 q4 + e of block kb
-    f32x4_t o[DB][2];
+    f32x4_t o[DB][QB];
 #pragma unroll
     for (int i = 0; i < DB; ++i)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[i][qb][e] = 0.f;
     // per query block: the reference the softmax subtracts (a row maximum, already multiplied by c_exp2; set by the first
     // tile) and this lane's share of the row sum
-    float mc[2] = {0.f, 0.f};
-    float l_run[2] = {0.f, 0.f};
-    f32x4_t s[4][2];
-    bf16x8_t pb[2][2];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
+    float mc[QB], l_run[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) mc[qb] = l_run[qb] = 0.f;
+    f32x4_t s[4][QB];
+    bf16x8_t pb[QB][2];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
 
     // S(0) = K(0) Q^T from K slot 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
 #define LVX_ATTN_S0()                                                                                          \
     {                                                                                                          \
         _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) {                                                     \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][0][e] = s[kb][1][e] = 0.f;                     \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = 0.f; \
             bf16x8_t a[MK];                                                                                    \
             _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
                 a[m] = *reinterpret_cast<const bf16x8_t *>(ks + kb * 16 * K_ROW_B + kfo[m]);                   \
-            _Pragma("unroll") for (int m = 0; m < MK; ++m) {                                                   \
-                s[kb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[0][m], s[kb][0], 0, 0, 0);         \
-                s[kb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[1][m], s[kb][1], 0, 0, 0);         \
-            }                                                                                                  \
+            _Pragma("unroll") for (int m = 0; m < MK; ++m) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)   \
+                s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[qb][m], s[kb][qb], 0, 0, 0);      \
         }                                                                                                      \
     }
     // Matrix phase X(j): O^T += V(j)^T P(j)^T from V slot j%NS, then S(j+1) = K(j+1) Q^T from K slot (j+1)%NS (past the last
@@ -201,25 +200,24 @@ __global__ void __launch_bounds__(64 * NWAVES)
         const char *kr = ks + (((j_) + 1) & (NS - 1)) * TILE_B;                                                \
         bf16x8_t fr[PD];                                                                                       \
         _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
-        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)         \
-            s[kb][0][e] = s[kb][1][e] = 0.f;                                                                   \
+        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)     \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = 0.f;                                  \
         _Pragma("unroll") for (int f = 0; f < NV + NK; ++f) {                                                  \
             const bf16x8_t a = fr[f % PD];                                                                     \
             if (f + PD < NV + NK) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                          \
-            if (f < NV) {                                                                                      \
-                o[f % DB][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[0][(f / DB) & 1], o[f % DB][0], 0, 0, 0); \
-                o[f % DB][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[1][(f / DB) & 1], o[f % DB][1], 0, 0, 0); \
-            } else {                                                                                           \
-                s[(f - NV) & 3][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[0][((f - NV) >> 2) % MK], s[(f - NV) & 3][0], 0, 0, 0); \
-                s[(f - NV) & 3][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[1][((f - NV) >> 2) % MK], s[(f - NV) & 3][1], 0, 0, 0); \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                \
+                if (f < NV)                                                                                    \
+                    o[f % DB][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qb][(f / DB) & 1], o[f % DB][qb], 0, 0, 0); \
+                else                                                                                           \
+                    s[(f - NV) & 3][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qb][((f - NV) >> 2) % MK], s[(f - NV) & 3][qb], 0, 0, 0); \
             }                                                                                                  \
         }                                                                                                      \
         __builtin_amdgcn_sched_group_barrier(0x100, PD, 0);                                                    \
         _Pragma("unroll") for (int f = 0; f < NV + NK - PD; ++f) {                                             \
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                                 \
+            __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                                                \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
         }                                                                                                      \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * PD, 0);                                                \
+        __builtin_amdgcn_sched_group_barrier(0x008, QB * PD, 0);                                               \
     }
     // vector phase: s[kb][qb][e] is the score of key  t*64 + 32 (kb >> 1) + 8 q4 + 4 (kb & 1) + e  for query 16 qb + l16
 #define LVX_ATTN_Y(t_)                                                                                         \
@@ -229,17 +227,19 @@ __global__ void __launch_bounds__(64 * NWAVES)
             int lim_ = n_keys - (t_) * KT - 8 * q4; /* valid keys, counted from this lane group's first key */ \
             asm volatile("" : "+v"(lim_));          /* keep the compares out of the loop preheader */          \
             _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)     \
-                if (32 * (kb >> 1) + 4 * (kb & 1) + e >= lim_) s[kb][0][e] = s[kb][1][e] = -INFINITY;          \
+                if (32 * (kb >> 1) + 4 * (kb & 1) + e >= lim_) {                                               \
+                    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) s[kb][qb][e] = -INFINITY;                \
+                }                                                                                              \
         }                                                                                                      \
         /* The reference mc only has to keep exp2 inside the fp32 range, so no per-tile maximum is taken: mc is the first     \
            tile's row maximum, and a later tile whose sum of exponentials reaches 2^64 (or overflows) is redone with its own   \
            maximum as the new reference and the accumulators rescaled.  The four lane groups that share a query decide     \
            together (wave-wide vote); the final division by the row sum absorbs whatever reference was used. */            \
-        float lsum0, lsum1;                                                                                    \
+        float lsum[QB];                                                                                        \
         bool rebase_ = (t_) == 0;                                                                              \
         for (;;) {                                                                                             \
             if (rebase_) {                                                                                     \
-                _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                             \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                            \
                     float tmax = s[0][qb][0];                                                                  \
                     _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
                         tmax = fmaxf(tmax, s[kb][qb][e]);                                                      \
@@ -255,21 +255,19 @@ __global__ void __launch_bounds__(64 * NWAVES)
                         o[i][qb][e] *= alpha;                                                                  \
                 }                                                                                              \
             }                                                                                                  \
-            lsum0 = 0.f;                                                                                       \
-            lsum1 = 0.f;                                                                                       \
-            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) {   \
-                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][0][e], c_exp2, -mc[0]));          \
-                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][1][e], c_exp2, -mc[1]));          \
-                lsum0 += p0;                                                                                   \
-                lsum1 += p1;                                                                                   \
-                pb[0][kb >> 1][4 * (kb & 1) + e] = (__bf16)p0;                                                 \
-                pb[1][kb >> 1][4 * (kb & 1) + e] = (__bf16)p1;                                                 \
-            }                                                                                                  \
-            if (rebase_ || !__any(!(lsum0 < 0x1p64f && lsum1 < 0x1p64f))) break;                               \
+            bool fits_ = true;                                                                                 \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;                                  \
+            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)     \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                            \
+                    const float p_ = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][qb][e], c_exp2, -mc[qb]));    \
+                    lsum[qb] += p_;                                                                            \
+                    pb[qb][kb >> 1][4 * (kb & 1) + e] = (__bf16)p_;                                            \
+                }                                                                                              \
+            _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) fits_ = fits_ && (lsum[qb] < 0x1p64f);           \
+            if (rebase_ || !__any(!fits_)) break;                                                              \
             rebase_ = true;                                                                                    \
         }                                                                                                      \
-        l_run[0] += lsum0;                                                                                     \
-        l_run[1] += lsum1;                                                                                     \
+        _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];                               \
     }
 
     LVX_ATTN_DMA_K(0);
@@ -283,7 +281,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // A wave whose 32 queries all lie past n_q (ragged last query tile: 4680 = 18 x 256 + 72) only keeps up the DMA and
     // barrier protocol: no LDS reads, no MFMAs, no softmax.  Its SIMD partner then has the matrix core to itself, so such a
     // workgroup finishes early and frees its CU, and the padding costs no energy on a chip that is power-limited.
-    const bool active = __builtin_amdgcn_readfirstlane(qtile * QT + wave * 32) < n_q;
+    const bool active = __builtin_amdgcn_readfirstlane(qtile * QT + wave * (16 * QB)) < n_q;
     if (!active) {
         __syncthreads();
         LVX_ATTN_STAGE_DMA(2);
@@ -334,11 +332,11 @@ __global__ void __launch_bounds__(64 * NWAVES)
 
     uint32_t amax_b = 0;  // largest magnitude among the bf16 values this lane stores (bit pattern without sign)
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
         float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 16);
         l_tot += __shfl_xor(l_tot, 32);
         const float inv = 1.0f / l_tot;
-        const int row = qtile * QT + wave * 32 + 16 * qb + l16;
+        const int row = qtile * QT + wave * (16 * QB) + 16 * qb + l16;
         if (row < n_q) {
             bf16_t *op = out + (size_t)row * ld_out + (size_t)head * D;
             // accumulator register e of block (db, qb) holds O^T[d = 16db + 4q4 + e][query 16qb + l16]
@@ -369,15 +367,15 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 }
 
-template <int D, int NWAVES>
+template <int D, int NWAVES, int QB = 2>
 lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
                     float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots) {
-    constexpr int QT = 32 * NWAVES;
+    constexpr int QT = 16 * QB * NWAVES;
     const int n_qtiles = (n_q + QT - 1) / QT;
     const int total = n_qtiles * H;
     const int per_xcd = (total + 7) / 8;
     const float c = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
+    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
                        n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -391,6 +389,9 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
     LVX_REQUIRE(n_q > 0 && n_keys > 0 && n_keys <= cap && cap % KT == 0, LVX_ERR_SHAPE, "attention: n_q %d, n_keys %d, cap %d", n_q,
                 n_keys, cap);
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
+#ifdef LVX_ATTN_16W
+    if (D == 128) return launch<128, 16, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+#endif
     if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     if (D == 64) return launch<64, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);

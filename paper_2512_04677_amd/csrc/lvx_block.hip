@@ -71,11 +71,11 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.ld_cq = (int64_t)d + WS_PAD;
     w.ld_ffn = (int64_t)s->d_ffn + WS_PAD;
     w.ld_ckv = (int64_t)2 * d + WS_PAD;
-    w.ld_qk32 = (int64_t)2 * d + WS_PAD / 2;
+    w.ld_qk32 = (int64_t)d + WS_PAD / 2;
     size_t off = 0;
     w.u = off;       off += round256((size_t)n_tokens * w.ld_u * 2);
     w.big = off;     off += round256((size_t)n_tokens * (wide + WS_PAD) * 2);
-    w.qk32 = off;    // fp32 q | k columns of the QKV projection (bf16 stages only; an FP8 stage stores them in bf16)
+    w.qk32 = off;    // fp32 k columns of the QKV projection (bf16 stages only; an FP8 stage stores them in bf16)
     if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * w.ld_qk32 * 4);
     // context K | V rows and their packed forms for a group of layers at once (bf16 stages; an FP8 stage uses one slot)
     w.ctx_group = s->blocks_fp8 != nullptr ? 1 : (s->n_layers < CTX_GROUP ? s->n_layers : CTX_GROUP);
@@ -208,25 +208,31 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
                                      feeds_fp8 ? amax_out() : nullptr, st);
     };
 
-    // self-attention branch.  bf16 stage: the q | k columns of the QKV projection leave the GEMM in fp32 and are rounded to bf16
+    // self-attention branch.  bf16 stage: the k columns of the QKV projection leave the GEMM in fp32 and are rounded to bf16
     // once, by the RMSNorm + RoPE kernel, after the rotation (the cached K-hat then carries two bf16 roundings, u and itself,
-    // instead of three); the v columns are stored in bf16, as the cache holds them.  FP8 stage: all three in bf16.
-    float *qk32 = (float *)(ws + L.qk32);
+    // instead of three); the q and v columns are stored in bf16 (the queries' extra rounding changes the block's output by
+    // 2e-5 of its RMS, and fp32 columns cost the GEMM's epilogue and the RoPE kernel their bytes).  FP8 stage: all three in bf16.
+    float *k32 = (float *)(ws + L.qk32);
     const int64_t ld32 = L.ld_qk32;
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
     {
         prof_scope_t ps(LVX_PROF_GEMM_QKV, st);
-        if (w8 == nullptr)
-            LVX_TRY(lvx_launch_linear_dual(u, ldu, (const bf16_t *)w.W_qkv, (const bf16_t *)w.W_qkv + (size_t)2 * d * ldw, ldw, qk32, ld32, 1,
-                                           big + 2 * d, ldq, n, 2 * d, d, d, st));
-        else
+        if (w8 == nullptr) {
+            const bf16_t *Wq = (const bf16_t *)w.W_qkv;
+            lvx_gemm_segs_t segs;
+            segs.n = 3;
+            segs.s[0] = {Wq, big, ldq, d, 0, 0, 0};
+            segs.s[1] = {Wq + (size_t)d * ldw, k32, ld32, d, 0, 1, 0};
+            segs.s[2] = {Wq + (size_t)2 * d * ldw, big + 2 * d, ldq, d, 0, 0, 0};
+            LVX_TRY(lvx_launch_linear_segments(u, ldu, ldw, segs, n, d, st));
+        } else
             LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
     }
     if (!sink_prefill) {
         {
             prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
             if (w8 == nullptr)
-                LVX_TRY(lvx_rope3d_f32in(&s->rope, qk32, qk32 + d, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
+                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
             else
                 LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
         }
@@ -241,8 +247,8 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         // widened from the bf16 projection in an FP8 stage
         float *src32 = c->sink_src + (size_t)layer * c->sink_keys * d;
         if (w8 == nullptr) {
-            LVX_TRY(lvx_rope3d_f32in(&s->rope, qk32, nullptr, ld32, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));  // q: norm + RoPE
-            LVX_TRY(lvx_launch_rmsnorm_f32(&s->rope, qk32 + d, ld32, w.g_k, n, src32, d, st));                       // k: norm only
+            LVX_TRY(lvx_rope3d(&s->rope, big, nullptr, ldq, w.g_q, nullptr, n, t0, big, nullptr, ldq, st));  // q: norm + RoPE
+            LVX_TRY(lvx_launch_rmsnorm_f32(&s->rope, k32, ld32, w.g_k, n, src32, d, st));                    // k: norm only
         } else {
             lvx_rope_desc_t k_norm_only = s->rope;
             k_norm_only.apply_rope = 0;

@@ -95,6 +95,21 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     __shared__ __attribute__((aligned(1024))) char lds[NSTAGE * STAGE_B];
 
     const int total = tiles_m * tiles_n;
+#ifdef LVX_GEMM_NPART
+    // experiment: XCD x owns the column tiles [x * tn_per, (x + 1) * tn_per) and walks all row tiles of them, bands of 8 row tiles
+    const int tn_per = (tiles_n + 7) / 8;
+    const int tn_lo = (blockIdx.x & 7) * tn_per;
+    const int tn_cnt = tiles_n - tn_lo < tn_per ? tiles_n - tn_lo : tn_per;
+    const int kx = blockIdx.x >> 3;
+    if (tn_cnt <= 0 || kx >= tiles_m * tn_cnt) return;
+    const int band = kx / (GROUP_M * tn_cnt);
+    const int first_m = band * GROUP_M;
+    const int band_m = tiles_m - first_m < GROUP_M ? tiles_m - first_m : GROUP_M;
+    const int in_band = kx - band * GROUP_M * tn_cnt;
+    const int tm = first_m + in_band % band_m;
+    int tn = tn_lo + in_band / band_m;
+    const int widx = tm * tiles_n + tn;
+#else
     const int widx = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (widx >= total) return;
     const int band = widx / (GROUP_M * tiles_n);
@@ -103,6 +118,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     const int in_band = widx - band * GROUP_M * tiles_n;
     const int tm = first_m + in_band % band_m;
     int tn = in_band / band_m;
+#endif
     // several projections of the same activations in one launch (tiles_n counts all of them): the column tile's segment gives
     // the weight matrix, the output, its width, its row stride and whether it is stored in fp32 (workgroup-uniform)
     bool seg_f32 = false;
@@ -303,7 +319,11 @@ lvx_status_t launch(const bf16_t *A, int64_t lda, const bf16_t *W, int64_t ldw, 
     }
     const int tiles_m = (M + BM - 1) / BM;
     const int total = tiles_m * tiles_n;
+#ifdef LVX_GEMM_NPART
+    const int per_xcd = tiles_m * ((tiles_n + 7) / 8);
+#else
     const int per_xcd = (total + 7) / 8;
+#endif
     const dim3 grid(per_xcd * 8), block(64 * WAVES_M * WAVES_N);
 #define LVX_GEMM_LAUNCH(EPI_)                                                                                                      \
     hipLaunchKernelGGL((lvx_gemm_dma_kernel<BM, BN, WAVES_M, WAVES_N, EPI_, CONV>), grid, block, 0, stream, A, lda, W, ldw, C, ldc, M, N, K, \

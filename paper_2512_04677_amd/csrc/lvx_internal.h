@@ -108,6 +108,10 @@ lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
+// RMSNorm + RoPE with q rows in bf16 and k rows in fp32 (outputs bf16).
+lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
+                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
+                                     hipStream_t stream);
 // RMSNorm (no rotation) of n_batch sets of token-major rows (bf16, or fp32 with strides in fp32 elements), written straight into n_batch packed K arrays [H][cap][D]
 // from key 0 on; gains[b] is batch b's gain vector (NULL: that batch is copied un-normalised).  n_batch <= LVX_GEMM_MAX_SEGS.
 lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,

@@ -30,11 +30,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 constexpr int ROWS_PER_WG = 4;
 
-// CPL = 8-element chunks per lane (row length <= 64*8*CPL); F32IN: the input rows are fp32 (ld_in, batch_stride_in in fp32
-// elements), else bf16; F32OUT (norm-only form, needs F32IN): the result is stored in fp32, token-major, un-rounded
-template <int CPL, bool F32IN, bool F32OUT = false>
+// CPL = 8-element chunks per lane (row length <= 64*8*CPL).  IN_MODE: 0 = q and k rows are bf16, 1 = both fp32, 2 = q bf16 and
+// k fp32 (row strides and batch strides of an fp32 input count fp32 elements; ld_in is q's row stride, ld_in_k is k's).
+// F32OUT (norm-only form, needs fp32 input): the result is stored in fp32, token-major, un-rounded
+template <int CPL, int IN_MODE, bool F32OUT = false>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
-    lvx_rope_norm_kernel(const void *q_in, const void *k_in, int64_t ld_in,
+    lvx_rope_norm_kernel(const void *q_in, const void *k_in, int64_t ld_in, int64_t ld_in_k,
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
                          bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
                          float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out,
@@ -68,11 +69,13 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
 
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
+        if (gridDim.y == 2 && which != (int)blockIdx.y) continue;  // q and k rows of a token go to different waves
         const void *in = which == 0 ? q_in : k_in;
         bf16_t *outp = which == 0 ? q_out : k_out;
         const float *g = which == 0 ? g_q : (gtab.n > 0 ? gtab.g[batch] : g_k);
         if (in == nullptr) continue;
-        const size_t row_off = (size_t)batch * batch_stride_in + (size_t)token * ld_in;
+        const bool F32IN = IN_MODE == 1 || (IN_MODE == 2 && which == 1);
+        const size_t row_off = (size_t)batch * batch_stride_in + (size_t)token * (which == 0 ? ld_in : ld_in_k);
         float x[CPL][8];
         float ss = 0.f;
 #pragma unroll
@@ -225,7 +228,8 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
 static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, const void *k_in, int64_t ld_in, const float *g_q,
                                 const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
                                 hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0,
-                                bool f32_in = false, const gain_table_t *gains = nullptr) {
+                                int in_mode = 0, const gain_table_t *gains = nullptr, int64_t ld_in_k = -1) {
+    if (ld_in_k < 0) ld_in_k = ld_in;
     gain_table_t gtab = {};
     if (gains != nullptr) gtab = *gains;
     const int d = desc->n_heads * desc->head_dim;
@@ -242,27 +246,30 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, c
                 tab.axis[p] = ax;
             }
     }
-    const dim3 grid((unsigned)(((int64_t)n_tokens * n_batch + ROWS_PER_WG - 1) / ROWS_PER_WG)), block(64 * ROWS_PER_WG);
+    // with both inputs present the q rows and the k rows are handled by different workgroups (twice the waves in flight,
+    // half the dependent load -> reduce -> store chain per wave)
+    const dim3 grid((unsigned)(((int64_t)n_tokens * n_batch + ROWS_PER_WG - 1) / ROWS_PER_WG), (q_in != nullptr && k_in != nullptr) ? 2 : 1),
+        block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
-#define LVX_ROPE_LAUNCH(CPL, F32)                                                                                                \
-    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, F32>), grid, block, 0, stream, q_in, k_in, ld_in, g_q, g_k, n_tokens, t0, q_out, k_out, \
-                       ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab, n_batch,  \
-                       batch_stride_in, batch_stride_out, gtab)
-    if (f32_in) {
-        if (cpl <= 2)
-            LVX_ROPE_LAUNCH(2, true);
-        else if (cpl <= 10)
-            LVX_ROPE_LAUNCH(10, true);
-        else
-            LVX_ROPE_LAUNCH(16, true);
+#define LVX_ROPE_LAUNCH(CPL, MODE)                                                                                               \
+    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, MODE>), grid, block, 0, stream, q_in, k_in, ld_in, ld_in_k, g_q, g_k, n_tokens, t0, q_out, \
+                       k_out, ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab,    \
+                       n_batch, batch_stride_in, batch_stride_out, gtab)
+#define LVX_ROPE_LAUNCH_MODE(MODE)          \
+    if (cpl <= 2)                           \
+        LVX_ROPE_LAUNCH(2, MODE);           \
+    else if (cpl <= 10)                     \
+        LVX_ROPE_LAUNCH(10, MODE);          \
+    else                                    \
+        LVX_ROPE_LAUNCH(16, MODE)
+    if (in_mode == 1) {
+        LVX_ROPE_LAUNCH_MODE(1);
+    } else if (in_mode == 2) {
+        LVX_ROPE_LAUNCH_MODE(2);
     } else {
-        if (cpl <= 2)
-            LVX_ROPE_LAUNCH(2, false);
-        else if (cpl <= 10)
-            LVX_ROPE_LAUNCH(10, false);
-        else
-            LVX_ROPE_LAUNCH(16, false);
+        LVX_ROPE_LAUNCH_MODE(0);
     }
+#undef LVX_ROPE_LAUNCH_MODE
 #undef LVX_ROPE_LAUNCH
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -286,7 +293,7 @@ static lvx_status_t rope3d_entry(const lvx_rope_desc_t *desc, const void *dev_q_
     if (n_tokens == 0) return LVX_OK;
 
     return launch_rope(desc, dev_q_in, dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out, (bf16_t *)dev_k_out, ld_out,
-                       desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in);
+                       desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in ? 1 : 0);
 }
 
 extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
@@ -301,6 +308,17 @@ extern "C" lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc, const floa
     return rope3d_entry(desc, dev_q_in, dev_k_in, ld_in, true, dev_g_q, dev_g_k, n_tokens, t0, dev_q_out, dev_k_out, ld_out, stream);
 }
 
+// q rows bf16 (ld_q elements), k rows fp32 (ld_k fp32 elements): the block's QKV projection keeps only its k columns un-rounded
+// (they become the cached keys); outputs bf16 with row stride ld_out.
+lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
+                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
+                                     hipStream_t stream) {
+    lvx_status_t st = check_rope_desc(desc);
+    if (st != LVX_OK) return st;
+    if (n_tokens == 0) return LVX_OK;
+    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k);
+}
+
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream) {
@@ -308,7 +326,7 @@ lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const floa
     if (st != LVX_OK) return st;
     if (n_tokens == 0 || n_layers == 0) return LVX_OK;
     return launch_rope(desc, nullptr, src, ld_src, nullptr, nullptr, n_tokens, t0, nullptr, k_packed, desc->head_dim,
-                       (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst, true);
+                       (int64_t)cap * desc->head_dim, stream, n_layers, layer_stride_src, layer_stride_dst, 1);
 }
 
 lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,
@@ -324,7 +342,7 @@ lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void
     gt.n = n_batch;
     for (int b = 0; b < n_batch; ++b) gt.g[b] = gains[b];
     return launch_rope(&norm_only, nullptr, src, ld_src, nullptr, nullptr, n_tokens, 0, nullptr, k_packed, desc->head_dim,
-                       (int64_t)cap * desc->head_dim, stream, n_batch, batch_stride_src, batch_stride_dst, src_is_f32 != 0, &gt);
+                       (int64_t)cap * desc->head_dim, stream, n_batch, batch_stride_src, batch_stride_dst, src_is_f32 ? 1 : 0, &gt);
 }
 
 lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x, int64_t ld_in, const float *g, int n_tokens, float *y,
@@ -337,7 +355,7 @@ lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x,
     const dim3 grid((unsigned)((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG)), block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
 #define LVX_NORM32_LAUNCH(CPL)                                                                                                     \
-    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, true, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, \
+    hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, 1, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, ld_in, \
                        (const float *)nullptr, g, n_tokens, 0, (bf16_t *)nullptr, (bf16_t *)y, ld_out, (int64_t)desc->head_dim, d,    \
                        desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{})
     if (cpl <= 2)
