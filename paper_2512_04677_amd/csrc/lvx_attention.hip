@@ -28,8 +28,11 @@
 namespace {
 
 constexpr int KT = LVX_KEY_TILE;
+// from this many visible keys on, a phase of the pipeline covers two 64-key tiles instead of one (measured: 3 % slower at 544
+// keys, equal at 1560, 3 to 4 % faster from 6240 keys on)
+constexpr int TP2_MIN_KEYS = 16 * KT;
 
-template <int D, int NWAVES, int QB = 2>
+template <int D, int NWAVES, int QB = 2, int TP = 1>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
@@ -46,6 +49,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // swz(r) = r & 15 for 256-byte rows and (r >> 1) & 7 for 128-byte rows: 16 consecutive rows then hit 16 distinct
     // 16-byte units of a 256-byte bank row.
     constexpr int NS = 4;
+    static_assert(NS == 4 && (TP == 1 || TP == 2), "two stages of TP tiles must fit the ring");
     constexpr int TILE_B = KT * D * 2;        // bytes per K tile = per V^T tile
     constexpr int K_ROW_B = D * 2;
     constexpr int K_RPI = 1024 / K_ROW_B;     // K rows per DMA instruction (4 or 8)
@@ -82,6 +86,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 
     const int n_tiles = (n_keys + KT - 1) / KT;
+    const int n_ph = (n_tiles + TP - 1) / TP;  // phases: TP consecutive tiles each
     const char *k_src = reinterpret_cast<const char *>(kp + (size_t)head * cap * D);   // K tile t at k_src + t * TILE_B
     const char *v_src = reinterpret_cast<const char *>(vtp + (size_t)head * cap * D);  // V^T tile t at v_src + t * TILE_B
 
@@ -124,11 +129,13 @@ __global__ void __launch_bounds__(64 * NWAVES)
         _Pragma("unroll") for (int e = 0; e < DPW; ++e)                                                                     \
             lvx_dma16(v_src + (size_t)tt_ * TILE_B, vdoff[e], vs_wave + (uint32_t)(((t_) & (NS - 1)) * TILE_B + e * NWAVES * 1024)); \
     }
-    // stage u = { V^T(u), K(u+1) }: what the matrix phase X(u) reads
-#define LVX_ATTN_STAGE_DMA(u_) \
-    {                          \
-        LVX_ATTN_DMA_V(u_);    \
-        LVX_ATTN_DMA_K((u_) + 1); \
+    // stage u = { V^T(TP u + i), K(TP (u+1) + i), i < TP }: what the matrix phase X(u) reads
+#define LVX_ATTN_STAGE_DMA(u_)                                   \
+    {                                                            \
+        _Pragma("unroll") for (int i_ = 0; i_ < TP; ++i_) {      \
+            LVX_ATTN_DMA_V(TP * (u_) + i_);                      \
+            LVX_ATTN_DMA_K(TP * ((u_) + 1) + i_);                \
+        }                                                        \
     }
 #define LVX_ATTN_WAIT_DMA(n_) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n_) : "memory")
 
@@ -149,10 +156,12 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // other is in Y, so the matrix core and the vector ALU of each SIMD are busy at the same time.
     //   iteration i, first half :  group 0: X(i-1) (S(0) only before the loop)  group 1: Y(i-1)
     //   iteration i, second half:  group 0: Y(i)                                group 1: X(i-1)
-    // Staging: every wave issues the DMA of stage i+2 at the end of the first half of iteration i and, before the second
-    // half's barrier, waits until its own DMA of stage i has landed (two younger stages may still be in flight); stage i
-    // is first read by group 0 in X(i), right after that barrier.  Stage i-2, whose ring slots stage i+2 overwrites, was
-    // last read in the second half of iteration i-1 (group 1's X(i-2)), which ended at a barrier before the issue.
+    // A phase covers TP consecutive tiles (TP = 2: 128 keys), which halves the barriers, the pipeline fills at a phase's start
+    // and the drains at its end per key.
+    // Staging: tile t lives in ring slot t % 4, so two stages fit.  Every wave issues the DMA of stage i at the start of
+    // iteration i, into the slots of stage i-2, whose last reader (group 1's X(i-2), second half of iteration i-1) ended at
+    // the barrier just passed, and waits for its own part before the barrier that ends iteration i; stage i is first read
+    // by group 0 in X(i), right after that barrier: a whole iteration of both groups' work covers the load.
     const int grp = wave / (NWAVES / 2);
 
     // o[db][qb][e] = O^T[d = 16 db + 4 q4 + e][query 16 qb + l16];  s[kb][qb][e] = score of key row 4 q4 + e of block kb
@@ -168,17 +177,17 @@ __global__ void __launch_bounds__(64 * NWAVES)
     float mc[QB], l_run[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) mc[qb] = l_run[qb] = 0.f;
-    f32x4_t s[4][QB];
-    bf16x8_t pb[QB][2];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
+    f32x4_t s[4 * TP][QB];
+    bf16x8_t pb[QB][2 * TP];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
 
     // S(0) = K(0) Q^T from K slot 0 (prologue of the pipeline; the steady state computes S inside LVX_ATTN_X)
 #define LVX_ATTN_S0()                                                                                          \
     {                                                                                                          \
-        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) {                                                     \
+        _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) {                                                \
             _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = 0.f; \
             bf16x8_t a[MK];                                                                                    \
             _Pragma("unroll") for (int m = 0; m < MK; ++m)                                                     \
-                a[m] = *reinterpret_cast<const bf16x8_t *>(ks + kb * 16 * K_ROW_B + kfo[m]);                   \
+                a[m] = *reinterpret_cast<const bf16x8_t *>(ks + (kb >> 2) * TILE_B + (kb & 3) * 16 * K_ROW_B + kfo[m]); \
             _Pragma("unroll") for (int m = 0; m < MK; ++m) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)   \
                 s[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], qf[qb][m], s[kb][qb], 0, 0, 0);      \
         }                                                                                                      \
@@ -191,29 +200,37 @@ __global__ void __launch_bounds__(64 * NWAVES)
     //   fragment f < NV :  V^T rows 16*(f%DB).., keys 32*(f/DB) ..      -> o[f%DB][qb] += frag * pb[qb][f/DB]
     //   fragment f >= NV:  g = f - NV: K rows 16*(g%4).., dims 32*(g/4) ..  -> s[g%4][qb] += frag * qf[qb][g/4]
 #define LVX_ATTN_FRAG(f_)                                                                                              \
-    ((f_) < NV ? *reinterpret_cast<const bf16x8_t *>(vr + ((f_) % DB) * 16 * V_ROW_B + vfo[((f_) / DB) & 1])            \
-               : *reinterpret_cast<const bf16x8_t *>(kr + (((f_) - NV) & 3) * 16 * K_ROW_B + kfo[(((f_) - NV) >> 2) % MK]))
+    ((f_) < NV * TP ? *reinterpret_cast<const bf16x8_t *>(vr[(f_) / NV] + (((f_) % NV) % DB) * 16 * V_ROW_B + vfo[(((f_) % NV) / DB) & 1]) \
+                    : *reinterpret_cast<const bf16x8_t *>(kr[(((f_) - NV * TP) / NK) % TP] + (((f_) - NV * TP) & 3) * 16 * K_ROW_B + \
+                                                          kfo[((((f_) - NV * TP) % NK) >> 2) % MK]))
 #define LVX_ATTN_X(j_)                                                                                         \
     {                                                                                                          \
         __builtin_amdgcn_s_setprio(2); /* the matrix phase wins instruction arbitration over the other wave's VALU */ \
-        const char *vr = vs + ((j_) & (NS - 1)) * TILE_B;                                                      \
-        const char *kr = ks + (((j_) + 1) & (NS - 1)) * TILE_B;                                                \
+        const char *vr[TP], *kr[TP];                                                                           \
+        _Pragma("unroll") for (int i_ = 0; i_ < TP; ++i_) {                                                    \
+            vr[i_] = vs + ((TP * (j_) + i_) & (NS - 1)) * TILE_B;                                              \
+            kr[i_] = ks + ((TP * ((j_) + 1) + i_) & (NS - 1)) * TILE_B;                                        \
+        }                                                                                                      \
         bf16x8_t fr[PD];                                                                                       \
         _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
-        _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb)     \
+        _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) \
             _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = 0.f;                                  \
-        _Pragma("unroll") for (int f = 0; f < NV + NK; ++f) {                                                  \
+        _Pragma("unroll") for (int f = 0; f < (NV + NK) * TP; ++f) {                                           \
             const bf16x8_t a = fr[f % PD];                                                                     \
-            if (f + PD < NV + NK) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                          \
+            if (f + PD < (NV + NK) * TP) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                   \
             _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                                \
-                if (f < NV)                                                                                    \
-                    o[f % DB][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qb][(f / DB) & 1], o[f % DB][qb], 0, 0, 0); \
-                else                                                                                           \
-                    s[(f - NV) & 3][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qb][((f - NV) >> 2) % MK], s[(f - NV) & 3][qb], 0, 0, 0); \
+                if (f < NV * TP) {                                                                             \
+                    const int u_ = f / NV, ff_ = f % NV;                                                       \
+                    o[ff_ % DB][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pb[qb][2 * u_ + ((ff_ / DB) & 1)], o[ff_ % DB][qb], 0, 0, 0); \
+                } else {                                                                                       \
+                    const int g_ = f - NV * TP, u_ = g_ / NK, gg_ = g_ % NK;                                   \
+                    s[4 * u_ + (gg_ & 3)][qb] =                                                                \
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[qb][(gg_ >> 2) % MK], s[4 * u_ + (gg_ & 3)][qb], 0, 0, 0); \
+                }                                                                                              \
             }                                                                                                  \
         }                                                                                                      \
         __builtin_amdgcn_sched_group_barrier(0x100, PD, 0);                                                    \
-        _Pragma("unroll") for (int f = 0; f < NV + NK - PD; ++f) {                                             \
+        _Pragma("unroll") for (int f = 0; f < (NV + NK) * TP - PD; ++f) {                                      \
             __builtin_amdgcn_sched_group_barrier(0x008, QB, 0);                                                \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                 \
         }                                                                                                      \
@@ -223,10 +240,10 @@ __global__ void __launch_bounds__(64 * NWAVES)
 #define LVX_ATTN_Y(t_)                                                                                         \
     {                                                                                                          \
         __builtin_amdgcn_s_setprio(0); /* the matrix phase's priority is kept through its DMA issue, up to here */ \
-        if ((t_) == n_tiles - 1 && (n_keys % KT) != 0) {                                                       \
-            int lim_ = n_keys - (t_) * KT - 8 * q4; /* valid keys, counted from this lane group's first key */ \
+        if ((t_) == n_ph - 1 && (n_keys % (TP * KT)) != 0) {                                                   \
+            int lim_ = n_keys - (t_) * (TP * KT) - 8 * q4; /* valid keys, counted from this lane group's first key */ \
             asm volatile("" : "+v"(lim_));          /* keep the compares out of the loop preheader */          \
-            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)     \
+            _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
                 if (32 * (kb >> 1) + 4 * (kb & 1) + e >= lim_) {                                               \
                     _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) s[kb][qb][e] = -INFINITY;                \
                 }                                                                                              \
@@ -241,7 +258,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
             if (rebase_) {                                                                                     \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                            \
                     float tmax = s[0][qb][0];                                                                  \
-                    _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
+                    _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
                         tmax = fmaxf(tmax, s[kb][qb][e]);                                                      \
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));                                                  \
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));                                                  \
@@ -257,7 +274,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
             }                                                                                                  \
             bool fits_ = true;                                                                                 \
             _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;                                  \
-            _Pragma("unroll") for (int kb = 0; kb < 4; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e)     \
+            _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                            \
                     const float p_ = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][qb][e], c_exp2, -mc[qb]));    \
                     lsum[qb] += p_;                                                                            \
@@ -270,27 +287,25 @@ __global__ void __launch_bounds__(64 * NWAVES)
         _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) l_run[qb] += lsum[qb];                               \
     }
 
-    LVX_ATTN_DMA_K(0);
+#pragma unroll
+    for (int i = 0; i < TP; ++i) LVX_ATTN_DMA_K(i);
     LVX_ATTN_STAGE_DMA(0);
-    LVX_ATTN_STAGE_DMA(1);
-    LVX_ATTN_WAIT_DMA(4 * DPW);  // K(0) landed; stages 0 and 1 may be in flight
+    LVX_ATTN_WAIT_DMA(0);
     __syncthreads();
 
     // Each group runs its own straight-line loop; both execute the same number of barriers (2 per iteration) and the same
-    // DMA issue / wait sequence (issue in the first half, wait in the second half of every iteration).
+    // DMA issue / wait sequence (issue at the start, wait at the end of every iteration).
     // A wave whose 32 queries all lie past n_q (ragged last query tile: 4680 = 18 x 256 + 72) only keeps up the DMA and
     // barrier protocol: no LDS reads, no MFMAs, no softmax.  Its SIMD partner then has the matrix core to itself, so such a
     // workgroup finishes early and frees its CU, and the padding costs no energy on a chip that is power-limited.
     const bool active = __builtin_amdgcn_readfirstlane(qtile * QT + wave * (16 * QB)) < n_q;
     if (!active) {
         __syncthreads();
-        LVX_ATTN_STAGE_DMA(2);
-        LVX_ATTN_WAIT_DMA(4 * DPW);
         __syncthreads();
-        for (int i = 1; i < n_tiles; ++i) {
-            LVX_ATTN_STAGE_DMA(i + 2);
+        for (int i = 1; i < n_ph; ++i) {
+            LVX_ATTN_STAGE_DMA(i);
             __syncthreads();
-            LVX_ATTN_WAIT_DMA(4 * DPW);
+            LVX_ATTN_WAIT_DMA(0);
             __syncthreads();
         }
         __syncthreads();
@@ -299,32 +314,28 @@ __global__ void __launch_bounds__(64 * NWAVES)
         LVX_ATTN_S0();
         __syncthreads();
         LVX_ATTN_Y(0);
-        LVX_ATTN_STAGE_DMA(2);
-        LVX_ATTN_WAIT_DMA(4 * DPW);  // stage 0 landed
         __syncthreads();
-        for (int i = 1; i < n_tiles; ++i) {
+        for (int i = 1; i < n_ph; ++i) {
+            LVX_ATTN_STAGE_DMA(i);
             LVX_ATTN_X(i - 1);
-            LVX_ATTN_STAGE_DMA(i + 2);
             __syncthreads();
             LVX_ATTN_Y(i);
-            LVX_ATTN_WAIT_DMA(4 * DPW);  // stage i landed
+            LVX_ATTN_WAIT_DMA(0);  // stage i landed
             __syncthreads();
         }
-        LVX_ATTN_X(n_tiles - 1);
+        LVX_ATTN_X(n_ph - 1);
         __syncthreads();
         __syncthreads();
     } else {
         __syncthreads();
         LVX_ATTN_S0();
-        LVX_ATTN_STAGE_DMA(2);
-        LVX_ATTN_WAIT_DMA(4 * DPW);
         __syncthreads();
-        for (int i = 1; i <= n_tiles; ++i) {
+        for (int i = 1; i <= n_ph; ++i) {
+            if (i < n_ph) LVX_ATTN_STAGE_DMA(i);
             LVX_ATTN_Y(i - 1);
-            if (i < n_tiles) LVX_ATTN_STAGE_DMA(i + 2);
             __syncthreads();
             LVX_ATTN_X(i - 1);
-            if (i < n_tiles) LVX_ATTN_WAIT_DMA(4 * DPW);
+            if (i < n_ph) LVX_ATTN_WAIT_DMA(0);
             __syncthreads();
         }
     }
@@ -367,7 +378,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 }
 
-template <int D, int NWAVES, int QB = 2>
+template <int D, int NWAVES, int QB = 2, int TP = 1>
 lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
                     float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots) {
     constexpr int QT = 16 * QB * NWAVES;
@@ -375,7 +386,7 @@ lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t 
     const int total = n_qtiles * H;
     const int per_xcd = (total + 7) / 8;
     const float c = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
+    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB, TP>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
                        n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -392,6 +403,8 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
 #ifdef LVX_ATTN_16W
     if (D == 128) return launch<128, 16, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
 #endif
+    if (D == 128 && n_keys >= TP2_MIN_KEYS)
+        return launch<128, 8, 2, 2>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     if (D == 64) return launch<64, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);

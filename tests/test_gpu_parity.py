@@ -207,12 +207,18 @@ def test_attention_random_shapes(lvx, seed):
     cache.close()
 
 
-def test_attention_growing_logits_rebase(lvx):
+LONG_SINK = dict(n_heads=2, head_dim=128, frame_h=5, frame_w=7, chunk_frames=3, window=2, sink_frames=32)
+
+
+@pytest.mark.parametrize("geometry", ["small", "long_sink"])
+def test_attention_growing_logits_rebase(lvx, geometry):
     """Scores that outgrow the first key tile's maximum by 2^49, 2^98 and 2^196 (and drop below it by as much): the kernel keeps
     the first tile's row maximum as its softmax reference and only re-bases when a tile's sum of exponentials passes 2^64 or
     overflows; both the finite and the overflowing re-base, in a middle tile and in the ragged last tile, must still give the
-    plain softmax the oracle computes in fp64.  Second step: the large keys come first, the rest falls far below."""
-    p = S.PRESETS["small"]
+    plain softmax the oracle computes in fp64.  Second step: the large keys come first, the rest falls far below.
+    `long_sink` puts 1120 sink keys in front (1225 and 1330 visible keys): from 1024 keys on the kernel's pipeline phases
+    cover two key tiles each, and the re-base then happens in the second tile of a phase, in a full phase and in a ragged one."""
+    p = S.PRESETS["small"] if geometry == "small" else LONG_SINK
     d, sink_n, chunk_n = dims(p)
     H, D, W = p["n_heads"], p["head_dim"], p["window"]
     assert D == 128
@@ -246,6 +252,47 @@ def test_attention_growing_logits_rebase(lvx):
         ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
                                      S.to_f64(v).reshape(chunk_n, H, D), scale, i)
         assert_close(out, ref.reshape(chunk_n, d), "growing logits, %s" % order)
+    cache.close()
+
+
+@pytest.mark.parametrize("geometry", [
+    dict(n_heads=2, head_dim=128, frame_h=5, frame_w=13, chunk_frames=3, window=5, sink_frames=1),   # 260 ... 1040, 1235 keys
+    dict(n_heads=1, head_dim=128, frame_h=8, frame_w=8, chunk_frames=2, window=7, sink_frames=0),    # 128 ... 1024 keys
+    dict(n_heads=1, head_dim=128, frame_h=8, frame_w=8, chunk_frames=2, window=8, sink_frames=1),    # ... 1088, 1216 keys
+    dict(n_heads=1, head_dim=128, frame_h=1, frame_w=1, chunk_frames=1, window=1, sink_frames=1279),  # 1280, 1281 keys, 1 query
+])
+def test_attention_two_tile_phases(lvx, geometry):
+    """From 1024 visible keys on (head_dim 128) a phase of the attention kernel's pipeline covers two 64-key tiles.  Key counts
+    on both sides of that switch: an even number of full tiles (1024), an odd number (1088 = 17, 1216 = 19: the second tile
+    of the last phase is entirely invalid), a ragged tile in the first half of the last phase (1040 = 16 tiles + 16 keys) and
+    in its second half (1235 = 19 tiles + 19 keys, 1281 = 20 tiles + 1 key), with the ring wrapping and evicting."""
+    p = geometry
+    d, sink_n, chunk_n = dims(p)
+    H, D, W = p["n_heads"], p["head_dim"], p["window"]
+    scale = 1.0 / math.sqrt(D)
+    cache = make_cache(lvx, p)
+    model = O.RollingKVCache(W)
+    if sink_n:
+        sink_k = S.randn_bf16((sink_n, d), S.seed_of("tp", sink_n, "sk"), device=DEV)
+        sink_v = S.randn_bf16((sink_n, d), S.seed_of("tp", sink_n, "sv"), device=DEV)
+        lvx.lvx_kvcache_set_sink(cache, 0, sink_k, sink_v)
+        model.set_sink(S.to_f64(sink_k).reshape(sink_n, H, D), S.to_f64(sink_v).reshape(sink_n, H, D))
+    else:
+        model.set_sink(np.zeros((0, H, D)), np.zeros((0, H, D)))
+    seen = set()
+    for i in range(W + 3):
+        q = S.randn_bf16((chunk_n, d), S.seed_of("tp", chunk_n, "q", i), device=DEV)
+        k = S.randn_bf16((chunk_n, d), S.seed_of("tp", chunk_n, "k", i), device=DEV)
+        v = S.randn_bf16((chunk_n, d), S.seed_of("tp", chunk_n, "v", i), device=DEV)
+        out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
+        info = lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
+        seen.add(info.key_count)
+        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        torch.cuda.synchronize()
+        ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
+                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "two-tile phases %s step %d (%d keys)" % (p, i, info.key_count))
+    assert max(seen) >= 1024
     cache.close()
 
 
