@@ -32,7 +32,7 @@ constexpr int KT = LVX_KEY_TILE;
 // keys, equal at 1560, 3 to 4 % faster from 6240 keys on)
 constexpr int TP2_MIN_KEYS = 16 * KT;
 
-template <int D, int NWAVES, int QB = 2, int TP = 1>
+template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false>
 __global__ void __launch_bounds__(64 * NWAVES)
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
@@ -175,8 +175,13 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // per query block: the reference the softmax subtracts (a row maximum, already multiplied by c_exp2; set by the first
     // tile) and this lane's share of the row sum
     float mc[QB], l_run[QB];
+    // PRE: the queries arrive multiplied by scale * log2(e) (before their rounding to bf16), and the score MFMAs start their
+    // accumulators at -mc, so a score leaves the matrix phase as the exponent itself and the vector phase saves one FMA per
+    // score.  sub = what the accumulators of the scores at hand were started at; it differs from mc only in the first phase and
+    // after a re-base, where the difference is added explicitly.
+    float sub[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) mc[qb] = l_run[qb] = 0.f;
+    for (int qb = 0; qb < QB; ++qb) mc[qb] = l_run[qb] = sub[qb] = 0.f;
     f32x4_t s[4 * TP][QB];
     bf16x8_t pb[QB][2 * TP];  // [qb][ks]: P^T for keys 32 ks + 8 q4 .. + 7, query 16 qb + l16
 
@@ -214,7 +219,8 @@ __global__ void __launch_bounds__(64 * NWAVES)
         bf16x8_t fr[PD];                                                                                       \
         _Pragma("unroll") for (int f = 0; f < PD; ++f) fr[f] = LVX_ATTN_FRAG(f);                               \
         _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) \
-            _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = 0.f;                                  \
+            _Pragma("unroll") for (int e = 0; e < 4; ++e) s[kb][qb][e] = PRE ? -mc[qb] : 0.f;                  \
+        if (PRE) { _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) sub[qb] = mc[qb]; }                       \
         _Pragma("unroll") for (int f = 0; f < (NV + NK) * TP; ++f) {                                           \
             const bf16x8_t a = fr[f % PD];                                                                     \
             if (f + PD < (NV + NK) * TP) fr[f % PD] = LVX_ATTN_FRAG(f + PD);                                   \
@@ -263,7 +269,7 @@ __global__ void __launch_bounds__(64 * NWAVES)
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 16));                                                  \
                     tmax = fmaxf(tmax, __shfl_xor(tmax, 32));                                                  \
                     const bool first_ = (t_) == 0;                                                             \
-                    const float tmc = tmax * c_exp2;                                                           \
+                    const float tmc = PRE ? tmax + sub[qb] : tmax * c_exp2;                                    \
                     const bool need = first_ || tmc > mc[qb] + 6.0f;                                           \
                     const float alpha = (need && !first_) ? __builtin_amdgcn_exp2f(mc[qb] - tmc) : 1.0f;       \
                     if (need) mc[qb] = tmc;                                                                    \
@@ -272,11 +278,23 @@ __global__ void __launch_bounds__(64 * NWAVES)
                         o[i][qb][e] *= alpha;                                                                  \
                 }                                                                                              \
             }                                                                                                  \
+            if (PRE) {                                                                                         \
+                bool adj_ = false;                                                                             \
+                _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) adj_ = adj_ || (sub[qb] != mc[qb]);          \
+                if (__any(adj_)) {                                                                             \
+                    _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                        \
+                        const float d_ = sub[qb] - mc[qb];                                                     \
+                        _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
+                            s[kb][qb][e] += d_;                                                                \
+                        sub[qb] = mc[qb];                                                                      \
+                    }                                                                                          \
+                }                                                                                              \
+            }                                                                                                  \
             bool fits_ = true;                                                                                 \
             _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) lsum[qb] = 0.f;                                  \
             _Pragma("unroll") for (int kb = 0; kb < 4 * TP; ++kb) _Pragma("unroll") for (int e = 0; e < 4; ++e) \
                 _Pragma("unroll") for (int qb = 0; qb < QB; ++qb) {                                            \
-                    const float p_ = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][qb][e], c_exp2, -mc[qb]));    \
+                    const float p_ = __builtin_amdgcn_exp2f(PRE ? s[kb][qb][e] : __builtin_fmaf(s[kb][qb][e], c_exp2, -mc[qb])); \
                     lsum[qb] += p_;                                                                            \
                     pb[qb][kb >> 1][4 * (kb & 1) + e] = (__bf16)p_;                                            \
                 }                                                                                              \
@@ -378,15 +396,15 @@ __global__ void __launch_bounds__(64 * NWAVES)
     }
 }
 
-template <int D, int NWAVES, int QB = 2, int TP = 1>
+template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false>
 lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
                     float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots) {
     constexpr int QT = 16 * QB * NWAVES;
     const int n_qtiles = (n_q + QT - 1) / QT;
     const int total = n_qtiles * H;
     const int per_xcd = (total + 7) / 8;
-    const float c = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB, TP>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
+    const float c = scale * LVX_LOG2E;
+    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB, TP, PRE>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
                        n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
@@ -396,13 +414,20 @@ lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t 
 
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream, uint32_t *amax_slots) {
+                                  hipStream_t stream, uint32_t *amax_slots, bool q_prescaled) {
     LVX_REQUIRE(n_q > 0 && n_keys > 0 && n_keys <= cap && cap % KT == 0, LVX_ERR_SHAPE, "attention: n_q %d, n_keys %d, cap %d", n_q,
                 n_keys, cap);
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
 #ifdef LVX_ATTN_16W
     if (D == 128) return launch<128, 16, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
 #endif
+    if (q_prescaled) {  // q already carries scale * log2(e): see PRE in the kernel
+        if (D == 128 && n_keys >= TP2_MIN_KEYS)
+            return launch<128, 8, 2, 2, true>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+        if (D == 128) return launch<128, 8, 2, 1, true>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+        if (D == 64) return launch<64, 8, 2, 1, true>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+        return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
+    }
     if (D == 128 && n_keys >= TP2_MIN_KEYS)
         return launch<128, 8, 2, 2>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
     if (D == 128) return launch<128, 8>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);

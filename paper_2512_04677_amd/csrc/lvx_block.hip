@@ -232,15 +232,16 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         {
             prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
             if (w8 == nullptr)
-                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
+                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, scale * LVX_LOG2E, st));
             else
                 LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
         }
         { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
         {
             prof_scope_t ps(LVX_PROF_ATTN_SELF, st);
+            // bf16 stage: the queries were written pre-scaled by the RoPE kernel above
             LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->state[layer].key_count,
-                                         scale, u, ldu, st, amax_out()));
+                                         scale, u, ldu, st, amax_out(), w8 == nullptr));
         }
     } else {
         // the sink's un-rotated keys go into the cache's fp32 source storage: un-rounded from the projection in a bf16 stage,

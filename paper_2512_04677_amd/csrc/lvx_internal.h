@@ -67,6 +67,8 @@ __device__ __forceinline__ void lvx_dma16(const void *gbase, uint32_t voff, uint
 }
 #pragma clang diagnostic pop
 
+#define LVX_LOG2E 1.4426950408889634f
+
 // ---- cache handle (host) ----------------------------------------------------------------------
 struct lvx_kvcache {
     lvx_cache_desc_t desc;
@@ -93,7 +95,7 @@ lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, in
 // Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream, uint32_t *amax_slots = nullptr);
+                                  hipStream_t stream, uint32_t *amax_slots = nullptr, bool q_prescaled = false);
 // out = bf16((x ? x : 0) + dt * h) with h in fp32: the Euler step of the stage (x given) or the narrowing of a block's
 // fp32 residual stream (x NULL, dt 1).
 lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
@@ -111,7 +113,7 @@ lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const floa
 // RMSNorm + RoPE with q rows in bf16 and k rows in fp32 (outputs bf16).
 lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
                                      const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
-                                     hipStream_t stream);
+                                     float q_scale, hipStream_t stream);
 // RMSNorm (no rotation) of n_batch sets of token-major rows (bf16, or fp32 with strides in fp32 elements), written straight into n_batch packed K arrays [H][cap][D]
 // from key 0 on; gains[b] is batch b's gain vector (NULL: that batch is copied un-normalised).  n_batch <= LVX_GEMM_MAX_SEGS.
 lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,

@@ -39,7 +39,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
                          bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
                          float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out,
-                         gain_table_t gtab) {
+                         gain_table_t gtab, float q_scale) {
     // n_batch independent row sets of n_tokens rows each (the sink keys of several layers in one launch); positions and t0
     // are those of the row inside its set
     const int lane = threadIdx.x & 63;
@@ -103,6 +103,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
             ss = wave_sum(ss);
             rinv = 1.0f / sqrtf(ss / (float)d_model + eps);
         }
+        if (which == 0) rinv *= q_scale;  // 1, or the attention's logit scale folded into the queries before their rounding
         // element (token, head, e) of the output lives at token*ld_out + head*ld_out_head + e: token-major rows have
         // ld_out_head = head_dim, packed cache K rows [head][key][head_dim] have ld_out = head_dim, ld_out_head = cap*head_dim
         bf16_t *dst = outp + (size_t)batch * batch_stride_out + (size_t)token * ld_out;
@@ -228,7 +229,7 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
 static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, const void *k_in, int64_t ld_in, const float *g_q,
                                 const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
                                 hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0,
-                                int in_mode = 0, const gain_table_t *gains = nullptr, int64_t ld_in_k = -1) {
+                                int in_mode = 0, const gain_table_t *gains = nullptr, int64_t ld_in_k = -1, float q_scale = 1.0f) {
     if (ld_in_k < 0) ld_in_k = ld_in;
     gain_table_t gtab = {};
     if (gains != nullptr) gtab = *gains;
@@ -254,7 +255,7 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, c
 #define LVX_ROPE_LAUNCH(CPL, MODE)                                                                                               \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, MODE>), grid, block, 0, stream, q_in, k_in, ld_in, ld_in_k, g_q, g_k, n_tokens, t0, q_out, \
                        k_out, ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab,    \
-                       n_batch, batch_stride_in, batch_stride_out, gtab)
+                       n_batch, batch_stride_in, batch_stride_out, gtab, q_scale)
 #define LVX_ROPE_LAUNCH_MODE(MODE)          \
     if (cpl <= 2)                           \
         LVX_ROPE_LAUNCH(2, MODE);           \
@@ -309,14 +310,15 @@ extern "C" lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc, const floa
 }
 
 // q rows bf16 (ld_q elements), k rows fp32 (ld_k fp32 elements): the block's QKV projection keeps only its k columns un-rounded
-// (they become the cached keys); outputs bf16 with row stride ld_out.
+// (they become the cached keys); outputs bf16 with row stride ld_out.  The q rows are multiplied by q_scale before they are
+// rounded (the attention kernel's pre-scaled mode).
 lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
                                      const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
-                                     hipStream_t stream) {
+                                     float q_scale, hipStream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     if (n_tokens == 0) return LVX_OK;
-    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k);
+    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k, q_scale);
 }
 
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
@@ -357,7 +359,7 @@ lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x,
 #define LVX_NORM32_LAUNCH(CPL)                                                                                                     \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, 1, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, ld_in, \
                        (const float *)nullptr, g, n_tokens, 0, (bf16_t *)nullptr, (bf16_t *)y, ld_out, (int64_t)desc->head_dim, d,    \
-                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{})
+                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{}, 1.0f)
     if (cpl <= 2)
         LVX_NORM32_LAUNCH(2);
     else if (cpl <= 10)
