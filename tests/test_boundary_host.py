@@ -186,7 +186,8 @@ def test_fp8_entry_points_host_checks():
     plain = lvx.Stage(1, 13824, 0, 0, r, castb)
     # an FP8 stage holds, beside the bf16 activations and the fp32 stream, the quantised input of its widest linear
     assert lib.lvx_workspace_bytes(C.byref(ok), 4680, 544) >= 4680 * (5120 * 2 + 15360 * 2 + 5120 * 4 + 13824)
-    assert lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) >= 4680 * (5120 * 2 + 15360 * 2 + 5120 * 4 + 2 * 5120 * 4)
+    # a bf16 stage: the fp32 copy of the projection's k columns instead
+    assert lib.lvx_workspace_bytes(C.byref(plain), 4680, 544) >= 4680 * (5120 * 2 + 15360 * 2 + 5120 * 4 + 5120 * 4)
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824 + 64, 0, 0, r, castb, cast8, 0, 0)), 4680, 544) == 0
     assert lib.lvx_workspace_bytes(C.byref(lvx.Stage(1, 13824, 0, 0, r, castb, cast8, 5120 + 8, 0)), 4680, 544) == 0
 
