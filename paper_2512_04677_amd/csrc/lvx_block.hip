@@ -229,19 +229,35 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
             LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
     }
     if (!sink_prefill) {
-        {
-            prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
-            if (w8 == nullptr)
-                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, big + d, ldq, scale * LVX_LOG2E, st));
-            else
-                LVX_TRY(lvx_rope3d(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, st));
+        if (w8 == nullptr) {
+            // the RoPE kernel writes the chunk's keys straight into their ring slot of the cache (one write instead of a write, a
+            // read and a write); the append then only has the values left to transpose
+            lvx_slot_info_t slot;
+            LVX_TRY(lvx_cache_append_begin(c, layer, chunk_index, &slot));
+            bf16_t *k_slot = const_cast<bf16_t *>(lvx_cache_k(c, layer)) + (size_t)slot.key_offset * D;
+            {
+                prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
+                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, ldq, k_slot, D, (int64_t)c->cap_keys * D,
+                                                scale * LVX_LOG2E, st));
+            }
+            {
+                prof_scope_t ps(LVX_PROF_APPEND, st);
+                LVX_TRY(lvx_launch_pack_kv(nullptr, big + 2 * d, ldq, n, H, D, c->cap_keys, slot.key_offset, const_cast<bf16_t *>(lvx_cache_k(c, layer)),
+                                           const_cast<bf16_t *>(lvx_cache_vt(c, layer)), st));
+            }
+            lvx_cache_append_commit(c, layer, chunk_index, &slot);
+        } else {
+            {
+                prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
+                LVX_TRY(lvx_launch_rope_bf16(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, scale * LVX_LOG2E, st));
+            }
+            { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
         }
-        { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
         {
             prof_scope_t ps(LVX_PROF_ATTN_SELF, st);
-            // bf16 stage: the queries were written pre-scaled by the RoPE kernel above
+            // the queries were written pre-scaled by the RoPE kernel above
             LVX_TRY(lvx_launch_attention(big, ldq, n, H, D, lvx_cache_k(c, layer), lvx_cache_vt(c, layer), c->cap_keys, c->state[layer].key_count,
-                                         scale, u, ldu, st, amax_out(), w8 == nullptr));
+                                         scale, u, ldu, st, amax_out(), true));
         }
     } else {
         // the sink's un-rotated keys go into the cache's fp32 source storage: un-rounded from the projection in a bf16 stage,

@@ -453,25 +453,34 @@ extern "C" lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *c, i
                                 2 * ld, c->sink_keys, 2 * d, (hipStream_t)stream);
 }
 
+lvx_status_t lvx_cache_append_begin(const lvx_kvcache *c, int layer, int64_t chunk_index, lvx_slot_info_t *info) {
+    const lvx_ring_state_t &s = c->state[layer];
+    LVX_REQUIRE(chunk_index == s.last_chunk + 1, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", layer,
+                (long long)(s.last_chunk + 1), (long long)chunk_index);
+    LVX_REQUIRE(c->sink_keys == 0 || s.sink_set, LVX_ERR_STATE, "layer %d: sink not set before the first append", layer);
+    return lvx_ring_slot(&c->desc, chunk_index, info);
+}
+
+void lvx_cache_append_commit(lvx_kvcache *c, int layer, int64_t chunk_index, const lvx_slot_info_t *info) {
+    lvx_ring_state_t &s = c->state[layer];
+    s.last_chunk = chunk_index;
+    s.slot_chunk[info->slot] = chunk_index;
+    s.n_valid_chunks = info->n_valid_chunks;
+    s.key_count = info->key_count;
+}
+
 extern "C" lvx_status_t lvx_chunk_append_evict(lvx_kvcache_t *c, int32_t layer, const void *dev_k, const void *dev_v, int64_t ld,
                                                int64_t chunk_index, lvx_slot_info_t *out, lvx_stream_t stream) {
     lvx_status_t st = check_layer_and_rows(c, layer, dev_k, dev_v, ld);
     if (st != LVX_OK) return st;
-    lvx_ring_state_t &s = c->state[layer];
-    LVX_REQUIRE(chunk_index == s.last_chunk + 1, LVX_ERR_STATE, "layer %d expects chunk %lld, got %lld", layer,
-                (long long)(s.last_chunk + 1), (long long)chunk_index);
-    LVX_REQUIRE(c->sink_keys == 0 || s.sink_set, LVX_ERR_STATE, "layer %d: sink not set before the first append", layer);
     lvx_slot_info_t info;
-    st = lvx_ring_slot(&c->desc, chunk_index, &info);
+    st = lvx_cache_append_begin(c, layer, chunk_index, &info);
     if (st != LVX_OK) return st;
     st = lvx_launch_pack_kv((const bf16_t *)dev_k, (const bf16_t *)dev_v, ld, c->chunk_keys, c->desc.n_heads, c->desc.head_dim,
                             c->cap_keys, info.key_offset, (bf16_t *)lvx_cache_k(c, layer), (bf16_t *)lvx_cache_vt(c, layer),
                             (hipStream_t)stream);
     if (st != LVX_OK) return st;
-    s.last_chunk = chunk_index;
-    s.slot_chunk[info.slot] = chunk_index;
-    s.n_valid_chunks = info.n_valid_chunks;
-    s.key_count = info.key_count;
+    lvx_cache_append_commit(c, layer, chunk_index, &info);
     if (out) *out = info;
     return LVX_OK;
 }

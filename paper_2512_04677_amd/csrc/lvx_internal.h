@@ -111,9 +111,16 @@ lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const floa
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
 // RMSNorm + RoPE with q rows in bf16 and k rows in fp32 (outputs bf16).
+lvx_status_t lvx_launch_rope_bf16(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
+                                  const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, float q_scale,
+                                  hipStream_t stream);
 lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
-                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
-                                     float q_scale, hipStream_t stream);
+                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
+                                     int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream);
+// Append in two steps for a producer that writes the chunk's keys into the cache itself: begin validates and names the slot
+// (nothing changes), commit records the chunk in the layer's ring state.
+lvx_status_t lvx_cache_append_begin(const lvx_kvcache *c, int layer, int64_t chunk_index, lvx_slot_info_t *info);
+void lvx_cache_append_commit(lvx_kvcache *c, int layer, int64_t chunk_index, const lvx_slot_info_t *info);
 // RMSNorm (no rotation) of n_batch sets of token-major rows (bf16, or fp32 with strides in fp32 elements), written straight into n_batch packed K arrays [H][cap][D]
 // from key 0 on; gains[b] is batch b's gain vector (NULL: that batch is copied un-normalised).  n_batch <= LVX_GEMM_MAX_SEGS.
 lvx_status_t lvx_launch_norm_to_packed_k(const lvx_rope_desc_t *desc, const void *src, int src_is_f32, int64_t ld_src, int n_tokens,

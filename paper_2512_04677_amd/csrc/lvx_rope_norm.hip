@@ -39,7 +39,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                          const float *__restrict__ g_q, const float *__restrict__ g_k, int n_tokens, int t0, bf16_t *q_out,
                          bf16_t *k_out, int64_t ld_out, int64_t ld_out_head, int d_model, int head_dim, int frame_h, int frame_w,
                          float eps, int apply_rope, rope_table_t tab, int n_batch, int64_t batch_stride_in, int64_t batch_stride_out,
-                         gain_table_t gtab, float q_scale) {
+                         gain_table_t gtab, float q_scale, int64_t ld_out_k, int64_t ld_out_head_k) {
     // n_batch independent row sets of n_tokens rows each (the sink keys of several layers in one launch); positions and t0
     // are those of the row inside its set
     const int lane = threadIdx.x & 63;
@@ -106,7 +106,9 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
         if (which == 0) rinv *= q_scale;  // 1, or the attention's logit scale folded into the queries before their rounding
         // element (token, head, e) of the output lives at token*ld_out + head*ld_out_head + e: token-major rows have
         // ld_out_head = head_dim, packed cache K rows [head][key][head_dim] have ld_out = head_dim, ld_out_head = cap*head_dim
-        bf16_t *dst = outp + (size_t)batch * batch_stride_out + (size_t)token * ld_out;
+        // (the k rows may have strides of their own: q token-major for the attention, k straight into the cache's packed rows)
+        const int64_t ldo = which == 0 ? ld_out : ld_out_k, ldoh = which == 0 ? ld_out_head : ld_out_head_k;
+        bf16_t *dst = outp + (size_t)batch * batch_stride_out + (size_t)token * ldo;
 #pragma unroll
         for (int j = 0; j < CPL; ++j) {
             const int c = lane + 64 * j;
@@ -130,7 +132,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                     const float b = x[j][2 * e + 1] * rinv * gg[2 * e + 1];
                     y[e] = pack_bf16x2(a * c4[e] - b * s4[e], a * s4[e] + b * c4[e]);
                 }
-                *reinterpret_cast<u32x4_t *>(dst + (size_t)(c / cph) * ld_out_head + (c % cph) * 8) = y;
+                *reinterpret_cast<u32x4_t *>(dst + (size_t)(c / cph) * ldoh + (c % cph) * 8) = y;
             }
         }
     }
@@ -229,8 +231,10 @@ static lvx_status_t check_rope_desc(const lvx_rope_desc_t *r) {
 static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, const void *k_in, int64_t ld_in, const float *g_q,
                                 const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, int64_t ld_out_head,
                                 hipStream_t stream, int n_batch = 1, int64_t batch_stride_in = 0, int64_t batch_stride_out = 0,
-                                int in_mode = 0, const gain_table_t *gains = nullptr, int64_t ld_in_k = -1, float q_scale = 1.0f) {
+                                int in_mode = 0, const gain_table_t *gains = nullptr, int64_t ld_in_k = -1, float q_scale = 1.0f,
+                                int64_t ld_out_k = -1, int64_t ld_out_head_k = -1) {
     if (ld_in_k < 0) ld_in_k = ld_in;
+    if (ld_out_k < 0) ld_out_k = ld_out, ld_out_head_k = ld_out_head;
     gain_table_t gtab = {};
     if (gains != nullptr) gtab = *gains;
     const int d = desc->n_heads * desc->head_dim;
@@ -255,7 +259,7 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, c
 #define LVX_ROPE_LAUNCH(CPL, MODE)                                                                                               \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, MODE>), grid, block, 0, stream, q_in, k_in, ld_in, ld_in_k, g_q, g_k, n_tokens, t0, q_out, \
                        k_out, ld_out, ld_out_head, d, desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, desc->apply_rope, tab,    \
-                       n_batch, batch_stride_in, batch_stride_out, gtab, q_scale)
+                       n_batch, batch_stride_in, batch_stride_out, gtab, q_scale, ld_out_k, ld_out_head_k)
 #define LVX_ROPE_LAUNCH_MODE(MODE)          \
     if (cpl <= 2)                           \
         LVX_ROPE_LAUNCH(2, MODE);           \
@@ -278,7 +282,7 @@ static lvx_status_t launch_rope(const lvx_rope_desc_t *desc, const void *q_in, c
 
 static lvx_status_t rope3d_entry(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in, bool f32_in,
                                  const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
-                                 void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
+                                 void *dev_k_out, int64_t ld_out, lvx_stream_t stream, float q_scale = 1.0f) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     LVX_REQUIRE(dev_q_in != nullptr || dev_k_in != nullptr, LVX_ERR_INVALID_ARG, "both q and k are NULL");
@@ -294,7 +298,14 @@ static lvx_status_t rope3d_entry(const lvx_rope_desc_t *desc, const void *dev_q_
     if (n_tokens == 0) return LVX_OK;
 
     return launch_rope(desc, dev_q_in, dev_k_in, ld_in, dev_g_q, dev_g_k, n_tokens, t0, (bf16_t *)dev_q_out, (bf16_t *)dev_k_out, ld_out,
-                       desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in ? 1 : 0);
+                       desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in ? 1 : 0, nullptr, -1, q_scale);
+}
+
+// lvx_rope3d on bf16 rows with the q rows multiplied by q_scale before their rounding (the attention kernel's pre-scaled mode)
+lvx_status_t lvx_launch_rope_bf16(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
+                                  const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, float q_scale,
+                                  hipStream_t stream) {
+    return rope3d_entry(desc, q_in, k_in, ld_in, false, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, (lvx_stream_t)stream, q_scale);
 }
 
 extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
@@ -310,15 +321,17 @@ extern "C" lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc, const floa
 }
 
 // q rows bf16 (ld_q elements), k rows fp32 (ld_k fp32 elements): the block's QKV projection keeps only its k columns un-rounded
-// (they become the cached keys); outputs bf16 with row stride ld_out.  The q rows are multiplied by q_scale before they are
-// rounded (the attention kernel's pre-scaled mode).
+// (they become the cached keys); outputs bf16: q token-major with row stride ld_out, k with element (token, head, e) at
+// token * ld_out_k + head * ld_out_head_k + e (token-major rows, or the cache's packed rows).  The q rows are multiplied by
+// q_scale before they are rounded (the attention kernel's pre-scaled mode).
 lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
-                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out,
-                                     float q_scale, hipStream_t stream) {
+                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
+                                     int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     if (n_tokens == 0) return LVX_OK;
-    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k, q_scale);
+    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k, q_scale,
+                       ld_out_k, ld_out_head_k);
 }
 
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
@@ -359,7 +372,7 @@ lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x,
 #define LVX_NORM32_LAUNCH(CPL)                                                                                                     \
     hipLaunchKernelGGL((lvx_rope_norm_kernel<CPL, 1, true>), grid, block, 0, stream, (const void *)nullptr, (const void *)x, ld_in, ld_in, \
                        (const float *)nullptr, g, n_tokens, 0, (bf16_t *)nullptr, (bf16_t *)y, ld_out, (int64_t)desc->head_dim, d,    \
-                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{}, 1.0f)
+                       desc->head_dim, desc->frame_h, desc->frame_w, desc->eps, 0, tab, 1, (int64_t)0, (int64_t)0, gain_table_t{}, 1.0f, ld_out, (int64_t)desc->head_dim)
     if (cpl <= 2)
         LVX_NORM32_LAUNCH(2);
     else if (cpl <= 10)
