@@ -24,10 +24,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA, published
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per attention launch at the full cache, from two rocprofv3 --pmc runs (FETCH_SIZE 604112 KiB, WRITE_SIZE 46856 KiB
+# HBM-side bytes per attention launch at the full cache, from two rocprofv3 --pmc runs (FETCH_SIZE 618857 KiB, WRITE_SIZE 46803 KiB
 # per dispatch; both counters read 1.000x the known size of a plain copy kernel in the same runs).  Summary and commands:
 # profiles/attention_gemm_14b_pmc_hbm_traffic.txt.  Only valid for the 24960-key, 4680-query, 40-head launch timed here.
-ATTN_TRAFFIC_BYTES = (604112 + 46856) * 1024
+ATTN_TRAFFIC_BYTES = (618857 + 46803) * 1024
 
 
 def attention_flops(n_q, n_k, H, D):
