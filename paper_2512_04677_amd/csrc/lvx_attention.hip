@@ -33,7 +33,7 @@ constexpr int KT = LVX_KEY_TILE;
 constexpr int TP2_MIN_KEYS = 16 * KT;
 
 template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false>
-__global__ void __launch_bounds__(64 * NWAVES)
+__global__ void __launch_bounds__(64 * NWAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
                          int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots) {
@@ -48,8 +48,8 @@ __global__ void __launch_bounds__(64 * NWAVES)
     // chunk c of row r is stored at position c ^ swz(r) instead (the lane fetches the matching global chunk), with
     // swz(r) = r & 15 for 256-byte rows and (r >> 1) & 7 for 128-byte rows: 16 consecutive rows then hit 16 distinct
     // 16-byte units of a 256-byte bank row.
-    constexpr int NS = 4;
-    static_assert(NS == 4 && (TP == 1 || TP == 2), "two stages of TP tiles must fit the ring");
+    constexpr int NS = NWAVES == 4 ? 2 : 4;  // two stages of TP tiles each (the 8-wave form keeps four slots at TP = 1 as well)
+    static_assert(NS >= 2 * TP && (TP == 1 || TP == 2), "two stages of TP tiles must fit the ring");
     constexpr int TILE_B = KT * D * 2;        // bytes per K tile = per V^T tile
     constexpr int K_ROW_B = D * 2;
     constexpr int K_RPI = 1024 / K_ROW_B;     // K rows per DMA instruction (4 or 8)
@@ -420,6 +420,9 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
 #ifdef LVX_ATTN_16W
     if (D == 128) return launch<128, 16, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
+#endif
+#ifdef LVX_ATTN_2WG  // experiment: workgroups of 4 waves (128 queries, 64 KB of LDS), two of them per CU
+    if (D == 128) return launch<128, 4, 2, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
 #endif
     if (q_prescaled) {  // q already carries scale * log2(e): see PRE in the kernel
         if (D == 128 && n_keys >= TP2_MIN_KEYS)
