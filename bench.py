@@ -126,9 +126,8 @@ def kernel_classes(prof, steps, n, d, f, n_k, n_ctx, H, D, L, sink_n, fp8=False)
     fl = {"attn_self": attention_flops(n, n_k, H, D), "gemm_qkv": 2.0 * n * d * 3 * d, "gemm_o": 2.0 * n * d * d, "gemm_cross": 2 * 2.0 * n * d * d,
           "gemm_ffn1": 2.0 * n * d * f, "gemm_ffn2": 2.0 * n * d * f, "attn_cross": attention_flops(n, n_ctx, H, D), "ctx_kv": 2 * 2.0 * n_ctx * d * d}
     # algorithmic bytes per layer: rope+norm reads q (bf16) and k (fp32; bf16 in an FP8 stage) and writes q^, k^ (bf16, k^ straight
-    # into the cache in a bf16 stage); the append then reads and writes v only (k^ as well in an FP8 stage); each LayerNorm reads
-    # the fp32 stream and writes bf16 (3 per layer)
-    by = {"rope_norm": n * d * (2 + 2 + 2 + 2) if fp8 else n * d * (2 + 4 + 2 + 2), "append": (4.0 if fp8 else 2.0) * n * d * 2,
+    # into the cache); the append then reads and writes v only; each LayerNorm reads the fp32 stream and writes bf16 (3 per layer)
+    by = {"rope_norm": n * d * (2 + 2 + 2 + 2) if fp8 else n * d * (2 + 4 + 2 + 2), "append": 2.0 * n * d * 2,
           "layernorm": 3.0 * n * d * (4 + 2), "cross_qnorm": 2.0 * n * d * 2}
     per_step = {"misc": n * d * (2 + 4) + n * d * (2 + 4 + 2), "sink_rope": L * sink_n * d * (4 + 2)}
     out = {}

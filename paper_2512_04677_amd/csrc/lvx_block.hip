@@ -163,7 +163,7 @@ lvx_status_t precompute_ctx(const lvx_stage_t *s, int l0, int l1, const bf16_t *
 // ctx_slot: slot of the context group that holds this layer's packed context K / V (bf16 stages, see precompute_ctx).
 lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x, int n, const bf16_t *ctx, int n_ctx,
                        const float *mod6, int64_t chunk_index, int t0, char *ws, const ws_layout_t &L, hipStream_t st, int *amax_cur,
-                       int ctx_slot, bool sink_prefill = false) {
+                       int ctx_slot, bool sink_prefill = false, bool ctx_codes_ready = false) {
     const lvx_block_weights_t &w = s->blocks[layer];
     const int H = s->rope.n_heads, D = s->rope.head_dim, d = H * D, f = s->d_ffn;
     const float eps = s->rope.eps;
@@ -214,7 +214,7 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     // 2e-5 of its RMS, and fp32 columns cost the GEMM's epilogue and the RoPE kernel their bytes).  FP8 stage: all three in bf16.
     float *k32 = (float *)(ws + L.qk32);
     const int64_t ld32 = L.ld_qk32;
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift1, scale1, eps, n, d, u, ldu, st, amax_out())); }
     {
         prof_scope_t ps(LVX_PROF_GEMM_QKV, st);
         if (w8 == nullptr) {
@@ -226,19 +226,23 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
             segs.s[2] = {Wq + (size_t)2 * d * ldw, big + 2 * d, ldq, d, 0, 0, 0};
             LVX_TRY(lvx_launch_linear_segments(u, ldu, ldw, segs, n, d, st));
         } else
-            LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false));
+            LVX_TRY(linear(u, ldu, w.W_qkv, 0, big, ldq, n, 3 * d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, true, false));
     }
     if (!sink_prefill) {
-        if (w8 == nullptr) {
+        {
             // the RoPE kernel writes the chunk's keys straight into their ring slot of the cache (one write instead of a write, a
-            // read and a write); the append then only has the values left to transpose
+            // read and a write); the append then only has the values left to transpose.  bf16 stage: k comes un-rounded (fp32).
             lvx_slot_info_t slot;
             LVX_TRY(lvx_cache_append_begin(c, layer, chunk_index, &slot));
             bf16_t *k_slot = const_cast<bf16_t *>(lvx_cache_k(c, layer)) + (size_t)slot.key_offset * D;
             {
                 prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
-                LVX_TRY(lvx_launch_rope_q16_k32(&s->rope, big, ldq, k32, ld32, w.g_q, w.g_k, n, t0, big, ldq, k_slot, D, (int64_t)c->cap_keys * D,
-                                                scale * LVX_LOG2E, st));
+                if (w8 == nullptr)
+                    LVX_TRY(lvx_launch_rope_qk(&s->rope, big, ldq, k32, 1, ld32, w.g_q, w.g_k, n, t0, big, ldq, k_slot, D, (int64_t)c->cap_keys * D,
+                                               scale * LVX_LOG2E, st));
+                else
+                    LVX_TRY(lvx_launch_rope_qk(&s->rope, big, ldq, big + d, 0, ldq, w.g_q, w.g_k, n, t0, big, ldq, k_slot, D,
+                                               (int64_t)c->cap_keys * D, scale * LVX_LOG2E, st));
             }
             {
                 prof_scope_t ps(LVX_PROF_APPEND, st);
@@ -246,12 +250,6 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
                                            const_cast<bf16_t *>(lvx_cache_vt(c, layer)), st));
             }
             lvx_cache_append_commit(c, layer, chunk_index, &slot);
-        } else {
-            {
-                prof_scope_t ps(LVX_PROF_ROPE_NORM, st);
-                LVX_TRY(lvx_launch_rope_bf16(&s->rope, big, big + d, ldq, w.g_q, w.g_k, n, t0, big, big + d, ldq, scale * LVX_LOG2E, st));
-            }
-            { prof_scope_t ps(LVX_PROF_APPEND, st); LVX_TRY(lvx_chunk_append_evict(c, layer, big + d, big + 2 * d, ldq, chunk_index, nullptr, st)); }
         }
         {
             prof_scope_t ps(LVX_PROF_ATTN_SELF, st);
@@ -281,14 +279,15 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     { prof_scope_t ps(LVX_PROF_GEMM_O, st); LVX_TRY(linear(u, ldu, w.W_o, 1, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, gate1, false, false, true, false)); }
 
     // cross-attention to the audio + text context
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, false, false)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st, amax_out())); }
+    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, true, false)); }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
     if (w.gc_q) { prof_scope_t ps(LVX_PROF_CROSS_QNORM, st); LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st)); }
     if (w8 != nullptr) {  // FP8 stage: this layer's context projections, norm and pack, into slot 0 (the context is quantised once)
         prof_scope_t ps(LVX_PROF_CTX_KV, st);
-        LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, false, false, false));
+        // (the context is the same for every layer of a call: its codes and scale are formed by the first layer and reused)
+        LVX_TRY(linear(ctx, d, w.Wc_k, 3, ctx_kv, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, ctx_codes_ready, false, false));
         LVX_TRY(linear(ctx, d, w.Wc_v, 4, ctx_kv + d, ldk, n_ctx, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, true, true, false, false));
         const float *gains[1] = {w.gc_k};
         LVX_TRY(lvx_launch_norm_to_packed_k(&s->rope, ctx_kv, 0, ldk, n_ctx, gains, pack_k, L.cap_ctx, 1, 0, 0, st));
@@ -298,8 +297,8 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
     { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false, true, false)); }
 
     // feed-forward
-    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, ldu, st)); }
-    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(linear(u, ldu, w.W_1, 6, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, false, false, false, true)); }
+    { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, shift2, scale2, eps, n, d, u, ldu, st, amax_out())); }
+    { prof_scope_t ps(LVX_PROF_GEMM_FFN1, st); LVX_TRY(linear(u, ldu, w.W_1, 6, big, ldf, n, f, d, LVX_EPI_GELU_TANH, nullptr, 0, nullptr, false, false, true, true)); }
     { prof_scope_t ps(LVX_PROF_GEMM_FFN2, st); LVX_TRY(linear(big, ldf, w.W_2, 7, x, d, n, d, f, LVX_EPI_RESID_GATE_F32, x, d, gate2, false, false, true, false)); }
     return LVX_OK;
 }
@@ -326,7 +325,7 @@ lvx_status_t run_layers(const lvx_stage_t *s, int l0, int l1, lvx_kvcache *c, fl
             if (slot == 0) LVX_TRY(precompute_ctx(s, l, l + L.ctx_group < l1 ? l + L.ctx_group : l1, ctx, n_ctx, ws, L, st));
         }
         const float *m6 = mod6 ? mod6 + (size_t)(l - l0) * mod6_stride : nullptr;
-        LVX_TRY(run_block(s, l, c, h, n, ctx, n_ctx, m6, chunk_index, t0, ws, L, st, amax_cur, slot, sink_prefill));
+        LVX_TRY(run_block(s, l, c, h, n, ctx, n_ctx, m6, chunk_index, t0, ws, L, st, amax_cur, slot, sink_prefill, l > l0));
     }
     return LVX_OK;
 }

@@ -101,7 +101,7 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
 lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
 lvx_status_t lvx_launch_widen(const bf16_t *src, float *dst, size_t n_elems, hipStream_t stream);
 lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,
-                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream);
+                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream, uint32_t *amax_slots = nullptr);
 // Strided row copy [n_rows][row_elems] (row_elems % 8 == 0), bit-exact.
 lvx_status_t lvx_launch_copy_rows(const bf16_t *src, int64_t ld_src, bf16_t *dst, int64_t ld_dst, int n_rows, int row_elems,
                                   hipStream_t stream);
@@ -111,12 +111,9 @@ lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const floa
                                          bf16_t *k_packed, int cap, int n_layers, int64_t layer_stride_src, int64_t layer_stride_dst,
                                          hipStream_t stream);
 // RMSNorm + RoPE with q rows in bf16 and k rows in fp32 (outputs bf16).
-lvx_status_t lvx_launch_rope_bf16(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
-                                  const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, float q_scale,
-                                  hipStream_t stream);
-lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
-                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
-                                     int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream);
+lvx_status_t lvx_launch_rope_qk(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const void *k_in, int k_is_f32, int64_t ld_k,
+                                const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
+                                int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream);
 // Append in two steps for a producer that writes the chunk's keys into the cache itself: begin validates and names the slot
 // (nothing changes), commit records the chunk in the layer's ring state.
 lvx_status_t lvx_cache_append_begin(const lvx_kvcache *c, int layer, int64_t chunk_index, lvx_slot_info_t *info);

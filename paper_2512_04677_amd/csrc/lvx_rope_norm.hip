@@ -143,69 +143,94 @@ template <int CPL, bool F32IN>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     lvx_layernorm_modulate_kernel(const void *__restrict__ x_in, int64_t ldx, const float *__restrict__ shift,
                                   const float *__restrict__ scale, float eps, int n_tokens, int d, bf16_t *__restrict__ u_out,
-                                  int64_t ldu) {
+                                  int64_t ldu, uint32_t *__restrict__ amax_slots) {
     const int lane = threadIdx.x & 63;
     const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
-    if (token >= n_tokens) return;
-    const int n_chunks = d / 8;
-    float x[CPL][8];
-    float sum = 0.f;
+    // amax_slots != NULL: the output feeds an FP8 linear, whose per-tensor scale needs max |u| over the whole tensor: every
+    // workgroup adds the largest magnitude among the bf16 values it stores (one atomic per workgroup, spread over the slots)
+    __shared__ uint32_t wg_amax[ROWS_PER_WG];
+    uint32_t amax_b = 0;
+    if (token < n_tokens) {
+        const int n_chunks = d / 8;
+        float x[CPL][8];
+        float sum = 0.f;
 #pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-        const int c = lane + 64 * j;
-        if (c < n_chunks) {
-            if (F32IN) {
-                const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(x_in) + (size_t)token * ldx) + 2 * c;
-                const float4 a = src[0], b = src[1];
-                x[j][0] = a.x, x[j][1] = a.y, x[j][2] = a.z, x[j][3] = a.w, x[j][4] = b.x, x[j][5] = b.y, x[j][6] = b.z, x[j][7] = b.w;
-            } else {
-                const u32x4_t v = reinterpret_cast<const u32x4_t *>(reinterpret_cast<const bf16_t *>(x_in) + (size_t)token * ldx)[c];
+        for (int j = 0; j < CPL; ++j) {
+            const int c = lane + 64 * j;
+            if (c < n_chunks) {
+                if (F32IN) {
+                    const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(x_in) + (size_t)token * ldx) + 2 * c;
+                    const float4 a = src[0], b = src[1];
+                    x[j][0] = a.x, x[j][1] = a.y, x[j][2] = a.z, x[j][3] = a.w, x[j][4] = b.x, x[j][5] = b.y, x[j][6] = b.z, x[j][7] = b.w;
+                } else {
+                    const u32x4_t v = reinterpret_cast<const u32x4_t *>(reinterpret_cast<const bf16_t *>(x_in) + (size_t)token * ldx)[c];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    x[j][2 * e] = bf16_lo(v[e]);
-                    x[j][2 * e + 1] = bf16_hi(v[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        x[j][2 * e] = bf16_lo(v[e]);
+                        x[j][2 * e + 1] = bf16_hi(v[e]);
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum += x[j][e];
+            }
+        }
+        const float mean = wave_sum(sum) / (float)d;
+        float sq = 0.f;
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int c = lane + 64 * j;
+            if (c < n_chunks) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float a = x[j][e] - mean;
+                    sq += a * a;
                 }
             }
+        }
+        const float rinv = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
+        u32x4_t *dst = reinterpret_cast<u32x4_t *>(u_out + (size_t)token * ldu);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sum += x[j][e];
+        for (int j = 0; j < CPL; ++j) {
+            const int c = lane + 64 * j;
+            if (c < n_chunks) {
+                float sc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sh[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                if (scale != nullptr) {
+                    const float4 a = *reinterpret_cast<const float4 *>(scale + c * 8), b = *reinterpret_cast<const float4 *>(scale + c * 8 + 4);
+                    sc[0] = a.x, sc[1] = a.y, sc[2] = a.z, sc[3] = a.w, sc[4] = b.x, sc[5] = b.y, sc[6] = b.z, sc[7] = b.w;
+                }
+                if (shift != nullptr) {
+                    const float4 a = *reinterpret_cast<const float4 *>(shift + c * 8), b = *reinterpret_cast<const float4 *>(shift + c * 8 + 4);
+                    sh[0] = a.x, sh[1] = a.y, sh[2] = a.z, sh[3] = a.w, sh[4] = b.x, sh[5] = b.y, sh[6] = b.z, sh[7] = b.w;
+                }
+                u32x4_t y;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = (x[j][2 * e] - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
+                    const float b = (x[j][2 * e + 1] - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
+                    y[e] = pack_bf16x2(a, b);
+                    if (amax_slots != nullptr) {
+                        const uint32_t lo = y[e] & 0x7fffu, hi = (y[e] >> 16) & 0x7fffu;
+                        amax_b = amax_b > lo ? amax_b : lo;
+                        amax_b = amax_b > hi ? amax_b : hi;
+                    }
+                }
+                dst[c] = y;
+            }
         }
     }
-    const float mean = wave_sum(sum) / (float)d;
-    float sq = 0.f;
+    if (amax_slots != nullptr) {  // uniform over the grid: every wave of the workgroup gets here
 #pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-        const int c = lane + 64 * j;
-        if (c < n_chunks) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float a = x[j][e] - mean;
-                sq += a * a;
-            }
+        for (int s = 32; s >= 1; s >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)amax_b, s);
+            amax_b = amax_b > o ? amax_b : o;
         }
-    }
-    const float rinv = 1.0f / sqrtf(wave_sum(sq) / (float)d + eps);
-    u32x4_t *dst = reinterpret_cast<u32x4_t *>(u_out + (size_t)token * ldu);
+        if (lane == 0) wg_amax[threadIdx.x >> 6] = amax_b;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t m = wg_amax[0];
 #pragma unroll
-    for (int j = 0; j < CPL; ++j) {
-        const int c = lane + 64 * j;
-        if (c < n_chunks) {
-            float sc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, sh[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (scale != nullptr) {
-                const float4 a = *reinterpret_cast<const float4 *>(scale + c * 8), b = *reinterpret_cast<const float4 *>(scale + c * 8 + 4);
-                sc[0] = a.x, sc[1] = a.y, sc[2] = a.z, sc[3] = a.w, sc[4] = b.x, sc[5] = b.y, sc[6] = b.z, sc[7] = b.w;
-            }
-            if (shift != nullptr) {
-                const float4 a = *reinterpret_cast<const float4 *>(shift + c * 8), b = *reinterpret_cast<const float4 *>(shift + c * 8 + 4);
-                sh[0] = a.x, sh[1] = a.y, sh[2] = a.z, sh[3] = a.w, sh[4] = b.x, sh[5] = b.y, sh[6] = b.z, sh[7] = b.w;
-            }
-            u32x4_t y;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float a = (x[j][2 * e] - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
-                const float b = (x[j][2 * e + 1] - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
-                y[e] = pack_bf16x2(a, b);
-            }
-            dst[c] = y;
+            for (int w = 1; w < ROWS_PER_WG; ++w) m = m > wg_amax[w] ? m : wg_amax[w];
+            if (m != 0) atomicMax(amax_slots + (blockIdx.x & (LVX_AMAX_SLOTS - 1)), m << 16);
         }
     }
 }
@@ -301,13 +326,6 @@ static lvx_status_t rope3d_entry(const lvx_rope_desc_t *desc, const void *dev_q_
                        desc->head_dim, (hipStream_t)stream, 1, 0, 0, f32_in ? 1 : 0, nullptr, -1, q_scale);
 }
 
-// lvx_rope3d on bf16 rows with the q rows multiplied by q_scale before their rounding (the attention kernel's pre-scaled mode)
-lvx_status_t lvx_launch_rope_bf16(const lvx_rope_desc_t *desc, const bf16_t *q_in, const bf16_t *k_in, int64_t ld_in, const float *g_q,
-                                  const float *g_k, int n_tokens, int t0, bf16_t *q_out, bf16_t *k_out, int64_t ld_out, float q_scale,
-                                  hipStream_t stream) {
-    return rope3d_entry(desc, q_in, k_in, ld_in, false, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, (lvx_stream_t)stream, q_scale);
-}
-
 extern "C" lvx_status_t lvx_rope3d(const lvx_rope_desc_t *desc, const void *dev_q_in, const void *dev_k_in, int64_t ld_in,
                                    const float *dev_g_q, const float *dev_g_k, int32_t n_tokens, int32_t t0, void *dev_q_out,
                                    void *dev_k_out, int64_t ld_out, lvx_stream_t stream) {
@@ -320,18 +338,18 @@ extern "C" lvx_status_t lvx_rope3d_f32in(const lvx_rope_desc_t *desc, const floa
     return rope3d_entry(desc, dev_q_in, dev_k_in, ld_in, true, dev_g_q, dev_g_k, n_tokens, t0, dev_q_out, dev_k_out, ld_out, stream);
 }
 
-// q rows bf16 (ld_q elements), k rows fp32 (ld_k fp32 elements): the block's QKV projection keeps only its k columns un-rounded
-// (they become the cached keys); outputs bf16: q token-major with row stride ld_out, k with element (token, head, e) at
-// token * ld_out_k + head * ld_out_head_k + e (token-major rows, or the cache's packed rows).  The q rows are multiplied by
-// q_scale before they are rounded (the attention kernel's pre-scaled mode).
-lvx_status_t lvx_launch_rope_q16_k32(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const float *k_in, int64_t ld_k,
-                                     const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
-                                     int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream) {
+// The block's RMSNorm + RoPE: q rows bf16 (ld_q elements); k rows fp32 (ld_k fp32 elements: a bf16 stage's QKV projection keeps its
+// k columns un-rounded, they become the cached keys) or bf16 (ld_k bf16 elements).  Outputs bf16: q token-major with row stride
+// ld_out, multiplied by q_scale before the rounding (the attention kernel's pre-scaled mode); k with element (token, head, e) at
+// token * ld_out_k + head * ld_out_head_k + e (token-major rows, or straight into the cache's packed rows).
+lvx_status_t lvx_launch_rope_qk(const lvx_rope_desc_t *desc, const bf16_t *q_in, int64_t ld_q, const void *k_in, int k_is_f32, int64_t ld_k,
+                                const float *g_q, const float *g_k, int n_tokens, int t0, bf16_t *q_out, int64_t ld_out, bf16_t *k_out,
+                                int64_t ld_out_k, int64_t ld_out_head_k, float q_scale, hipStream_t stream) {
     lvx_status_t st = check_rope_desc(desc);
     if (st != LVX_OK) return st;
     if (n_tokens == 0) return LVX_OK;
-    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, 2, nullptr, ld_k, q_scale,
-                       ld_out_k, ld_out_head_k);
+    return launch_rope(desc, q_in, k_in, ld_q, g_q, g_k, n_tokens, t0, q_out, k_out, ld_out, desc->head_dim, stream, 1, 0, 0, k_is_f32 ? 2 : 0,
+                       nullptr, ld_k, q_scale, ld_out_k, ld_out_head_k);
 }
 
 lvx_status_t lvx_launch_rope_to_packed_k(const lvx_rope_desc_t *desc, const float *src, int64_t ld_src, int n_tokens, int t0,
@@ -385,7 +403,7 @@ lvx_status_t lvx_launch_rmsnorm_f32(const lvx_rope_desc_t *desc, const float *x,
 }
 
 lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, const float *shift, const float *scale, float eps,
-                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream) {
+                                  int n_tokens, int d, bf16_t *u, int64_t ldu, hipStream_t stream, uint32_t *amax_slots) {
     LVX_REQUIRE(x != nullptr && u != nullptr, LVX_ERR_INVALID_ARG, "x or u is NULL");
     LVX_REQUIRE(lvx_aligned16(x) && lvx_aligned16(u) && lvx_aligned16(shift) && lvx_aligned16(scale), LVX_ERR_INVALID_ARG,
                 "pointers must be 16-byte aligned");
@@ -396,7 +414,8 @@ lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, cons
     const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
 #define LVX_LN_LAUNCH(CPL, F32)                                                                                                  \
-    hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, u, ldu)
+    hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, u, ldu, \
+                       amax_slots)
     if (x_is_f32) {
         if (cpl <= 2)
             LVX_LN_LAUNCH(2, true);
@@ -419,5 +438,5 @@ lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, cons
 
 extern "C" lvx_status_t lvx_layernorm_modulate(const void *dev_x, int64_t ldx, const float *dev_shift, const float *dev_scale, float eps,
                                                int32_t n_tokens, int32_t d, void *dev_u, int64_t ldu, lvx_stream_t stream) {
-    return lvx_launch_layernorm(dev_x, 0, ldx, dev_shift, dev_scale, eps, n_tokens, d, (bf16_t *)dev_u, ldu, (hipStream_t)stream);
+    return lvx_launch_layernorm(dev_x, 0, ldx, dev_shift, dev_scale, eps, n_tokens, d, (bf16_t *)dev_u, ldu, (hipStream_t)stream, nullptr);
 }
