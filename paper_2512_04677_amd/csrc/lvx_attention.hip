@@ -32,11 +32,11 @@ constexpr int KT = LVX_KEY_TILE;
 // keys, equal at 1560, 3 to 4 % faster from 6240 keys on)
 constexpr int TP2_MIN_KEYS = 16 * KT;
 
-template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false>
+template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false, bool QN = false>
 __global__ void __launch_bounds__(64 * NWAVES) __attribute__((amdgpu_waves_per_eu(2, 2)))
     lvx_attention_kernel(const bf16_t *__restrict__ q, int64_t ld_q, int n_q, const bf16_t *__restrict__ kp,
                          const bf16_t *__restrict__ vtp, int cap, int n_keys, float c_exp2, bf16_t *__restrict__ out,
-                         int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots) {
+                         int64_t ld_out, int n_qtiles, int total_wg, int per_xcd, uint32_t *amax_slots, lvx_attn_qnorm_t qn) {
     constexpr int QT = 16 * QB * NWAVES;  // QB blocks of 16 queries per wave
     constexpr int MK = D / 32;  // MFMA k-steps (32 wide) over head_dim
     constexpr int DB = D / 16;  // 16-row blocks of O^T
@@ -76,6 +76,21 @@ __global__ void __launch_bounds__(64 * NWAVES) __attribute__((amdgpu_waves_per_e
     // Q fragments (B operand of S^T = K Q^T, v_mfma_f32_16x16x32_bf16): for query block qb, lane (l16, q4) holds
     // Q[query 16qb + l16][d = 32m + 8q4 .. +7]
     bf16x8_t qf[QB][MK];
+    float ss_row = 0.f;
+    if (QN) {
+        // lane L adds one half (L & 1) of the partial sums of query row L / 2 of this wave: contiguous 16-byte loads, all issued
+        // before the first add, in a fixed order (the result is bit-reproducible); the two halves meet through one shuffle
+        int r = qtile * QT + wave * 32 + (lane >> 1);
+        if (r > n_q - 1) r = n_q - 1;
+        const int per4 = qn.n_parts / 8;  // float4 loads per lane, at most 16 (d_model <= 8192)
+        const float4 *pp = reinterpret_cast<const float4 *>(qn.sumsq + (size_t)r * qn.ld + (lane & 1) * (qn.n_parts / 2));
+        float4 part[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[i] = i < per4 ? pp[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ss_row += (part[i].x + part[i].y) + (part[i].z + part[i].w);
+        ss_row += __shfl_xor(ss_row, 1);
+    }
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         int row = qtile * QT + wave * (16 * QB) + 16 * qb + l16;
@@ -83,6 +98,25 @@ __global__ void __launch_bounds__(64 * NWAVES) __attribute__((amdgpu_waves_per_e
         const bf16_t *qp = q + (size_t)row * ld_q + (size_t)head * D + q4 * 8;
 #pragma unroll
         for (int m = 0; m < MK; ++m) qf[qb][m] = *reinterpret_cast<const bf16x8_t *>(qp + 32 * m);
+        if (QN) {
+            // RMSNorm of the query row over all d_model channels, its gain and the logit scale, applied in fp32 to the bf16
+            // projection output and rounded once.  ss_row (computed once per wave, above) holds the sum of squares of query
+            // row lane / 2 of this wave in every lane.
+            static_assert(!QN || (PRE && QB == 2), "normalised queries are also pre-scaled; 32 query rows per wave");
+            const float ss = __shfl(ss_row, 2 * (16 * qb + l16));
+            const float rinv = c_exp2 / sqrtf(ss / (float)qn.d_model + qn.eps);
+            const float *gp = qn.gain + head * D + q4 * 8;
+#pragma unroll
+            for (int m = 0; m < MK; ++m) {
+                const float4 g0 = *reinterpret_cast<const float4 *>(gp + 32 * m), g1 = *reinterpret_cast<const float4 *>(gp + 32 * m + 4);
+                const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                u32x4_t w = __builtin_bit_cast(u32x4_t, qf[qb][m]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    w[e] = pack_bf16x2(bf16_lo(w[e]) * rinv * gg[2 * e], bf16_hi(w[e]) * rinv * gg[2 * e + 1]);
+                qf[qb][m] = __builtin_bit_cast(bf16x8_t, w);
+            }
+        }
     }
 
     const int n_tiles = (n_keys + KT - 1) / KT;
@@ -396,16 +430,18 @@ __global__ void __launch_bounds__(64 * NWAVES) __attribute__((amdgpu_waves_per_e
     }
 }
 
-template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false>
+template <int D, int NWAVES, int QB = 2, int TP = 1, bool PRE = false, bool QN = false>
 lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t *kp, const bf16_t *vtp, int cap, int n_keys,
-                    float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots) {
+                    float scale, bf16_t *out, int64_t ld_out, hipStream_t stream, uint32_t *amax_slots, const lvx_attn_qnorm_t *qnorm = nullptr) {
     constexpr int QT = 16 * QB * NWAVES;
     const int n_qtiles = (n_q + QT - 1) / QT;
     const int total = n_qtiles * H;
     const int per_xcd = (total + 7) / 8;
     const float c = scale * LVX_LOG2E;
-    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB, TP, PRE>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
-                       n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots);
+    lvx_attn_qnorm_t qn = {};
+    if (qnorm != nullptr) qn = *qnorm;
+    hipLaunchKernelGGL((lvx_attention_kernel<D, NWAVES, QB, TP, PRE, QN>), dim3(per_xcd * 8), dim3(64 * NWAVES), 0, stream, q, ld_q, n_q, kp, vtp, cap,
+                       n_keys, c, out, ld_out, n_qtiles, total, per_xcd, amax_slots, qn);
     LVX_CHECK_HIP(hipGetLastError());
     return LVX_OK;
 }
@@ -414,7 +450,7 @@ lvx_status_t launch(const bf16_t *q, int64_t ld_q, int n_q, int H, const bf16_t 
 
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream, uint32_t *amax_slots, bool q_prescaled) {
+                                  hipStream_t stream, uint32_t *amax_slots, bool q_prescaled, const lvx_attn_qnorm_t *qnorm) {
     LVX_REQUIRE(n_q > 0 && n_keys > 0 && n_keys <= cap && cap % KT == 0, LVX_ERR_SHAPE, "attention: n_q %d, n_keys %d, cap %d", n_q,
                 n_keys, cap);
     LVX_REQUIRE(scale > 0.f, LVX_ERR_INVALID_ARG, "attention: scale must be positive");
@@ -424,6 +460,13 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
 #ifdef LVX_ATTN_2WG  // experiment: workgroups of 4 waves (128 queries, 64 KB of LDS), two of them per CU
     if (D == 128) return launch<128, 4, 2, 1>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);
 #endif
+    if (qnorm != nullptr) {  // the kernel normalises and scales the queries as it loads them (cross-attention of a bf16 stage)
+        LVX_REQUIRE(D == 128 && qnorm->sumsq != nullptr && qnorm->gain != nullptr && qnorm->n_parts > 0 && qnorm->n_parts % 8 == 0 &&
+                        qnorm->n_parts <= 128 && qnorm->ld % 4 == 0 && qnorm->d_model == H * D,
+                    LVX_ERR_INVALID_ARG,
+                    "attention: query norm needs head_dim 128, partial sums and a gain");
+        return launch<128, 8, 2, 1, true, true>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots, qnorm);
+    }
     if (q_prescaled) {  // q already carries scale * log2(e): see PRE in the kernel
         if (D == 128 && n_keys >= TP2_MIN_KEYS)
             return launch<128, 8, 2, 2, true>(q, ld_q, n_q, H, k_packed, vt_packed, cap, n_keys, scale, out, ld_out, stream, amax_slots);

@@ -48,7 +48,7 @@ typedef lvx_prof_scope_t prof_scope_t;
 constexpr int CTX_GROUP = LVX_GEMM_MAX_SEGS / 2;
 
 struct ws_layout_t {
-    size_t u, big, qk32, ctx_k32, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
+    size_t u, big, qk32, q_sumsq, ctx_k32, ctx_kv, pack_k, pack_v, h, q8, q8_ctx, q8_misc, total;  // byte offsets
     int64_t ld_q8, ld_q8c;                            // row strides (bytes) of the FP8 activation buffers
     int cap_ctx, ctx_group;
     int64_t ld_u, ld_qkv, ld_cq, ld_ffn, ld_ckv;      // padded row strides (elements) of the bf16 workspace matrices
@@ -77,6 +77,8 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.big = off;     off += round256((size_t)n_tokens * (wide + WS_PAD) * 2);
     w.qk32 = off;    // fp32 k columns of the QKV projection (bf16 stages only; an FP8 stage stores them in bf16)
     if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * w.ld_qk32 * 4);
+    w.q_sumsq = off;  // partial sums of squares of the cross-attention's query rows (bf16 stages), d / 64 per row
+    if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * LVX_GEMM_SUMSQ_PARTS(d) * 4);
     // context K | V rows and their packed forms for a group of layers at once (bf16 stages; an FP8 stage uses one slot)
     w.ctx_group = s->blocks_fp8 != nullptr ? 1 : (s->n_layers < CTX_GROUP ? s->n_layers : CTX_GROUP);
     w.ctx_kv = off;  off += round256((size_t)w.ctx_group * n_ctx * w.ld_ckv * 2);
@@ -280,10 +282,24 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
 
     // cross-attention to the audio + text context
     { prof_scope_t ps(LVX_PROF_LAYERNORM, st); LVX_TRY(lvx_launch_layernorm(x, 1, d, nullptr, nullptr, eps, n, d, u, ldu, st, amax_out())); }
-    { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, true, false)); }
+    // bf16 stage with a query gain: the projection leaves each row's partial sums of squares beside its bf16 output and the
+    // attention kernel normalises, scales and rounds the queries as it loads them (no norm-only pass over q)
+    const bool fuse_qnorm = w8 == nullptr && w.gc_q != nullptr && D == 128 && d % 512 == 0 && d <= 8192;
+    float *q_sumsq = (float *)(ws + L.q_sumsq);
+    const int q_parts = LVX_GEMM_SUMSQ_PARTS(d);
+    {
+        prof_scope_t ps(LVX_PROF_GEMM_CROSS, st);
+        if (fuse_qnorm) {
+            lvx_gemm_segs_t segs;
+            segs.n = 1;
+            segs.s[0] = {(const bf16_t *)w.Wc_q, big, ldc, d, 0, 0, q_parts, q_sumsq};
+            LVX_TRY(lvx_launch_linear_segments(u, ldu, ldw, segs, n, d, st));
+        } else
+            LVX_TRY(linear(u, ldu, w.Wc_q, 2, big, ldc, n, d, d, LVX_EPI_STORE, nullptr, 0, nullptr, false, false, true, false));
+    }
     lvx_rope_desc_t norm_only = s->rope;
     norm_only.apply_rope = 0;
-    if (w.gc_q) { prof_scope_t ps(LVX_PROF_CROSS_QNORM, st); LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st)); }
+    if (w.gc_q && !fuse_qnorm) { prof_scope_t ps(LVX_PROF_CROSS_QNORM, st); LVX_TRY(lvx_rope3d(&norm_only, big, nullptr, ldc, w.gc_q, nullptr, n, 0, big, nullptr, ldc, st)); }
     if (w8 != nullptr) {  // FP8 stage: this layer's context projections, norm and pack, into slot 0 (the context is quantised once)
         prof_scope_t ps(LVX_PROF_CTX_KV, st);
         // (the context is the same for every layer of a call: its codes and scale are formed by the first layer and reused)
@@ -293,7 +309,11 @@ lvx_status_t run_block(const lvx_stage_t *s, int layer, lvx_kvcache *c, float *x
         LVX_TRY(lvx_launch_norm_to_packed_k(&s->rope, ctx_kv, 0, ldk, n_ctx, gains, pack_k, L.cap_ctx, 1, 0, 0, st));
         LVX_TRY(lvx_launch_pack_kv(nullptr, ctx_kv + d, ldk, n_ctx, H, D, L.cap_ctx, 0, pack_k, pack_v, st));
     }
-    { prof_scope_t ps(LVX_PROF_ATTN_CROSS, st); LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st, amax_out())); }
+    {
+        prof_scope_t ps(LVX_PROF_ATTN_CROSS, st);
+        const lvx_attn_qnorm_t qn = {q_sumsq, w.gc_q, q_parts, q_parts, d, s->rope.eps};
+        LVX_TRY(lvx_launch_attention(big, ldc, n, H, D, pack_k, pack_v, L.cap_ctx, n_ctx, scale, u, ldu, st, amax_out(), false, fuse_qnorm ? &qn : nullptr));
+    }
     { prof_scope_t ps(LVX_PROF_GEMM_CROSS, st); LVX_TRY(linear(u, ldu, w.Wc_o, 5, x, d, n, d, d, LVX_EPI_RESID_GATE_F32, x, d, nullptr, false, false, true, false)); }
 
     // feed-forward

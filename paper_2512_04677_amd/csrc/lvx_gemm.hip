@@ -65,6 +65,25 @@ __device__ __forceinline__ void lvx_gemm_epilogue(f32x4_t (&acc)[FM][FN], f32x4_
     }
 }
 
+// Sum of squares of this wave's FN * 16 columns for each of its rows (fp32 accumulators), one float per row at out[m * ld + part].
+template <int FM, int FN>
+__device__ __forceinline__ void lvx_gemm_row_sumsq(const f32x4_t (&acc)[FM][FN], float *out, int64_t ld, int part, int M, int m0, int l16) {
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) ss += acc[i][j][e] * acc[i][j][e];
+            ss += __shfl_xor(ss, 1);
+            ss += __shfl_xor(ss, 2);
+            ss += __shfl_xor(ss, 4);
+            ss += __shfl_xor(ss, 8);
+            const int m = m0 + i * 16 + e;
+            if (l16 == 0 && m < M) out[(size_t)m * ld + part] = ss;
+        }
+}
+
 // gfx950's global_load_lds_dwordx4 moves 16 bytes per lane from
 // global memory straight into LDS (LDS byte address = M0 + 16*lane), so a slab needs no staging registers, no ds_write
 // and no trip through the register file; the pipeline depth is set by LDS stages (three 48 KB stages for a 128x256 tile)
@@ -122,6 +141,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
     // several projections of the same activations in one launch (tiles_n counts all of them): the column tile's segment gives
     // the weight matrix, the output, its width, its row stride and whether it is stored in fp32 (workgroup-uniform)
     bool seg_f32 = false;
+    float *seg_sumsq = nullptr;
+    int seg_ld_sumsq = 0;
     if (EPI == LVX_EPI_SEGMENTS) {
         int sg = 0;
         for (int i = 1; i < segs.n; ++i)
@@ -132,6 +153,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
         ldc = segs.s[sg].ldc;
         N = segs.s[sg].N;
         seg_f32 = segs.s[sg].f32 != 0;
+        seg_sumsq = segs.s[sg].sumsq;
+        seg_ld_sumsq = segs.s[sg].ld_sumsq;
     }
 
     const int tid = threadIdx.x;
@@ -295,6 +318,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N)
             lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE_F32>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
         else
             lvx_gemm_epilogue<FM, FN, LVX_EPI_STORE>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
+        if (seg_sumsq != nullptr) lvx_gemm_row_sumsq<FM, FN>(acc, seg_sumsq, seg_ld_sumsq, tn * WAVES_N + wn, M, m0, l16);
     } else {
         lvx_gemm_epilogue<FM, FN, EPI>(acc, rres, C, ldc, R, ldr, gate, M, N, m0, n0);
     }
@@ -575,6 +599,9 @@ lvx_status_t lvx_launch_linear_segments(const bf16_t *A, int64_t lda, int64_t ld
     LVX_REQUIRE(segs.n >= 1 && segs.n <= LVX_GEMM_MAX_SEGS, LVX_ERR_INVALID_ARG, "linear segments: %d segments (1..%d)", segs.n, LVX_GEMM_MAX_SEGS);
     for (int i = 0; i < segs.n; ++i)
         LVX_TRY(check_dual(A, lda, segs.s[i].W, segs.s[i].W, ldw, segs.s[i].C, segs.s[i].ldc, segs.s[i].C, segs.s[i].ldc, M, segs.s[i].N, segs.s[i].N, K));
+    for (int i = 0; i < segs.n; ++i)
+        LVX_REQUIRE(segs.s[i].sumsq == nullptr || (segs.s[i].N % 256 == 0 && !segs.s[i].f32 && segs.s[i].ld_sumsq >= LVX_GEMM_SUMSQ_PARTS(segs.s[i].N)),
+                    LVX_ERR_SHAPE, "linear segments: row sums of squares need a bf16 segment of N %% 256 == 0 and ld_sumsq >= N / 64");
     if (M == 0) return LVX_OK;
     return launch<128, 256, 2, 4>(A, lda, segs.s[0].W, ldw, (bf16_t *)segs.s[0].C, segs.s[0].ldc, M, segs.s[0].N, K, (int)LVX_EPI_SEGMENTS, nullptr, 0,
                                   nullptr, stream, &segs);

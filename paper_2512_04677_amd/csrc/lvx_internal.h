@@ -93,9 +93,19 @@ lvx_status_t lvx_launch_pack_kv(const bf16_t *k, const bf16_t *v, int64_t ld, in
                                 bf16_t *k_packed, bf16_t *vt_packed, hipStream_t stream, int n_batch = 1, int64_t batch_stride_src = 0,
                                 int64_t batch_stride_dst = 0);
 // Attention of q [n_q][ld_q] against packed K / V^T holding n_keys visible keys per head.
+// Optional transform of the queries as the attention kernel loads them: RMSNorm over all d_model channels with the row's sum of
+// squares given as n_parts partial sums (lvx_gemm_seg_t::sumsq) and a per-channel gain; the kernel also multiplies by
+// scale * log2(e) and rounds to bf16 once (its pre-scaled mode).  Replaces a separate norm-only pass over q.
+struct lvx_attn_qnorm_t {
+    const float *sumsq;  // [n_q][ld] partial sums of squares
+    const float *gain;   // [d_model]
+    int32_t n_parts, ld, d_model;
+    float eps;
+};
 lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H, int D, const bf16_t *k_packed,
                                   const bf16_t *vt_packed, int cap, int n_keys, float scale, bf16_t *out, int64_t ld_out,
-                                  hipStream_t stream, uint32_t *amax_slots = nullptr, bool q_prescaled = false);
+                                  hipStream_t stream, uint32_t *amax_slots = nullptr, bool q_prescaled = false,
+                                  const lvx_attn_qnorm_t *qnorm = nullptr);
 // out = bf16((x ? x : 0) + dt * h) with h in fp32: the Euler step of the stage (x given) or the narrowing of a block's
 // fp32 residual stream (x NULL, dt 1).
 lvx_status_t lvx_launch_euler(const bf16_t *x, const float *h, float dt, bf16_t *out, size_t n_elems, hipStream_t stream);
@@ -152,8 +162,13 @@ struct lvx_gemm_seg_t {
     const bf16_t *W;
     void *C;
     int64_t ldc;
-    int32_t N, tn_begin, f32, pad;
+    int32_t N, tn_begin, f32, ld_sumsq;
+    // NULL, or [M][ld_sumsq] floats: besides the bf16 store, every wave leaves the sum of squares of its 64 columns (taken on the
+    // fp32 accumulators) of each of its rows at column index (column tile within the segment) * 4 + (wave column): the partial
+    // sums of a row's RMS, added up in a fixed order by the consumer (no atomics: results stay bit-reproducible).  N % 256 == 0.
+    float *sumsq;
 };
+#define LVX_GEMM_SUMSQ_PARTS(N_) ((N_) / 64)
 struct lvx_gemm_segs_t {
     int32_t n, pad;
     lvx_gemm_seg_t s[LVX_GEMM_MAX_SEGS];

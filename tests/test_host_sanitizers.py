@@ -31,12 +31,11 @@ def test_host_logic_is_clean_under_asan_and_ubsan(tmp_path):
     with ThreadPoolExecutor(max_workers=4) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     drv = str(tmp_path / "driver.o")
-    r = subprocess.run([HIPCC, "--cuda-host-only", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-omit-frame-pointer",
-                        "-I" + os.path.join(ROOT, "include"), "-x", "c++", os.path.join(ROOT, "tests", "host_sanitize", "driver.cpp"), "-c",
-                        "-o", drv], capture_output=True, text=True)
+    r = subprocess.run(common + HOST_SAN + ["-x", "hip", os.path.join(ROOT, "tests", "host_sanitize", "driver.cpp"), "-c", "-o", drv],
+                       capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
     exe = str(tmp_path / "driver")
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-o", exe, drv] + objs, capture_output=True, text=True)
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950"] + HOST_SAN + ["-o", exe, drv] + objs, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-2000:]
     env = dict(os.environ)
     # leaks: the HIP runtime's own start-up allocations; link order: other preloaded libraries may come before the runtime
