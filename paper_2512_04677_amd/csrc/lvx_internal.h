@@ -178,9 +178,9 @@ lvx_status_t lvx_launch_linear_segments(const bf16_t *A, int64_t lda, int64_t ld
 #define LVX_EPI_SEGMENTS 100
 // Per-tensor dynamic FP8 quantisation of a bf16 matrix.  The amax is collected in an array of LVX_AMAX_SLOTS fp32 bit patterns
 // (256 bytes, zero before the producers write): either by lvx_launch_fp8_amax, or by the kernel that produced x (attention,
-// the GELU epilogue of an FP8 linear), which saves the extra pass.  (The LayerNorm kernel does not: its one-row waves would
-// each need an atomic, which costs that memory-bound kernel more than the separate pass over its L2-resident output.)  lvx_launch_fp8_quant reduces the slots, writes
-// codes and scale and clears `zero_slots` (another slot array, may be NULL) for the next producer.
+// the GELU epilogue of an FP8 linear, the LayerNorm kernel with one atomic per workgroup), which saves the extra pass.
+// lvx_launch_fp8_quant reduces the slots, writes codes and scale and clears `zero_slots` (another slot array, may be NULL)
+// for the next producer.
 #define LVX_AMAX_SLOTS 64
 lvx_status_t lvx_launch_fp8_amax(const bf16_t *x, int64_t ld, int rows, int cols, uint32_t *amax_slots, hipStream_t stream);
 lvx_status_t lvx_launch_fp8_quant(const bf16_t *x, int64_t ld, int rows, int cols, uint8_t *q, int64_t ldq, const uint32_t *amax_slots,
