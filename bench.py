@@ -24,10 +24,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA, published
 PEAK_HBM_GBS = 8000.0
-# HBM-side bytes per attention launch at the full cache, from two rocprofv3 --pmc runs (FETCH_SIZE 618857 KiB, WRITE_SIZE 46803 KiB
+# HBM-side bytes per attention launch at the full cache, from two rocprofv3 --pmc runs (FETCH_SIZE 617994 KiB, WRITE_SIZE 46803 KiB
 # per dispatch; both counters read 1.000x the known size of a plain copy kernel in the same runs).  Summary and commands:
 # profiles/attention_gemm_14b_pmc_hbm_traffic.txt.  Only valid for the 24960-key, 4680-query, 40-head launch timed here.
-ATTN_TRAFFIC_BYTES = (618857 + 46803) * 1024
+ATTN_TRAFFIC_BYTES = (617994 + 46803) * 1024
 
 
 def attention_flops(n_q, n_k, H, D):
@@ -265,7 +265,7 @@ def main():
                    "ms_per_chunk_max": round(step_ms[-1], 3),
                    "stage_tflops": round(stage_fl / (seconds / args.steps) / 1e12, 2),
                    "stage_frac_of_bf16_peak": round(stage_fl / (seconds / args.steps) / 1e12 / PEAK_BF16_TFLOPS, 4)},
-        "roofline": {"kernel": "lvx_attention_kernel<128,8,2,2> (chunk-to-cache self-attention, configs[1] shape)", "bound": "mfma",
+        "roofline": {"kernel": "lvx_attention_kernel<128,8,2,2,true,false> (chunk-to-cache self-attention, configs[1] shape)", "bound": "mfma",
                      "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
                      "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE); algorithmic: %d" % (2 * d * (2 * n + 2 * n_k)),
