@@ -302,7 +302,9 @@ size_t lvx_workspace_bytes(const lvx_stage_t *stage /* host */, int32_t n_tokens
  * read them (the conditions C_i of Alg. 3 / Alg. 4 are one set per forward, so a stage prepares them for a group of layers in
  * one GEMM launch): K = RMSNorm(ctx Wc_k^T) * gc_k, V = ctx Wc_v^T, read back token-major as [n_layers][n_ctx][ld] bf16 each.
  * Exported for parity checks of that path; the blocks keep these tensors in the attention kernel's packed layout inside the
- * workspace.  n_layers <= 8; bf16 stages only; workspace >= lvx_workspace_bytes(stage, 1, n_ctx). */
+ * workspace.  n_layers is at most the stage's own group size (at most 8; the group is sized so that its tiles fill whole rounds
+ * of the chip: 5 layers for 544 context rows at d_model 5120) -- LVX_ERR_SHAPE otherwise; bf16 stages only;
+ * workspace >= lvx_workspace_bytes(stage, 1, n_ctx). */
 lvx_status_t lvx_context_kv(const lvx_stage_t *stage /* host */, int32_t layer0, int32_t n_layers, const void *dev_ctx, int32_t n_ctx,
                             void *dev_k_out, void *dev_v_out, int64_t ld, void *dev_workspace, size_t ws_bytes, lvx_stream_t stream);
 

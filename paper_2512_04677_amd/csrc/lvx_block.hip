@@ -61,6 +61,21 @@ constexpr int WS_PAD = 64;
 
 size_t round256(size_t b) { return (b + 255) / 256 * 256; }
 
+// Layers per context-projection launch: the group size (at most CTX_GROUP) whose 128 x 256 tiles fill whole rounds of the
+// chip's 256 compute units best, i.e. the fewest rounds per layer (544 context rows, d_model 5120: 5 layers = 1000 tiles = 3.9
+// rounds, where 8 layers = 1600 tiles would need 7 rounds for 6.25 rounds of work).
+int ctx_group_size(int n_layers, int n_ctx, size_t d) {
+    const int max_g = n_layers < CTX_GROUP ? n_layers : CTX_GROUP;
+    const long tiles_per_layer = (long)((n_ctx + 127) / 128) * 2 * (long)((d + 255) / 256);
+    int best = 1;
+    double best_cost = 1e30;
+    for (int g = 1; g <= max_g; ++g) {
+        const double cost = (double)((tiles_per_layer * g + 255) / 256) / g;
+        if (cost < best_cost - 1e-9 || (cost < best_cost + 1e-9 && g > best)) best = g, best_cost = cost;
+    }
+    return best;
+}
+
 ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     ws_layout_t w;
     const size_t d = (size_t)s->rope.n_heads * s->rope.head_dim;
@@ -80,7 +95,7 @@ ws_layout_t ws_layout(const lvx_stage_t *s, int n_tokens, int n_ctx) {
     w.q_sumsq = off;  // partial sums of squares of the cross-attention's query rows (bf16 stages), d / 64 per row
     if (s->blocks_fp8 == nullptr) off += round256((size_t)n_tokens * LVX_GEMM_SUMSQ_PARTS(d) * 4);
     // context K | V rows and their packed forms for a group of layers at once (bf16 stages; an FP8 stage uses one slot)
-    w.ctx_group = s->blocks_fp8 != nullptr ? 1 : (s->n_layers < CTX_GROUP ? s->n_layers : CTX_GROUP);
+    w.ctx_group = s->blocks_fp8 != nullptr ? 1 : ctx_group_size(s->n_layers, n_ctx, d);
     w.ctx_kv = off;  off += round256((size_t)w.ctx_group * n_ctx * w.ld_ckv * 2);
     w.ctx_k32 = off;  // un-rounded context keys before their RMSNorm (bf16 stages), row stride ld_u fp32 elements
     if (s->blocks_fp8 == nullptr) off += round256((size_t)w.ctx_group * n_ctx * w.ld_u * 4);
