@@ -23,6 +23,11 @@
 //     taken after the first tile); the final division by the row sum absorbs whatever reference was used.
 //   * workgroup -> (head, query tile) mapping keeps all query tiles of a head on one XCD (hardware deals consecutive
 //     workgroup ids round-robin over the 8 XCDs), so a head's K/V stream is fetched into one L2 only.
+//   * template switches: TP = 64-key tiles per pipeline phase (2 from 1024 visible keys on: half the barriers, pipeline fills and
+//     drains per key); PRE = the queries arrive multiplied by scale * log2(e) and the score accumulators start at minus the
+//     softmax reference, so a score leaves the MFMA as the exponent (one FMA per score less; used inside a block, where the
+//     RoPE kernel applies the factor before its one rounding); QN = the kernel itself applies the queries' RMSNorm, gain and
+//     that factor as it loads them (cross-attention inside a block: no norm-only pass over q).
 #include "lvx_internal.h"
 
 namespace {
