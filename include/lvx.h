@@ -216,7 +216,7 @@ lvx_status_t lvx_linear(const void *dev_a, int64_t lda, const void *dev_w, int64
  * store, W1 / W2 share the row stride ldw.  c1_is_f32 != 0: C1 is fp32 (ldc1 in fp32 elements), its accumulators are stored
  * un-rounded -- what a key projection wants, whose result is normalised and rotated before the one rounding to bf16 that the
  * cache holds.  C2 is always bf16.  The block's own launches are built on the same segment mechanism: q | k (fp32) | v of the
- * self-attention in one launch, the context's K (fp32) and V of eight layers in one launch.  K % 64 == 0, N1, N2 % 8 == 0. */
+ * self-attention in one launch, the context's K (fp32) and V of a group of layers in one launch.  K % 64 == 0, N1, N2 % 8 == 0. */
 lvx_status_t lvx_linear_dual(const void *dev_a, int64_t lda, const void *dev_w1, const void *dev_w2, int64_t ldw, void *dev_c1,
                              int64_t ldc1, int32_t c1_is_f32, void *dev_c2, int64_t ldc2, int32_t M, int32_t N1, int32_t N2, int32_t K,
                              lvx_stream_t stream);
