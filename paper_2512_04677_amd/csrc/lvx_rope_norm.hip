@@ -139,14 +139,14 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
 }
 
 // Input row is bf16 or fp32 (the residual stream is carried in fp32 inside a block / stage); output is bf16.
-template <int CPL, bool F32IN>
+template <int CPL, bool F32IN, bool AMAX>
 __global__ void __launch_bounds__(64 * ROWS_PER_WG)
     lvx_layernorm_modulate_kernel(const void *__restrict__ x_in, int64_t ldx, const float *__restrict__ shift,
                                   const float *__restrict__ scale, float eps, int n_tokens, int d, bf16_t *__restrict__ u_out,
                                   int64_t ldu, uint32_t *__restrict__ amax_slots) {
     const int lane = threadIdx.x & 63;
     const int token = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
-    // amax_slots != NULL: the output feeds an FP8 linear, whose per-tensor scale needs max |u| over the whole tensor: every
+    // AMAX: the output feeds an FP8 linear, whose per-tensor scale needs max |u| over the whole tensor: every
     // workgroup adds the largest magnitude among the bf16 values it stores (one atomic per workgroup, spread over the slots)
     __shared__ uint32_t wg_amax[ROWS_PER_WG];
     uint32_t amax_b = 0;
@@ -208,7 +208,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
                     const float a = (x[j][2 * e] - mean) * rinv * (1.f + sc[2 * e]) + sh[2 * e];
                     const float b = (x[j][2 * e + 1] - mean) * rinv * (1.f + sc[2 * e + 1]) + sh[2 * e + 1];
                     y[e] = pack_bf16x2(a, b);
-                    if (amax_slots != nullptr) {
+                    if (AMAX) {
                         const uint32_t lo = y[e] & 0x7fffu, hi = (y[e] >> 16) & 0x7fffu;
                         amax_b = amax_b > lo ? amax_b : lo;
                         amax_b = amax_b > hi ? amax_b : hi;
@@ -218,7 +218,7 @@ __global__ void __launch_bounds__(64 * ROWS_PER_WG)
             }
         }
     }
-    if (amax_slots != nullptr) {  // uniform over the grid: every wave of the workgroup gets here
+    if (AMAX) {  // every wave of the workgroup gets here
 #pragma unroll
         for (int s = 32; s >= 1; s >>= 1) {
             const uint32_t o = (uint32_t)__shfl_xor((int)amax_b, s);
@@ -413,9 +413,15 @@ lvx_status_t lvx_launch_layernorm(const void *x, int x_is_f32, int64_t ldx, cons
     if (n_tokens == 0) return LVX_OK;
     const dim3 grid((n_tokens + ROWS_PER_WG - 1) / ROWS_PER_WG), block(64 * ROWS_PER_WG);
     const int cpl = (d / 8 + 63) / 64;
-#define LVX_LN_LAUNCH(CPL, F32)                                                                                                  \
-    hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, u, ldu, \
-                       amax_slots)
+#define LVX_LN_LAUNCH(CPL, F32)                                                                                                      \
+    do {                                                                                                                             \
+        if (amax_slots != nullptr)                                                                                                   \
+            hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32, true>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, \
+                               u, ldu, amax_slots);                                                                                  \
+        else                                                                                                                         \
+            hipLaunchKernelGGL((lvx_layernorm_modulate_kernel<CPL, F32, false>), grid, block, 0, stream, x, ldx, shift, scale, eps, n_tokens, d, \
+                               u, ldu, amax_slots);                                                                                  \
+    } while (0)
     if (x_is_f32) {
         if (cpl <= 2)
             LVX_LN_LAUNCH(2, true);
