@@ -167,7 +167,7 @@ def test_attention_peaked_logits(lvx):
     stream_attention(lvx, "tiny", 3, scale_mult=0.01)     # near-uniform softmax
 
 
-@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("seed", range(12))
 def test_attention_random_shapes(lvx, seed):
     """Seeded random cache geometries: 1..3 heads of 64 or 128, frames of 1..90 tokens, 1..3 frames per chunk, windows of 1..3
     chunks, with and without a sink segment, over warm-up and eviction.  Covers single-key and single-query cases, query
@@ -180,6 +180,9 @@ def test_attention_random_shapes(lvx, seed):
         p.update(frame_h=1, frame_w=1, chunk_frames=1, sink_frames=0, window=1)   # one query, one key at step 0
     if seed == 1:
         p.update(frame_h=8, frame_w=8, chunk_frames=1, sink_frames=1, window=2)   # everything a multiple of the 64-key tile
+    if seed >= 8:   # larger frames, head_dim 128: 1024 and more visible keys (two key tiles per pipeline phase), ragged everywhere
+        p.update(head_dim=128, frame_h=int(r.integers(9, 15)), frame_w=int(r.integers(11, 17)), chunk_frames=int(r.integers(2, 4)),
+                 window=int(r.integers(2, 5)), sink_frames=int(r.integers(0, 3)))
     d, sink_n, chunk_n = dims(p)
     H, D, W = p["n_heads"], p["head_dim"], p["window"]
     scale = 1.0 / math.sqrt(D)
