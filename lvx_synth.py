@@ -20,6 +20,9 @@ PRESETS = {
                  rope_axes=(24, 20, 20), ffn=256, n_ctx=24),
     "small": dict(n_heads=4, head_dim=128, frame_h=5, frame_w=7, chunk_frames=3, window=4, sink_frames=1,
                   rope_axes=(44, 42, 42), ffn=1280, n_ctx=40),
+    # 130-token frames: 520 .. 1300 visible keys, i.e. both sides of the attention kernel's switch to two key tiles per phase
+    "medium": dict(n_heads=4, head_dim=128, frame_h=10, frame_w=13, chunk_frames=3, window=2, sink_frames=1,
+                   rope_axes=(44, 42, 42), ffn=1024, n_ctx=72),
     "attn14b": dict(n_heads=40, head_dim=128, frame_h=30, frame_w=52, chunk_frames=3, window=4, sink_frames=1,
                     rope_axes=(44, 42, 42), ffn=13824, n_ctx=544),
 }

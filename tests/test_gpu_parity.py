@@ -508,7 +508,7 @@ def stage_setup(lvx, preset, n_layers, tag, n_caches=1):
     return p, stage, (caches[0] if n_caches == 1 else caches), cfg, models, ws, [S.weights_to_f64(w) for w in layers]
 
 
-@pytest.mark.parametrize("preset", ["tiny", "small"])
+@pytest.mark.parametrize("preset", ["tiny", "small", "medium"])
 def test_dit_block_streaming(lvx, preset):
     """One block over warm-up and eviction.  lvx_dit_block_f32 (fp32 residual stream in and out) is gated at the stated numbers;
     lvx_dit_block (bf16 in and out) must return exactly the bf16 narrowing of that result, and is also compared with the oracle
