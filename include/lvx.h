@@ -193,6 +193,12 @@ lvx_status_t lvx_kvcache_gather_sink_source(const lvx_kvcache_t *cache, int32_t 
  * ------------------------------------------------------------------------------------------------ */
 lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *cache, int32_t layer, const void *dev_q, int64_t ld_q,
                                  int32_t n_q, float scale, void *dev_out, int64_t ld_out, lvx_stream_t stream);
+/* The same for queries that already carry the softmax scale: dev_q holds q * (scale * log2(e)), folded in before q was rounded
+ * to bf16 (what the DiT block's RMSNorm + RoPE kernel emits), so that softmax_m(scale <q,K>) = 2^(<q',K>) / sum.  The kernel
+ * then starts its score accumulators at minus the softmax reference and the score leaves the matrix core as the exponent.
+ * Folding the factor into an ALREADY rounded q would round it a second time; for that case use lvx_chunk_attention. */
+lvx_status_t lvx_chunk_attention_prescaled(const lvx_kvcache_t *cache, int32_t layer, const void *dev_q_scaled, int64_t ld_q,
+                                           int32_t n_q, void *dev_out, int64_t ld_out, lvx_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Building blocks of the DiT block, exported for unit parity tests.

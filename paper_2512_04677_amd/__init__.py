@@ -82,6 +82,7 @@ SIGNATURES = {
     "lvx_rope3d": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
     "lvx_rope3d_f32in": (C.c_int, [C.POINTER(RopeDesc), _vp, _vp, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i64, _vp]),
     "lvx_chunk_attention": (C.c_int, [_vp, _i32, _vp, _i64, _i32, _f32, _vp, _i64, _vp]),
+    "lvx_chunk_attention_prescaled": (C.c_int, [_vp, _i32, _vp, _i64, _i32, _vp, _i64, _vp]),
     "lvx_linear": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i32, _i32, _i32, C.c_int, _vp, _i64, _vp, _vp]),
     "lvx_linear_dual": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _i32, _i32, _i32, _vp]),
     "lvx_fp8_quantize": (C.c_int, [_vp, _i64, _i32, _i32, _vp, _i64, _vp, _vp, _vp]),
@@ -268,6 +269,11 @@ def lvx_rope3d_f32in(desc, q_in, k_in, g_q, g_k, n_tokens, t0, q_out, k_out, ld_
 def lvx_chunk_attention(cache, layer, q, scale, out, n_q=None):
     _check(load().lvx_chunk_attention(cache.handle, layer, _ptr(q), q.stride(0), q.shape[0] if n_q is None else n_q,
                                       scale, _ptr(out), out.stride(0), _stream()))
+
+
+def lvx_chunk_attention_prescaled(cache, layer, q_scaled, out, n_q=None):
+    _check(load().lvx_chunk_attention_prescaled(cache.handle, layer, _ptr(q_scaled), q_scaled.stride(0),
+                                                q_scaled.shape[0] if n_q is None else n_q, _ptr(out), out.stride(0), _stream()))
 
 
 def lvx_linear(a, w, c, epi=EPI_STORE, resid=None, gate=None, M=None):

@@ -486,8 +486,8 @@ lvx_status_t lvx_launch_attention(const bf16_t *q, int64_t ld_q, int n_q, int H,
     return lvx_fail(LVX_ERR_UNSUPPORTED, "head_dim %d not supported (64 or 128)", D);
 }
 
-extern "C" lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *c, int32_t layer, const void *dev_q, int64_t ld_q, int32_t n_q,
-                                            float scale, void *dev_out, int64_t ld_out, lvx_stream_t stream) {
+static lvx_status_t chunk_attention_entry(const lvx_kvcache_t *c, int32_t layer, const void *dev_q, int64_t ld_q, int32_t n_q, float scale,
+                                          void *dev_out, int64_t ld_out, lvx_stream_t stream, bool q_prescaled) {
     LVX_REQUIRE(c != nullptr, LVX_ERR_INVALID_ARG, "cache handle is NULL");
     LVX_REQUIRE(layer >= 0 && layer < c->desc.n_layers, LVX_ERR_INVALID_ARG, "layer %d out of range [0,%d)", layer, c->desc.n_layers);
     LVX_REQUIRE(dev_q != nullptr && dev_out != nullptr, LVX_ERR_INVALID_ARG, "q or out is NULL");
@@ -502,5 +502,15 @@ extern "C" lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *c, int32_t laye
     LVX_REQUIRE(c->sink_t[layer] != LVX_SINK_STALE, LVX_ERR_STATE,
                 "layer %d: the sink was reset and its keys are not rotated yet (lvx_sink_rope_update)", layer);
     return lvx_launch_attention((const bf16_t *)dev_q, ld_q, n_q, c->desc.n_heads, c->desc.head_dim, lvx_cache_k(c, layer),
-                                lvx_cache_vt(c, layer), c->cap_keys, s.key_count, scale, (bf16_t *)dev_out, ld_out, (hipStream_t)stream);
+                                lvx_cache_vt(c, layer), c->cap_keys, s.key_count, scale, (bf16_t *)dev_out, ld_out, (hipStream_t)stream, nullptr, q_prescaled);
+}
+
+extern "C" lvx_status_t lvx_chunk_attention(const lvx_kvcache_t *c, int32_t layer, const void *dev_q, int64_t ld_q, int32_t n_q,
+                                            float scale, void *dev_out, int64_t ld_out, lvx_stream_t stream) {
+    return chunk_attention_entry(c, layer, dev_q, ld_q, n_q, scale, dev_out, ld_out, stream, false);
+}
+
+extern "C" lvx_status_t lvx_chunk_attention_prescaled(const lvx_kvcache_t *c, int32_t layer, const void *dev_q_scaled, int64_t ld_q,
+                                                      int32_t n_q, void *dev_out, int64_t ld_out, lvx_stream_t stream) {
+    return chunk_attention_entry(c, layer, dev_q_scaled, ld_q, n_q, 1.0f, dev_out, ld_out, stream, true);
 }

@@ -66,6 +66,7 @@ int main() {
     EXPECT(lvx_kvcache_destroy(nullptr) == LVX_ERR_INVALID_ARG);
     EXPECT(lvx_chunk_append_evict(nullptr, 0, p, p, 5120, 0, nullptr, nullptr) == LVX_ERR_INVALID_ARG);
     EXPECT(lvx_chunk_attention(nullptr, 0, p, 5120, 10, 1.0f, p, 5120, nullptr) == LVX_ERR_INVALID_ARG);
+    EXPECT(lvx_chunk_attention_prescaled(nullptr, 0, p, 5120, 10, p, 5120, nullptr) == LVX_ERR_INVALID_ARG);
 
     EXPECT(lvx_linear(p, 100, p, 100, p, 64, 4, 64, 100, LVX_EPI_STORE, nullptr, 0, nullptr, nullptr) == LVX_ERR_SHAPE);
     EXPECT(lvx_linear(p, 128, p, 128, p, 64, 4, 60, 128, LVX_EPI_STORE, nullptr, 0, nullptr, nullptr) == LVX_ERR_SHAPE);

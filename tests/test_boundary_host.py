@@ -99,6 +99,7 @@ def test_error_paths_without_a_device():
     assert lib.lvx_kvcache_destroy(None) == 1
     assert lib.lvx_chunk_append_evict(None, 0, C.c_void_p(4096), C.c_void_p(4096), 5120, 0, None, None) == 1
     assert lib.lvx_chunk_attention(None, 0, C.c_void_p(4096), 5120, 10, 1.0, C.c_void_p(4096), 5120, None) == 1
+    assert lib.lvx_chunk_attention_prescaled(None, 0, C.c_void_p(4096), 5120, 10, C.c_void_p(4096), 5120, None) == 1
     # linear: shape checks come before any launch
     p = C.c_void_p(4096)
     assert lib.lvx_linear(p, 100, p, 100, p, 64, 4, 64, 100, 0, None, 0, None, None) == 2      # K % 64

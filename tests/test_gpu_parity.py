@@ -23,6 +23,7 @@ from oracle import lvx_oracle as O
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+LOG2E = 1.4426950408889634
 MAX_ABS, MEAN_ABS = 2e-2, 2e-3
 # Narrowing a fp32 result to bf16 (round to nearest even) costs mean-abs 1.12e-3 of the RMS for N(0, sigma) data (measured on
 # the oracle's own outputs, CPU test test_bf16_narrowing_error_of_unit_normal_data): (1.12 / 2)^2 = 0.31 of a link.
@@ -125,7 +126,7 @@ def test_ring_append_evict_bit_exact(lvx, preset):
 
 
 # ------------------------------------------------------------------------------------------------ attention
-def stream_attention(lvx, preset, n_steps, scale_mult=1.0, std=1.0):
+def stream_attention(lvx, preset, n_steps, scale_mult=1.0, std=1.0, prescaled=False):
     p = S.PRESETS[preset]
     d, sink_n, chunk_n = dims(p)
     H, D, W = p["n_heads"], p["head_dim"], p["window"]
@@ -142,11 +143,17 @@ def stream_attention(lvx, preset, n_steps, scale_mult=1.0, std=1.0):
         v = S.randn_bf16((chunk_n, d), S.seed_of(preset, "a_v", i), device=DEV)
         out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
         lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
-        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        if prescaled:
+            # the queries carry scale * log2(e), folded in before their rounding to bf16: softmax(scale <q,K>) = 2^<q',K> / sum,
+            # so the oracle takes the rounded q' with the scale ln 2
+            q = (q.float() * (scale * LOG2E)).to(torch.bfloat16)
+            lvx.lvx_chunk_attention_prescaled(cache, 0, q, out)
+        else:
+            lvx.lvx_chunk_attention(cache, 0, q, scale, out)
         torch.cuda.synchronize()
         ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
-                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
-        assert_close(out, ref.reshape(chunk_n, d), "%s attention step %d (scale x%g)" % (preset, i, scale_mult))
+                                     S.to_f64(v).reshape(chunk_n, H, D), math.log(2.0) if prescaled else scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "%s attention step %d (scale x%g%s)" % (preset, i, scale_mult, ", pre-scaled q" if prescaled else ""))
     cache.close()
 
 
@@ -159,6 +166,15 @@ def test_attention_config1_tiny(lvx):
 def test_attention_small_streaming_warmup_and_eviction(lvx):
     """head_dim 128, chunk 105 tokens (not a multiple of 8): key counts 140..560, eviction from step 5."""
     stream_attention(lvx, "small", 8)
+
+
+@pytest.mark.parametrize("preset", ["tiny", "small", "medium"])
+def test_attention_prescaled_queries(lvx, preset):
+    """lvx_chunk_attention_prescaled: queries that already carry scale * log2(e) (the form the block's RoPE kernel emits), over
+    warm-up and eviction; head_dim 64 and 128, and (medium) key counts on both sides of the two-tile switch.  Also with logit
+    std ~8, where the softmax reference moves."""
+    stream_attention(lvx, preset, S.PRESETS[preset]["window"] + 3, prescaled=True)
+    stream_attention(lvx, preset, 3, scale_mult=8.0, prescaled=True)
 
 
 def test_attention_peaked_logits(lvx):
@@ -213,8 +229,9 @@ def test_attention_random_shapes(lvx, seed):
 LONG_SINK = dict(n_heads=2, head_dim=128, frame_h=5, frame_w=7, chunk_frames=3, window=2, sink_frames=32)
 
 
+@pytest.mark.parametrize("prescaled", [False, True])
 @pytest.mark.parametrize("geometry", ["small", "long_sink"])
-def test_attention_growing_logits_rebase(lvx, geometry):
+def test_attention_growing_logits_rebase(lvx, geometry, prescaled):
     """Scores that outgrow the first key tile's maximum by 2^49, 2^98 and 2^196 (and drop below it by as much): the kernel keeps
     the first tile's row maximum as its softmax reference and only re-bases when a tile's sum of exponentials passes 2^64 or
     overflows; both the finite and the overflowing re-base, in a middle tile and in the ragged last tile, must still give the
@@ -249,12 +266,16 @@ def test_attention_growing_logits_rebase(lvx, geometry):
         v = S.randn_bf16((chunk_n, d), 38 + i, device=DEV)
         out = torch.empty((chunk_n, d), dtype=torch.bfloat16, device=DEV)
         lvx.lvx_chunk_append_evict(cache, 0, k, v, i)
-        lvx.lvx_chunk_attention(cache, 0, q, scale, out)
+        if prescaled:   # the pre-scaled form of the kernel keeps the reference in the score accumulators' start value
+            q = (q.float() * (scale * LOG2E)).to(torch.bfloat16)
+            lvx.lvx_chunk_attention_prescaled(cache, 0, q, out)
+        else:
+            lvx.lvx_chunk_attention(cache, 0, q, scale, out)
         torch.cuda.synchronize()
         assert bool(torch.isfinite(out.float()).all())
         ref = O.chunk_attention_step(model, S.to_f64(q).reshape(chunk_n, H, D), S.to_f64(k).reshape(chunk_n, H, D),
-                                     S.to_f64(v).reshape(chunk_n, H, D), scale, i)
-        assert_close(out, ref.reshape(chunk_n, d), "growing logits, %s" % order)
+                                     S.to_f64(v).reshape(chunk_n, H, D), math.log(2.0) if prescaled else scale, i)
+        assert_close(out, ref.reshape(chunk_n, d), "growing logits, %s%s" % (order, ", pre-scaled q" if prescaled else ""))
     cache.close()
 
 
